@@ -1,0 +1,182 @@
+/*
+ * bc.h - C ABI of the MI355X (gfx950) decode / compress / masked-prefill path of
+ * Breadcrumbs Reasoning (arXiv 2510.13797).
+ *
+ * Problem statement (paper, Alg. 1 and Sec. 3.1): while a model generates, every c
+ * generated tokens a beacon token is encoded; the beacon's K/V entry is kept and the
+ * entries of the c tokens before it are dropped.  Per sequence the cache therefore
+ * holds  [ prompt | one beacon per finished window | current window (<= c) ]  (Fig. 1).
+ * Attention itself is the standard softmax attention (Sec. 2) over whatever is
+ * resident.  Training does not evict; it masks (Fig. 2, Sec. 3.2).
+ *
+ * General conventions
+ *  - Every pointer is a DEVICE pointer owned by the caller unless the argument is
+ *    documented as "host".  The library allocates no device memory and keeps no state
+ *    between calls except the tuning override of bc_set_decode_tuning().
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Every
+ *    call except bc_tables_to_host() only enqueues work on that stream and returns.
+ *  - Return value: host-detectable errors only (bad argument, unsupported shape,
+ *    workspace too small, launch failure).  Violations only the device can see
+ *    (window already full, slab full, empty cache) set bits in *cache->err (sticky,
+ *    never cleared by the library) and leave the offending sequence untouched.
+ *  - `active` is an optional [B] byte mask (NULL = all active).  Inactive sequences
+ *    are never read or written; their output rows are left as they were.
+ *  - Step numbering: decode step t (t = 1, 2, ...) appends the K/V of the t-th generated
+ *    token, then attends; compression is due after step t when t mod c == 0
+ *    (iteration i = t of Alg. 1, whose x_i has been sampled but not yet encoded, so the
+ *    window holds exactly c entries).
+ *
+ * Cache layout in HBM
+ *  Sequence s owns cap[s] rows per KV head.  With E = Hkv * d elements per entry, its
+ *  part of a slab starts at element base[s] * E and is head-major:
+ *      element(s, kvh, j, x) = base[s]*E + (kvh*cap[s] + j)*d + x,   0 <= j < cap[s]
+ *  so the rows one (sequence, KV head) pair streams through are contiguous.  Rows
+ *  [0, P) are the prompt, [P, P+nb) the beacons, [P+nb, P+nb+w) the window; rows at and
+ *  beyond L = P + nb + w are unspecified (stale data may remain after an eviction).
+ *  Slabs and base[s]*E*elem_size must be 16-byte aligned.
+ */
+#ifndef BC_H
+#define BC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  BC_OK = 0,
+  BC_ERR_ARG = -1,        /* null / misaligned pointer, bad flag                 */
+  BC_ERR_SHAPE = -2,      /* unsupported B, Hq, Hkv, d or dtype                   */
+  BC_ERR_CAPACITY = -3,   /* (status string for the device error bit)            */
+  BC_ERR_STATE = -4,      /* (status string for the device error bit)            */
+  BC_ERR_WORKSPACE = -5,  /* workspace missing or smaller than required          */
+  BC_ERR_HIP = -6         /* a HIP call or kernel launch failed                  */
+} bc_status;
+
+typedef enum { BC_F32 = 0, BC_BF16 = 1 } bc_dtype;
+
+/* bits of *cache->err */
+#define BC_ERRBIT_STATE 1     /* operation not allowed in the sequence's state   */
+#define BC_ERRBIT_CAPACITY 2  /* the sequence's slab is full                     */
+
+/* kinds of row bc_append_kv() appends */
+#define BC_ROW_TOKEN 0
+#define BC_ROW_BEACON 1
+
+typedef struct {
+  int32_t B;         /* sequences                                                 */
+  int32_t Hq;        /* query heads                                               */
+  int32_t Hkv;       /* KV heads; Hq % Hkv == 0, group g = Hq/Hkv <= 8            */
+  int32_t d;         /* head dim: 64 or 128                                       */
+  int32_t kv_dtype;  /* bc_dtype of q, k, v and the slabs; outputs are fp32       */
+  float scale;       /* softmax scale; the paper is silent, callers pass 1/sqrt(d) */
+} bc_shape;
+
+typedef struct {
+  void *k_slab, *v_slab; /* sum_s cap[s]*Hkv*d elements each                      */
+  const int64_t *base;   /* [B] first entry of sequence s (in entries of Hkv*d)   */
+  const int32_t *cap;    /* [B] rows per KV head                                  */
+  const int32_t *P;      /* [B] prompt length                                     */
+  const int32_t *c;      /* [B] compression ratio; <= 0: never compress           */
+  int32_t *nb;           /* [B] beacons so far           (updated by the library) */
+  int32_t *w;            /* [B] rows after the beacons   (updated by the library) */
+  int32_t *err;          /* [1] sticky error bits                                 */
+  int32_t max_cap;       /* HOST value: max_s cap[s]; sizes grids and workspace   */
+} bc_cache;
+
+const char *bc_status_str(int32_t status);
+int32_t bc_version(void);
+
+/* Fill a freshly allocated cache from prompt K/V (Alg. 1, "Initialize: encode the
+ * prompt").  k_prompt / v_prompt: [total_rows, Hkv, d], token-major, sequences
+ * concatenated; prompt_offsets: device [B+1] int64, row of each sequence's first
+ * token.  total_rows is the host copy of prompt_offsets[B].  Sets nb = w = 0.  A
+ * sequence whose P[s] differs from its offset span, or exceeds cap[s], sets the
+ * state / capacity bit and is left unfilled. */
+int32_t bc_cache_init(const bc_shape *shape, const bc_cache *cache, const void *k_prompt,
+                      const void *v_prompt, const int64_t *prompt_offsets,
+                      int64_t total_rows, void *stream);
+
+/* Append one row per active sequence (Alg. 1: "KV is updated internally" for a token;
+ * "encode b" for a beacon).  k, v: [B, Hkv, d].
+ *  kind = BC_ROW_TOKEN : row goes to slot L; w += 1.  Needs w < c when c > 0 (else the
+ *                        state bit) and L < cap (else the capacity bit).
+ *  kind = BC_ROW_BEACON: acts only on sequences with c > 0 and w == c (others are
+ *                        skipped silently, so one call serves a batch with
+ *                        per-sequence c); the beacon joins at the tail, w = c + 1,
+ *                        to be attended by its own query and then compacted by
+ *                        bc_compress_evict(beacon_k = NULL). */
+int32_t bc_append_kv(const bc_shape *shape, const bc_cache *cache, const void *k,
+                     const void *v, const uint8_t *active, int32_t kind, void *stream);
+
+/* Bytes of workspace bc_decode_attn() needs for this shape and max_cap. */
+size_t bc_decode_workspace_bytes(const bc_shape *shape, int32_t max_cap);
+
+/* Zero the split counters at the head of a workspace.  Call once after allocating it
+ * (a workspace allocated zero-filled needs no call); bc_decode_attn() leaves the
+ * counters at zero when it finishes.  Enqueues a fill kernel, no memset node. */
+int32_t bc_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
+
+/* Single-token grouped-query attention over the resident entries (Sec. 2, Sec. 3.1:
+ * generation proceeds as in a vanilla Transformer over what is in the cache):
+ *   out[s,h,:] = sum_j softmax_j(scale * q[s,h,:] . K_j[kvh,:]) V_j[kvh,:],
+ *   j over all L_s = P+nb+w rows, kvh = floor(h / (Hq/Hkv)).
+ * q: [B, Hq, d] in kv_dtype; out: [B, Hq, d] fp32 (fp32 accumulation throughout).
+ * A sequence with L_s == 0 sets the state bit and its output is left untouched.
+ * The result is deterministic: partial results are combined in a fixed order.
+ * Calls sharing one workspace must not overlap in time. */
+int32_t bc_decode_attn(const bc_shape *shape, const bc_cache *cache, const void *q,
+                       float *out, const uint8_t *active, void *workspace,
+                       size_t workspace_bytes, void *stream);
+
+/* Beacon append + window eviction + in-place compaction (Alg. 1, the two eviction
+ * lines: drop the c entries before the beacon, keep the beacon).
+ *  beacon_k/v = [B, Hkv, d]: the beacon row is written to slot P+nb (the first window
+ *      slot); acts on active sequences with c > 0 and w == c, or 1 <= w <= c when
+ *      require_full_window == 0 (an extension; the paper never compresses a partial
+ *      window).  A sequence with w == c+1 (a beacon already at the tail) sets the state bit.
+ *  beacon_k = beacon_v = NULL: the beacon is already the tail entry (appended with
+ *      BC_ROW_BEACON); acts on sequences with w == c+1: row P+nb+c moves to P+nb.
+ *      require_full_window must be 1.
+ *  Afterwards nb += 1, w = 0.  Sequences that are not due are skipped silently. */
+int32_t bc_compress_evict(const bc_shape *shape, const bc_cache *cache, const void *beacon_k,
+                          const void *beacon_v, const uint8_t *active,
+                          int32_t require_full_window, void *stream);
+
+/* One decode step in two launches: append the token rows, attend, then evict where due
+ * (supplied-beacon form).  Same semantics as bc_append_kv(TOKEN) + bc_decode_attn +
+ * bc_compress_evict(beacon_k, beacon_v, require_full_window = 1) in that order.
+ * beacon_k/v may be NULL: then no eviction is attempted. */
+int32_t bc_decode_step(const bc_shape *shape, const bc_cache *cache, const void *k,
+                       const void *v, const void *q, float *out, const void *beacon_k,
+                       const void *beacon_v, const uint8_t *active, void *workspace,
+                       size_t workspace_bytes, void *stream);
+
+/* Training-time forward (Fig. 2, Sec. 3.2): attention over beacon-interleaved
+ * trajectories where eviction is simulated by the mask.  Rows of trajectory b are
+ * [row_offsets[b], row_offsets[b+1]); the first P[b] rows are the prompt (plain causal
+ * mask, no beacons), then c[b] response tokens, one beacon row, c[b] tokens, one beacon
+ * row, ...  A response row sees the prompt, every earlier beacon, the earlier rows of its
+ * own window and itself.  c[b] <= 0: plain causal attention.
+ * q: [total_rows, Hq, d]; k, v: [total_rows, Hkv, d] (kv_dtype must be BC_BF16);
+ * out: [total_rows, Hq, d] fp32; lse (nullable): [total_rows, Hq] fp32, natural log of
+ * the softmax denominator.  row_offsets: device [B+1] int64; P, c: device [B] int32;
+ * max_rows: HOST value >= the longest trajectory (sizes the grid). */
+int32_t bc_prefill_attn(const bc_shape *shape, const void *q, const void *k, const void *v,
+                        const int64_t *row_offsets, const int32_t *P, const int32_t *c,
+                        int32_t max_rows, float *out, float *lse, void *stream);
+
+/* Copy nb[B], w[B] and err[1] to HOST arrays (any may be NULL) and wait for the stream. */
+int32_t bc_tables_to_host(const bc_shape *shape, const bc_cache *cache, int32_t *nb_host,
+                          int32_t *w_host, int32_t *err_host, void *stream);
+
+/* Tuning override for experiments: rows of one (sequence, KV head) stream handled by one
+ * workgroup of bc_decode_attn (0 = automatic), and kernel variant (0 = automatic). */
+void bc_set_decode_tuning(int32_t rows_per_workgroup, int32_t variant);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BC_H */

@@ -1,0 +1,88 @@
+// Shared device/host helpers for the gfx950 kernels (wave64 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/bc.h"
+
+namespace bc {
+
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+
+struct bf16_t { uint16_t bits; };   // storage tag for bf16 rows
+
+constexpr float kNegBig = -1.0e30f;            // finite stand-in for -inf in running maxima
+constexpr float kLog2e = 1.4426950408889634f;
+
+template <typename T> struct Elem;
+template <> struct Elem<float>  { static constexpr int size = 4; static constexpr int per16 = 4; };
+template <> struct Elem<bf16_t> { static constexpr int size = 2; static constexpr int per16 = 8; };
+
+// 16 bytes of a row -> floats
+__device__ __forceinline__ void unpack16(const uint4& r, float (&f)[4], float) {
+  f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y);
+  f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
+}
+__device__ __forceinline__ void unpack16(const uint4& r, float (&f)[8], bf16_t) {
+  f[0] = __uint_as_float(r.x << 16); f[1] = __uint_as_float(r.x & 0xffff0000u);
+  f[2] = __uint_as_float(r.y << 16); f[3] = __uint_as_float(r.y & 0xffff0000u);
+  f[4] = __uint_as_float(r.z << 16); f[5] = __uint_as_float(r.z & 0xffff0000u);
+  f[6] = __uint_as_float(r.w << 16); f[7] = __uint_as_float(r.w & 0xffff0000u);
+}
+
+// x + (x of another lane), lane chosen by a DPP control word (row = 16 lanes)
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float x) {
+  int y = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true);
+  return x + __int_as_float(y);
+}
+constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141; // lane i <-> 7-i inside each 8
+constexpr int kDppMirror = 0x140;     // lane i <-> 15-i inside each 16
+
+// Sum over groups of LPR consecutive lanes; every lane of a group gets the sum.
+// After the two quad steps all lanes of a quad agree, so the mirrors act as xor 4 / xor 8.
+template <int LPR>
+__device__ __forceinline__ float group_allreduce_sum(float x) {
+  static_assert(LPR == 8 || LPR == 16 || LPR == 32, "lanes per row");
+  x = dpp_add<kDppXor1>(x);
+  x = dpp_add<kDppXor2>(x);
+  x = dpp_add<kDppHalfMirror>(x);
+  if (LPR >= 16) x = dpp_add<kDppMirror>(x);
+  if (LPR >= 32) x += __shfl_xor(x, 16, 64);
+  return x;
+}
+
+inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline int32_t check_shape(const bc_shape* sh) {
+  if (!sh) return BC_ERR_ARG;
+  if (sh->B < 1 || sh->Hq < 1 || sh->Hkv < 1) return BC_ERR_SHAPE;
+  if (sh->Hq % sh->Hkv != 0 || sh->Hq / sh->Hkv > 8) return BC_ERR_SHAPE;
+  if (sh->d != 64 && sh->d != 128) return BC_ERR_SHAPE;
+  if (sh->kv_dtype != BC_F32 && sh->kv_dtype != BC_BF16) return BC_ERR_SHAPE;
+  return BC_OK;
+}
+
+inline int32_t check_cache(const bc_cache* c) {
+  if (!c || !c->k_slab || !c->v_slab || !c->base || !c->cap || !c->P || !c->c || !c->nb ||
+      !c->w || !c->err)
+    return BC_ERR_ARG;
+  if (!aligned16(c->k_slab) || !aligned16(c->v_slab)) return BC_ERR_ARG;
+  if (c->max_cap < 1) return BC_ERR_ARG;
+  return BC_OK;
+}
+
+inline int elem_size(int32_t dtype) { return dtype == BC_BF16 ? 2 : 4; }
+
+inline int32_t launch_status() {
+  return hipGetLastError() == hipSuccess ? BC_OK : BC_ERR_HIP;
+}
+
+}  // namespace bc

@@ -19,6 +19,7 @@ import numpy as np
 BASE_SEED = 20251013
 
 _STREAM_PROMPT, _STREAM_TOKEN, _STREAM_BEACON, _STREAM_SHAPE, _STREAM_PREFILL = range(5)
+_BLOCK = 128      # decode steps whose K/V are drawn together
 
 
 # ---------------------------------------------------------------------------
@@ -66,6 +67,7 @@ class Workload:
     peak_scale: float = 4.0
     seed: int = BASE_SEED
     extra: dict = field(default_factory=dict)
+    _blocks: dict = field(default_factory=dict, repr=False)
 
     @property
     def scale(self) -> float:
@@ -108,33 +110,45 @@ class Workload:
             k[j % self.peak_every == self.peak_every - 1] *= self.peak_scale
         return round_to_dtype(k, self.dtype), round_to_dtype(v, self.dtype)
 
+    def _kv_block(self, stream: int, blk: int):
+        """K/V of `_BLOCK` consecutive steps drawn at once (key: stream, block index)."""
+        key = (stream, blk)
+        hit = self._blocks.get(key)
+        if hit is None:
+            r = self._rng(stream, blk, 0)
+            k = r.standard_normal((_BLOCK, self.B, self.Hkv, self.d), dtype=np.float32)
+            v = r.standard_normal((_BLOCK, self.B, self.Hkv, self.d), dtype=np.float32)
+            hit = (round_to_dtype(k, self.dtype), round_to_dtype(v, self.dtype))
+            if len(self._blocks) >= 4:
+                self._blocks.pop(next(iter(self._blocks)))
+            self._blocks[key] = hit
+        return hit
+
     def step_kv(self, t: int):
         """(k, v) [B, Hkv, d]: K/V of the token encoded at decode step t (t >= 1)."""
-        r = self._rng(_STREAM_TOKEN, t, 0)
-        k = r.standard_normal((self.B, self.Hkv, self.d), dtype=np.float32)
-        v = r.standard_normal((self.B, self.Hkv, self.d), dtype=np.float32)
+        kb, vb = self._kv_block(_STREAM_TOKEN, t // _BLOCK)
+        k, v = kb[t % _BLOCK].copy(), vb[t % _BLOCK].copy()
         if self.peak_every:
-            k[self._peak_mask_tokens(t)] *= self.peak_scale
-        return round_to_dtype(k, self.dtype), round_to_dtype(v, self.dtype)
+            k[self._peak_mask_tokens(t)] *= self.peak_scale     # x4 keeps bf16 values exact
+        return k, v
 
     def step_q(self, t: int):
         """q [B, Hq, d] of decode step t."""
-        r = self._rng(_STREAM_TOKEN, t, 1)
+        r = self._rng(_STREAM_TOKEN, t, 1, 1)
         q = r.standard_normal((self.B, self.Hq, self.d), dtype=np.float32)
         return round_to_dtype(q, self.dtype)
 
     def beacon_kv(self, t: int):
         """(k, v) [B, Hkv, d] of the beacons encoded after decode step t."""
-        r = self._rng(_STREAM_BEACON, t, 0)
-        k = r.standard_normal((self.B, self.Hkv, self.d), dtype=np.float32)
-        v = r.standard_normal((self.B, self.Hkv, self.d), dtype=np.float32)
+        kb, vb = self._kv_block(_STREAM_BEACON, t // _BLOCK)
+        k, v = kb[t % _BLOCK].copy(), vb[t % _BLOCK].copy()
         if self.peak_every:
             k[self._peak_mask_beacons(t)] *= self.peak_scale
-        return round_to_dtype(k, self.dtype), round_to_dtype(v, self.dtype)
+        return k, v
 
     def beacon_q(self, t: int):
         """q [B, Hq, d] of the beacon token's own forward pass after step t."""
-        r = self._rng(_STREAM_BEACON, t, 1)
+        r = self._rng(_STREAM_BEACON, t, 1, 1)
         return round_to_dtype(r.standard_normal((self.B, self.Hq, self.d), dtype=np.float32), self.dtype)
 
 

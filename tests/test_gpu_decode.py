@@ -1,0 +1,281 @@
+"""GPU parity: bc_append_kv / bc_decode_attn / bc_compress_evict against the CPU oracle,
+through the C ABI, on the five-config shapes (decode side).  Tolerances: max-abs-error
+1e-5 for fp32 inputs, 2e-3 for bf16 inputs (fp32 accumulation); tables, error bits and
+resident slab rows bit-exact."""
+import numpy as np
+import pytest
+
+from oracle import attention as OA
+from oracle import residency as OR
+from oracle.cache import BatchCache, ERR_CAPACITY, ERR_STATE
+from paper_2510_13797_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-3}
+
+
+@pytest.fixture(scope="module")
+def dev():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return torch.device("cuda:0")
+
+
+def _bc():
+    from paper_2510_13797_amd import bc
+    bc.load()                       # fails loudly if libbc.so is missing
+    return bc
+
+
+def make(wl, dev, cap=None):
+    bc = _bc()
+    cap = wl.capacity() if cap is None else cap
+    rt = bc.Runtime(wl.B, wl.Hq, wl.Hkv, wl.d, wl.dtype, wl.scale, wl.P, wl.c, cap, dev)
+    pk, pv = zip(*[wl.prompt_kv(s) for s in range(wl.B)])
+    rt.cache_init(list(pk), list(pv))
+    oc = BatchCache(list(pk), list(pv), wl.c, cap)
+    return rt, oc
+
+
+def check_tables(rt, oc, t=None):
+    nb, w, err = rt.tables()
+    assert list(nb) == oc.nb, ("nb", t)
+    assert list(w) == oc.w, ("w", t)
+    assert err == oc.err, ("err", t, err, oc.err)
+    return nb, w
+
+
+def check_slabs(rt, oc, seqs=None, t=None):
+    nb, w, _ = rt.tables()
+    for s in (range(rt.B) if seqs is None else seqs):
+        K, V = rt.resident(s, int(nb[s]), int(w[s]))
+        Ko, Vo = oc.resident(s)
+        assert K.shape == Ko.shape, (s, t)
+        assert np.array_equal(K, Ko) and np.array_equal(V, Vo), ("slab", s, t)
+
+
+def check_attention(o, q, oc, wl, seqs=None, t=None):
+    worst = 0.0
+    for s in (range(wl.B) if seqs is None else seqs):
+        K, V = oc.resident(s)
+        ref = OA.decode_attention(q[s], K, V, wl.scale)
+        worst = max(worst, float(np.abs(o[s].astype(np.float64) - ref).max()))
+    assert worst <= TOL[wl.dtype], (t, worst)
+    return worst
+
+
+def rollout(wl, rt, oc, steps, attn_steps, slab_steps, table_every=1, tail_form=False,
+            use_step_call=False, seq_sample=None):
+    """Alg. 1 for `steps` decode steps; sequences whose generation is over stay resident."""
+    attn_steps, slab_steps = set(attn_steps), set(slab_steps)
+    worst = 0.0
+    for t in range(1, steps + 1):
+        active = (wl.G >= t).astype(np.uint8)
+        act = None if active.all() else active
+        k, v = wl.step_kv(t)
+        need_attn = t in attn_steps
+        q = wl.step_q(t) if (need_attn or use_step_call) else None
+        bk, bv = wl.beacon_kv(t)
+        if use_step_call:
+            o = rt.decode_step(k, v, q, bk, bv, active=act)
+            oc.append(k, v, active=act)
+            if need_attn:
+                worst = max(worst, check_attention(o.cpu().numpy(), q, oc, wl, seq_sample, t))
+            oc.compress_evict(bk, bv, active=act)
+        else:
+            rt.append_kv(k, v, active=act)
+            oc.append(k, v, active=act)
+            if need_attn:
+                o = rt.decode_attn(q, active=act).cpu().numpy()
+                seqs = [s for s in (range(wl.B) if seq_sample is None else seq_sample) if active[s]]
+                worst = max(worst, check_attention(o, q, oc, wl, seqs, t))
+            if tail_form:
+                rt.append_kv(bk, bv, active=act, kind=1)
+                oc.append(bk, bv, active=act, beacon=True)
+                if need_attn:       # the beacon's own query sees prompt, beacons, window, itself
+                    due = [s for s in range(wl.B) if active[s] and oc.c[s] > 0 and oc.w[s] == oc.c[s] + 1]
+                    if due:
+                        qb = wl.beacon_q(t)
+                        dm = np.zeros(wl.B, np.uint8)
+                        dm[due] = 1
+                        ob = rt.decode_attn(qb, active=dm).cpu().numpy()
+                        worst = max(worst, check_attention(ob, qb, oc, wl, due, t))
+                rt.compress_evict(active=act)
+                oc.compress_evict(active=act)
+            else:
+                rt.compress_evict(bk, bv, active=act)
+                oc.compress_evict(bk, bv, active=act)
+        if t % table_every == 0 or t in slab_steps or t == steps:
+            check_tables(rt, oc, t)
+        if t in slab_steps:
+            check_slabs(rt, oc, seq_sample, t)
+    return worst
+
+
+# ---------------------------------------------------------------------------
+def test_config1_tiny_every_step(dev):
+    wl = W.tiny()
+    rt, oc = make(wl, dev)
+    steps = range(1, 257)
+    worst = rollout(wl, rt, oc, 256, steps, steps)
+    nb, w, _ = rt.tables()
+    assert list(nb) == [16, 16] and list(w) == [0, 0]
+    for s in range(wl.B):       # invariant: L = P + floor(t/c) + (t mod c)
+        assert 32 + nb[s] + w[s] == OR.len_after_step(32, 16, 256)
+    print("tiny worst", worst)
+
+
+def test_config1_tail_form_with_beacon_query(dev):
+    wl = W.tiny(seed=11)
+    rt, oc = make(wl, dev)
+    rollout(wl, rt, oc, 80, range(1, 81), range(1, 81), tail_form=True)
+
+
+def test_config1_fused_step_call(dev):
+    wl = W.tiny(seed=12)
+    rt, oc = make(wl, dev)
+    rollout(wl, rt, oc, 64, range(1, 65), (16, 17, 64), use_step_call=True)
+
+
+@pytest.mark.parametrize("c", [16, 0])
+def test_config2_batch64_full_rollout(dev, c):
+    wl = W.batch64(c=c)
+    rt, oc = make(wl, dev)
+    rng = np.random.default_rng(5)
+    sample = sorted(set([1, 2, 15, 16, 17, 31, 32, 33, 255, 256, 257, 1000, 2047, 2048, 4095, 4096])
+                    | set(int(x) for x in rng.integers(1, 4097, size=48)))
+    seqs = [0, 1, 31, 63] + [int(x) for x in rng.integers(0, 64, size=4)]
+    worst = rollout(wl, rt, oc, 4096, sample, (16, 17, 1000, 4096), table_every=1, seq_sample=seqs)
+    nb, w, _ = rt.tables()
+    if c > 0:
+        assert int(nb[0]) == 256 and int(w[0]) == 0          # 256 + 256 + 0 = 512 rows resident
+    else:
+        assert int(nb[0]) == 0 and int(w[0]) == 4096
+    check_slabs(rt, oc, None, 4096)
+    # whole batch at the final state, fresh query
+    q = wl.step_q(5000)
+    o = rt.decode_attn(q).cpu().numpy()
+    worst = max(worst, check_attention(o, q, oc, wl, None, 4096))
+    print("batch64 c=%d worst %.3g" % (c, worst))
+
+
+def test_config3_ragged_snapshot(dev):
+    wl = W.ragged256()
+    T = wl.extra["T"]
+    rt, oc = make(wl, dev)
+    rollout(wl, rt, oc, T - 1, (), (), table_every=512)
+    # snapshot at attention time of step T
+    active = (wl.G >= T).astype(np.uint8)
+    k, v = wl.step_kv(T)
+    rt.append_kv(k, v, active=active)
+    oc.append(k, v, active=active)
+    nb, w = check_tables(rt, oc, T)
+    for s in range(wl.B):       # closed form of the residency process
+        t_s = min(T, int(wl.G[s]))
+        if wl.G[s] >= T:
+            assert (int(nb[s]), int(w[s])) == OR.tables_at_attention(int(wl.c[s]), t_s)
+        else:
+            assert (int(nb[s]), int(w[s])) == OR.tables_after_step(int(wl.c[s]), t_s)
+    check_slabs(rt, oc, None, T)
+    q = wl.step_q(T)
+    o = rt.decode_attn(q).cpu().numpy()          # all sequences, finished ones included
+    worst = check_attention(o, q, oc, wl, None, T)
+    print("ragged T=%d sumL=%d worst %.3g" % (T, sum(oc.L(s) for s in range(wl.B)), worst))
+
+
+def test_config4_long_peaked(dev):
+    wl = W.long_reasoning()
+    rt, oc = make(wl, dev)
+    rng = np.random.default_rng(9)
+    # steps whose window holds a x4 key: the 64th written row falls on a token
+    sample = sorted(set([1, 31, 32, 33, 63, 64, 65, 4096, 32767, 32768])
+                    | set(int(x) for x in rng.integers(1, 32769, size=20)))
+    seqs = [0, 7, 31]
+    worst = rollout(wl, rt, oc, 32768, sample, (32, 33, 32768), table_every=1024, seq_sample=seqs)
+    nb, w, _ = rt.tables()
+    assert int(nb[0]) == 1024 and int(w[0]) == 0
+    q = wl.step_q(40000)
+    o = rt.decode_attn(q).cpu().numpy()
+    worst = max(worst, check_attention(o, q, oc, wl, None, 32768))
+    print("long worst %.3g" % worst)
+
+
+# ---------------------------------------------------------------------------
+def test_error_bits_and_inactive_rows_untouched(dev):
+    import torch
+    wl = W.Workload("edge", 90, 3, 4, 2, 64, "bf16", np.array([2, 0, 3], np.int32),
+                    np.array([8, 8, 8], np.int32), np.array([2, 2, 0], np.int32))
+    cap = np.array([2 + 1 + 2, 3, 5], np.int32)
+    rt, oc = make(wl, dev, cap)
+    # sequence 1 is empty: attention over it is a state error and leaves the output alone
+    rt.out.fill_(123.0)
+    q = wl.step_q(1)
+    o = rt.decode_attn(q)
+    nb, w, err = rt.tables()
+    assert err == ERR_STATE
+    assert torch.all(o[1] == 123.0)
+    K, V = oc.resident(0)
+    assert np.abs(o[0].cpu().numpy() - OA.decode_attention(q[0], K, V, wl.scale)).max() <= 2e-3
+    rt.err.zero_()
+    # inactive sequences: tables, slabs and outputs untouched
+    k, v = wl.step_kv(1)
+    rt.append_kv(k, v, active=[1, 0, 1]); oc.append(k, v, active=[1, 0, 1])
+    rt.out.fill_(-7.0)
+    o = rt.decode_attn(wl.step_q(2), active=[0, 0, 1])
+    assert torch.all(o[0] == -7.0) and torch.all(o[1] == -7.0) and not torch.any(o[2] == -7.0)
+    check_tables(rt, oc)
+    # window full -> state bit; slab full -> capacity bit; sequence untouched both times
+    k, v = wl.step_kv(2)
+    rt.append_kv(k, v); oc.append(k, v)                 # seq0 w=2, seq1 w=1, seq2 w=2 (cap 5 reached)
+    rt.append_kv(k, v, active=[1, 0, 0]); oc.append(k, v, active=[1, 0, 0])
+    assert oc.err == ERR_STATE
+    rt.append_kv(k, v, active=[0, 0, 1]); oc.append(k, v, active=[0, 0, 1])
+    assert oc.err == ERR_STATE | ERR_CAPACITY
+    check_tables(rt, oc)
+    check_slabs(rt, oc)
+    # partial-window compression is an opt-in extension
+    bk, bv = wl.beacon_kv(2)
+    rt.compress_evict(bk, bv); oc.compress_evict(bk, bv)             # seq0 only
+    rt.compress_evict(bk, bv, require_full_window=False)
+    oc.compress_evict(bk, bv, require_full=False)                    # seq1 (w=1)
+    check_tables(rt, oc)
+    check_slabs(rt, oc, [0, 2])
+
+
+def test_host_side_argument_errors(dev):
+    bc = _bc()
+    wl = W.tiny()
+    rt, _ = make(wl, dev)
+    import ctypes as C
+    sh = bc.bc_shape(2, 4, 3, 64, 0, 0.125)            # Hq % Hkv != 0
+    assert bc.bc_decode_attn(sh, rt.cache, C.c_void_p(rt.out.data_ptr()), C.c_void_p(rt.out.data_ptr()),
+                             None, C.c_void_p(rt.ws.data_ptr()), rt.ws_bytes, None) == -2
+    assert bc.bc_decode_attn(rt.shape, rt.cache, None, C.c_void_p(rt.out.data_ptr()), None,
+                             C.c_void_p(rt.ws.data_ptr()), rt.ws_bytes, None) == -1
+    assert bc.bc_decode_attn(rt.shape, rt.cache, C.c_void_p(rt.out.data_ptr()),
+                             C.c_void_p(rt.out.data_ptr()), None, C.c_void_p(rt.ws.data_ptr()), 8,
+                             None) == -5
+    assert bc.bc_compress_evict(rt.shape, rt.cache, None, None, None, 0, None) == -1
+    assert "workspace" in bc.bc_status_str(-5)
+
+
+def test_deterministic_and_split_invariant(dev):
+    import torch
+    bc = _bc()
+    wl = W.batch64(c=0, G=1500, B=8)
+    rt, oc = make(wl, dev)
+    for t in range(1, 1201):
+        k, v = wl.step_kv(t)
+        rt.append_kv(k, v)
+    q = wl.step_q(7)
+    a = rt.decode_attn(q).clone()
+    b = rt.decode_attn(q).clone()
+    assert torch.equal(a, b)                               # fixed merge order
+    try:
+        bc.bc_set_decode_tuning(512, 0)
+        c = rt.decode_attn(q).clone()
+    finally:
+        bc.bc_set_decode_tuning(0, 0)
+    assert float((a - c).abs().max()) < 1e-5               # independent of the split factor
+    assert not torch.equal(a, torch.zeros_like(a))
