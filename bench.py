@@ -1,0 +1,259 @@
+#!/usr/bin/env python3
+"""Benchmark of the decode hot path on one MI355X.
+
+Workload (benchmark configs[1]): batch 64, 12 query / 2 KV heads, head_dim 128, bf16,
+prompt 256, 4096 generated tokens, c = 16.  One *step* is one pass of the hot path over one
+batch for one attention layer: append the token's K/V, decode attention over
+[prompt | beacons | window], beacon append + eviction on the sequences that are due.
+The model is represented by `--layers` independent cache instances visited round-robin
+(as the layers of a model are), so consecutive steps touch different memory and the caches
+(together larger than the 256 MB Infinity Cache) are read from HBM, not from cache.
+The timed region is the last `--steps` layer-steps of the rollout, the warm-up the ones
+before it; by default the two cover the whole 4096-token rollout.
+
+Prints ONE JSON line (see README): value = algorithmic KV bytes read by decode
+attention per second over the whole timed region (all kernels and launch gaps included).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def kv_bytes_per_step(wl, t):
+    """Algorithmic K+V bytes decode attention reads at token-step t: every resident row once."""
+    es = 2 if wl.dtype == "bf16" else 4
+    c = int(wl.c[0])
+    L = (wl.P + ((t - 1) // c + (t - 1) % c + 1 if c > 0 else t)).astype(np.int64)
+    return int(L.sum()) * wl.Hkv * wl.d * 2 * es
+
+
+def cpu_baseline(wl, budget_s=12.0):
+    """Oracle decode attention timed on the host cores, on a bounded sample of the workload:
+    repeated decode steps over the end-of-rollout cache state (all sequences, all heads)."""
+    import psutil
+    from oracle import attention as OA
+    rng = np.random.default_rng(1)
+    c = int(wl.c[0])
+    G = int(wl.G[0])
+    L = int(wl.P[0]) + (G // c + G % c if c > 0 else G)
+    K = [rng.standard_normal((L, wl.Hkv, wl.d)).astype(np.float32) for _ in range(wl.B)]
+    V = [rng.standard_normal((L, wl.Hkv, wl.d)).astype(np.float32) for _ in range(wl.B)]
+    proc = psutil.Process()
+    cpu0 = proc.cpu_times()
+    t0 = time.perf_counter()
+    steps = 0
+    while time.perf_counter() - t0 < budget_s:
+        q = rng.standard_normal((wl.B, wl.Hq, wl.d)).astype(np.float32)
+        for s in range(wl.B):
+            OA.decode_attention(q[s], K[s], V[s], wl.scale)
+        steps += 1
+    wall = time.perf_counter() - t0
+    cpu1 = proc.cpu_times()
+    cpu = (cpu1.user - cpu0.user) + (cpu1.system - cpu0.system)
+    nbytes = steps * wl.B * L * wl.Hkv * wl.d * 2 * 2
+    return {"value": nbytes / wall / 1e9, "unit": "GB/s", "cores": max(1, int(round(cpu / wall))),
+            "kind": "oracle", "steps_per_sec": steps / wall,
+            "sample": "%d decode steps at the end-of-rollout state (L=%d), all %d sequences x %d heads, "
+                      "fp64 NumPy oracle, %.1f s" % (steps, L, wl.B, wl.Hq, wall)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=-1)
+    ap.add_argument("--warmup", type=int, default=-1)
+    ap.add_argument("--layers", type=int, default=16, help="cache instances visited round-robin")
+    ap.add_argument("--c", type=int, default=16, help="compression ratio (0: uncompressed control)")
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--rows-per-wg", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (--gpus 1); multi-GPU sharding is a design "
+              "note in DESIGN.md, not an implemented path", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2510_13797_amd import bc, workloads
+    bc.load()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    if args.rows_per_wg:
+        bc.bc_set_decode_tuning(args.rows_per_wg, 0)
+
+    wl = workloads.batch64(c=args.c)
+    NL = args.layers
+    G = int(wl.G[0])
+    c = int(wl.c[0])
+    cyc_tokens = c if c > 0 else 16
+    cycle = cyc_tokens * NL                     # layer-steps per captured graph
+    total = G * NL
+    W = args.warmup if args.warmup >= 0 else cycle
+    K = args.steps if args.steps >= 0 else total - W
+    use_graph = not args.no_graph and K % cycle == 0 and W % cycle == 0
+    if (K + W) % NL or K + W > total:
+        print("bench.py: steps + warmup must be a multiple of --layers and at most %d" % total,
+              file=sys.stderr)
+        sys.exit(2)
+    t0 = G - (K + W) // NL                      # tokens already generated when the warm-up starts
+
+    # --- state: NL cache instances fast-forwarded to token t0, inputs resident in HBM ---------
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(workloads.BASE_SEED)
+    tdt = torch.bfloat16
+    layers = []
+    for _ in range(NL):
+        rt = bc.Runtime(wl.B, wl.Hq, wl.Hkv, wl.d, wl.dtype, wl.scale, wl.P, wl.c, wl.capacity(), dev)
+        rt.k_slab.copy_(torch.randn(rt.k_slab.shape, generator=gen, device=dev, dtype=torch.float32))
+        rt.v_slab.copy_(torch.randn(rt.v_slab.shape, generator=gen, device=dev, dtype=torch.float32))
+        if c > 0:
+            rt.set_tables(np.full(wl.B, t0 // c, np.int32), np.full(wl.B, t0 % c, np.int32))
+        else:
+            rt.set_tables(np.zeros(wl.B, np.int32), np.full(wl.B, t0, np.int32))
+        layers.append(rt)
+    n_pool = 64
+
+    def rnd(*shape):
+        return torch.randn(*shape, generator=gen, device=dev, dtype=torch.float32).to(tdt)
+
+    pool = [dict(k=rnd(wl.B, wl.Hkv, wl.d), v=rnd(wl.B, wl.Hkv, wl.d), q=rnd(wl.B, wl.Hq, wl.d),
+                 bk=rnd(wl.B, wl.Hkv, wl.d), bv=rnd(wl.B, wl.Hkv, wl.d)) for _ in range(n_pool)]
+
+    def layer_step(i):
+        """i-th layer-step of the rollout (counted from the warm-up start)."""
+        rt = layers[i % NL]
+        x = pool[i % n_pool]
+        rt.decode_step(x["k"], x["v"], x["q"], x["bk"] if c > 0 else None, x["bv"] if c > 0 else None)
+
+    stream = torch.cuda.Stream()
+    graph = None
+    with torch.cuda.stream(stream):
+        if use_graph:
+            # the first cycle of the warm-up runs eagerly, the rest of it and all timed steps as
+            # replays of one captured cycle (window position and pool index repeat every cycle)
+            done = 0
+            if W > 0:
+                for i in range(cycle):
+                    layer_step(i)
+                done = cycle
+            stream.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            saved = [(rt.nb.clone(), rt.w.clone()) for rt in layers]
+            with torch.cuda.graph(graph, stream=stream):
+                for i in range(cycle):
+                    layer_step(i)
+            for rt, (nb, w) in zip(layers, saved):      # capture does not run; restore anyway
+                rt.nb.copy_(nb); rt.w.copy_(w)
+            for _ in range((W - done) // cycle):
+                graph.replay()
+        else:
+            for i in range(W):
+                layer_step(i)
+        stream.synchronize()
+
+        # --- timed region: exactly K layer-steps ------------------------------------------------
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        wall0 = time.perf_counter()
+        ev0.record(stream)
+        if use_graph:
+            for _ in range(K // cycle):
+                graph.replay()
+        else:
+            for i in range(W, W + K):
+                layer_step(i)
+        ev1.record(stream)
+        stream.synchronize()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - wall0
+    gpu_ms = ev0.elapsed_time(ev1)
+    elapsed = max(wall, gpu_ms / 1e3)
+
+    err = max(rt.tables()[2] for rt in layers)
+    nb_end, w_end, _ = layers[0].tables()
+    t_end = t0 + (W + K) // NL
+    want = (t_end // c, t_end % c) if c > 0 else (0, t_end)
+    assert err == 0 and (int(nb_end[0]), int(w_end[0])) == want, (err, nb_end[0], w_end[0], want)
+    assert torch.isfinite(layers[0].out).all()
+
+    tok_first = t0 + W // NL + 1
+    step_bytes = [kv_bytes_per_step(wl, t) for t in range(tok_first, t_end + 1)]
+    total_bytes = sum(step_bytes) * NL
+    value = total_bytes / elapsed / 1e9
+
+    # --- dominant kernel: bc_decode_attn launch durations by HIP events, same stream ----------
+    # Fresh pass over the same token range of the rollout with the three calls issued separately
+    # so that an event pair brackets the attention launch alone.
+    n_samp = 0
+    samp_bytes = 0
+    samp_ms = 0.0
+    with torch.cuda.stream(stream):
+        for rt in layers:
+            t_s = tok_first - 1
+            if c > 0:
+                rt.set_tables(np.full(wl.B, t_s // c, np.int32), np.full(wl.B, t_s % c, np.int32))
+            else:
+                rt.set_tables(np.zeros(wl.B, np.int32), np.full(wl.B, t_s, np.int32))
+        n_tok = t_end - tok_first + 1
+        stride = max(1, n_tok // 256)
+        pairs = []
+        for j in range(n_tok):
+            t = tok_first + j
+            for li, rt in enumerate(layers):
+                x = pool[(j * NL + li) % n_pool]
+                rt.append_kv(x["k"], x["v"])
+                if j % stride == 0 and li == (j // stride) % NL:
+                    e0 = torch.cuda.Event(enable_timing=True)
+                    e1 = torch.cuda.Event(enable_timing=True)
+                    e0.record(stream)
+                    rt.decode_attn(x["q"])
+                    e1.record(stream)
+                    pairs.append((e0, e1, step_bytes[j]))
+                else:
+                    rt.decode_attn(x["q"])
+                if c > 0:
+                    rt.compress_evict(x["bk"], x["bv"])
+        stream.synchronize()
+    for e0, e1, nbytes in pairs:
+        samp_ms += e0.elapsed_time(e1)
+        samp_bytes += nbytes
+        n_samp += 1
+    achieved = samp_bytes / (samp_ms / 1e3) / 1e9 if samp_ms > 0 else 0.0
+
+    rec = {
+        "metric": "decode_attn_kv_GBps", "value": round(value, 2), "unit": "GB/s",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(elapsed * 1e3 / K, 6),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "steps_per_sec": round(K / elapsed, 1),
+        "token_steps_per_sec_%d_layers" % NL: round(K / NL / elapsed, 1),
+        "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
+        "config": {"workload": "batch64 rollout: B=64, Hq=12, Hkv=2, d=128, bf16, P=256, G=4096, c=%s; "
+                               "tokens %d..%d of the rollout" % (c if c > 0 else "inf", tok_first, t_end),
+                   "layers_round_robin": NL, "hip_graph": bool(use_graph),
+                   "step": "append_kv + decode_attn + compress_evict for one layer",
+                   "kv_bytes_per_step_mean": int(np.mean(step_bytes))},
+        "roofline": {"bound": "hbm", "kernel": "bc::decode_kernel (bc_decode_attn)",
+                     "achieved": round(achieved, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "avg_launch_us": round(samp_ms * 1e3 / max(n_samp, 1), 3),
+                     "launches_sampled": n_samp,
+                     "bytes_per_launch_mean": int(samp_bytes / max(n_samp, 1))},
+    }
+    if not args.no_cpu_baseline:
+        rec["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(rec))
+
+
+if __name__ == "__main__":
+    main()
