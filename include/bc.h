@@ -114,9 +114,9 @@ int32_t bc_append_kv(const bc_shape *shape, const bc_cache *cache, const void *k
 /* Bytes of workspace bc_decode_attn() needs for this shape and max_cap. */
 size_t bc_decode_workspace_bytes(const bc_shape *shape, int32_t max_cap);
 
-/* Zero the split counters at the head of a workspace.  Call once after allocating it
- * (a workspace allocated zero-filled needs no call); bc_decode_attn() leaves the
- * counters at zero when it finishes.  Enqueues a fill kernel, no memset node. */
+/* Zero a freshly allocated workspace (it holds per-sequence counters that the library
+ * expects to find at zero and leaves at zero).  Call once after allocating it; a workspace
+ * allocated zero-filled needs no call.  Enqueues a fill kernel, no memset node. */
 int32_t bc_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
 
 /* Single-token grouped-query attention over the resident entries (Sec. 2, Sec. 3.1:
@@ -125,7 +125,7 @@ int32_t bc_workspace_init(void *workspace, size_t workspace_bytes, void *stream)
  *   j over all L_s = P+nb+w rows, kvh = floor(h / (Hq/Hkv)).
  * q: [B, Hq, d] in kv_dtype; out: [B, Hq, d] fp32 (fp32 accumulation throughout).
  * A sequence with L_s == 0 sets the state bit and its output is left untouched.
- * The result is deterministic: partial results are combined in a fixed order.
+ * The result is deterministic: partial results are combined in a fixed order (no atomics).
  * Calls sharing one workspace must not overlap in time. */
 int32_t bc_decode_attn(const bc_shape *shape, const bc_cache *cache, const void *q,
                        float *out, const uint8_t *active, void *workspace,
@@ -145,8 +145,8 @@ int32_t bc_compress_evict(const bc_shape *shape, const bc_cache *cache, const vo
                           const void *beacon_v, const uint8_t *active,
                           int32_t require_full_window, void *stream);
 
-/* One decode step in two launches: append the token rows, attend, then evict where due
- * (supplied-beacon form).  Same semantics as bc_append_kv(TOKEN) + bc_decode_attn +
+/* One decode step: append the token rows, attend, then evict where due (supplied-beacon
+ * form); a single launch for bf16, d = 128.  Same semantics as bc_append_kv(TOKEN) + bc_decode_attn +
  * bc_compress_evict(beacon_k, beacon_v, require_full_window = 1) in that order.
  * beacon_k/v may be NULL: then no eviction is attempted. */
 int32_t bc_decode_step(const bc_shape *shape, const bc_cache *cache, const void *k,

@@ -216,7 +216,8 @@ class Runtime:
                               self.nb.data_ptr(), self.w.data_ptr(), self.err.data_ptr(),
                               self.max_cap)
         self.ws_bytes = int(bc_decode_workspace_bytes(self.shape, self.max_cap))
-        self.ws = torch.zeros(max(self.ws_bytes, 16), dtype=torch.uint8, device=device)
+        self.ws = torch.empty(max(self.ws_bytes, 16), dtype=torch.uint8, device=device)
+        _check(bc_workspace_init(_ptr(self.ws), self.ws.numel(), _stream_ptr()))
         self.out = torch.empty(self.B, self.Hq, self.d, dtype=torch.float32, device=device)
 
     # -- helpers --------------------------------------------------------------

@@ -161,12 +161,6 @@ __global__ void compress_evict_kernel(CacheView cv, const char* __restrict__ bk,
   }
 }
 
-__global__ void fill_zero_kernel(uint32_t* p, int64_t n) {
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
-       i += (int64_t)gridDim.x * blockDim.x)
-    p[i] = 0u;
-}
-
 }  // namespace bc
 
 using namespace bc;
@@ -224,16 +218,6 @@ extern "C" int32_t bc_compress_evict(const bc_shape* shape, const bc_cache* cach
   compress_evict_kernel<<<shape->B, 64, 0, as_stream(stream)>>>(
       cv, static_cast<const char*>(beacon_k), static_cast<const char*>(beacon_v), active,
       require_full_window ? 1 : 0);
-  return launch_status();
-}
-
-extern "C" int32_t bc_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
-  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 3u)) return BC_ERR_ARG;
-  const int64_t n = (int64_t)(workspace_bytes / 4);
-  if (n == 0) return BC_OK;
-  const int64_t blocks = (n + 255) / 256;
-  fill_zero_kernel<<<(int)(blocks < 4096 ? blocks : 4096), 256, 0, as_stream(stream)>>>(
-      static_cast<uint32_t*>(workspace), n);
   return launch_status();
 }
 

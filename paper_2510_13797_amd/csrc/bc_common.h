@@ -21,6 +21,9 @@ template <typename T> struct Elem;
 template <> struct Elem<float>  { static constexpr int size = 4; static constexpr int per16 = 4; };
 template <> struct Elem<bf16_t> { static constexpr int size = 2; static constexpr int per16 = 8; };
 
+// 2^x by the hardware instruction (inputs here are <= 0 or moderate; -1e30 gives 0)
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
 // 16 bytes of a row -> floats
 __device__ __forceinline__ void unpack16(const uint4& r, float (&f)[4], float) {
   f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y);

@@ -2,14 +2,19 @@
 // (Sec. 2 and Sec. 3.1 of the paper: standard attention over whatever is resident).
 //
 // Split-K flash decoding.  Work item = (sequence, KV head) pair x chunk of R rows; grid =
-// (max chunks, pairs), workgroups whose chunk lies beyond L exit at once.  Inside a
-// workgroup of 4 waves every global load instruction of a wave reads 1 KB of consecutive
-// bytes (RPI whole rows); the LPR lanes that share a row each hold 16 bytes of it, so a
-// lane owns EPL head-dim elements of q, K, V and of the accumulator for all G query
-// heads of the group.  Scores are completed by a DPP all-reduce over the LPR lanes; the
-// softmax is kept online per lane group with one rescale per U rows.  Lane groups,
-// waves and finally chunks are merged in a fixed order (the last chunk to finish, found
-// by a ticket counter, merges the chunk partials), so results are bit-reproducible.
+// (max chunks, pairs); workgroups whose chunk lies beyond L exit at once.  A pair that fits
+// one chunk is finished by its workgroup; otherwise every chunk writes an (m, l, o) partial
+// and a second, tiny kernel merges the partials of each pair in chunk order.  No atomics and
+// no fences: results are bit-reproducible.
+//
+// Two main kernels:
+//  * decode_lds_kernel (bf16, d = 128): every wave streams 32-row K and V tiles from HBM
+//    straight into its own LDS region with 16-byte LDS-DMA loads (1 KB of consecutive bytes
+//    per instruction, 16 KB in flight per wave), then forms the q.K products and the p.V
+//    sums of all query heads of the group with 16x16x32 bf16 MFMA tiles fed from LDS (K by
+//    128-bit reads, V by the 16-bit transposing reads), softmax in registers.
+//  * decode_valu_kernel (fp32 and d = 64): rows held in registers, 16 bytes per lane, plain
+//    FMA dot products completed by a DPP all-reduce.
 #include "bc_common.h"
 
 namespace bc {
@@ -26,45 +31,350 @@ struct DecodeParams {
   const char* q;
   float* out;
   const uint8_t* active;
-  int32_t* counters;   // [pairs] tickets, zero between launches
-  float* part_o;       // [pairs][max_chunks][G][D]
-  float* part_ml;      // [pairs][max_chunks][2][G]
-  int32_t Hq, Hkv, g;  // g = real group size (<= G)
-  int32_t rows_per_wg; // R, multiple of the rows one pass covers
+  float* part_o;       // [pairs][max_chunks][Gp][D]
+  float* part_ml;      // [pairs][max_chunks][2][Gp]   (running max in log2 units, denominator)
+  int32_t* part_n;     // [pairs] chunks written by this launch (read by the merge kernel)
+  // fused step (all nullable): append this token row first, evict with this beacon afterwards
+  const int32_t* c;
+  int32_t* nb_rw;
+  int32_t* w_rw;
+  const char* new_k;
+  const char* new_v;
+  const char* bk;
+  const char* bv;
+  int32_t* tickets;    // [B], zero between launches
+  int32_t Hq, Hkv, g;  // g = real group size
+  int32_t Gp;          // padded group size of the partial layout
+  int32_t D;
+  int32_t rows_per_wg; // R
   int32_t max_chunks;
   float qscale;        // softmax scale * log2(e)
 };
 
-constexpr int kWaves = 4;
+struct PairInfo {
+  int s, kvh, L, nchunks, chunk, row0, row_end;
+  int P, nb, w_att, cap, c;   // tables as the attention of this launch sees them
+  int new_row;                // slot of the row appended by this launch, or -1
+  bool evict_due;             // this launch ends with beacon append + eviction
+  bool update;                // tables change at the end of this launch
+  bool live;
+};
+
+// Common prologue: which rows does this workgroup own?  Uniform across the workgroup.  All
+// table loads are issued together.  With a fused append the state rules of bc_append_kv are
+// applied here, identically in every workgroup of the sequence.
+__device__ __forceinline__ PairInfo pair_info(const DecodeParams& p) {
+  PairInfo pi;
+  const int pair = blockIdx.y;
+  pi.s = pair / p.Hkv;
+  pi.kvh = pair - pi.s * p.Hkv;
+  const int act = p.active ? p.active[pi.s] : 1;
+  pi.P = p.P[pi.s];
+  pi.nb = p.nb[pi.s];
+  const int w = p.w[pi.s];
+  pi.cap = p.cap[pi.s];
+  pi.c = p.c ? p.c[pi.s] : 0;
+  const bool herald = blockIdx.x == 0 && pi.kvh == 0 && threadIdx.x == 0;   // reports errors
+  pi.live = false;
+  pi.update = false; pi.evict_due = false; pi.new_row = -1;
+  pi.L = 0; pi.nchunks = 0; pi.chunk = blockIdx.x; pi.row0 = 0; pi.row_end = 0; pi.w_att = w;
+  if (act) {
+    const int L_old = pi.P + pi.nb + w;
+    bool append_ok = false;
+    if (p.new_k) {
+      if (pi.c > 0 && w >= pi.c) { if (herald) atomicOr(p.err, BC_ERRBIT_STATE); }
+      else if (L_old >= pi.cap)  { if (herald) atomicOr(p.err, BC_ERRBIT_CAPACITY); }
+      else append_ok = true;
+    }
+    pi.L = L_old + (append_ok ? 1 : 0);
+    pi.w_att = w + (append_ok ? 1 : 0);
+    if (append_ok) pi.new_row = L_old;
+    if (p.bk && pi.c > 0) {
+      if (pi.w_att == pi.c + 1) { if (herald) atomicOr(p.err, BC_ERRBIT_STATE); }
+      else if (pi.w_att == pi.c) pi.evict_due = true;
+    }
+    if (pi.L <= 0) {
+      if (herald) atomicOr(p.err, BC_ERRBIT_STATE);
+    } else {
+      pi.nchunks = (pi.L + p.rows_per_wg - 1) / p.rows_per_wg;
+      pi.update = append_ok || pi.evict_due;
+      if (pi.chunk < pi.nchunks) {
+        pi.row0 = pi.chunk * p.rows_per_wg;
+        pi.row_end = min(pi.L, pi.row0 + p.rows_per_wg);
+        pi.live = true;
+      }
+    }
+  }
+  if (p.part_n && blockIdx.x == 0 && threadIdx.x == 0) p.part_n[pair] = pi.nchunks;
+  return pi;
+}
+
+// Epilogue shared by both kernels: s_m/s_l/s_acc hold one (m, l, o) per wave in LDS;
+// merge them in wave order and write the result or the chunk partial.
+template <int NW, int D>
+__device__ __forceinline__ void merge_waves_and_store(const DecodeParams& p, const PairInfo& pi,
+                                                      const float* s_m, const float* s_l,
+                                                      const float* s_acc, int gstride) {
+  const int nout = p.g * D;
+  const int pair = blockIdx.y;
+  float* po = p.part_o + ((int64_t)pair * p.max_chunks + pi.chunk) * (p.Gp * D);
+  float* pml = p.part_ml + ((int64_t)pair * p.max_chunks + pi.chunk) * (2 * p.Gp);
+  float* outp = p.out + (int64_t)(pi.s * p.Hq + pi.kvh * p.g) * D;
+  for (int i = threadIdx.x; i < nout; i += blockDim.x) {
+    const int h = i / D, x = i - h * D;
+    float mx = s_m[h];
+#pragma unroll
+    for (int wv = 1; wv < NW; ++wv) mx = fmaxf(mx, s_m[wv * gstride + h]);
+    float lsum = 0.f, o = 0.f;
+#pragma unroll
+    for (int wv = 0; wv < NW; ++wv) {
+      const float a = fast_exp2(s_m[wv * gstride + h] - mx);
+      lsum += s_l[wv * gstride + h] * a;
+      o += s_acc[(wv * gstride + h) * D + x] * a;
+    }
+    if (pi.nchunks == 1) {
+      outp[i] = o / lsum;
+    } else {
+      po[i] = o;
+      if (x == 0) { pml[h] = mx; pml[p.Gp + h] = lsum; }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// bf16, d = 128: LDS-DMA tiles + MFMA
+// ---------------------------------------------------------------------------
+constexpr int kLdsWaves = 8;           // waves per workgroup
+constexpr int kTileRows = 32;          // rows per wave tile
+constexpr int kTileBytes = kTileRows * 256;   // one K (or V) tile: 8 KB
+constexpr int kLdsBytes = kLdsWaves * 2 * kTileBytes;   // 128 KB
+
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((address_space(1))) const void global_void_t;
+typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
+
+__device__ __forceinline__ uint32_t bf16_rne_bits(float x) {     // finite x only
+  const uint32_t u = __float_as_uint(x);
+  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+__global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams p) {
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  const PairInfo pi = pair_info(p);
+  if (!pi.live) return;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n = lane & 15, kb = lane >> 4;       // MFMA column / k-block of this lane
+  const int64_t stream_off = (p.base[pi.s] * p.Hkv + (int64_t)pi.kvh * pi.cap) * 256;
+  const char* kbase = p.k_slab + stream_off;
+  const char* vbase = p.v_slab + stream_off;
+  char* wk = lds + wave * (2 * kTileBytes);
+  char* wv = wk + kTileBytes;
+
+  // B operand of the score product: Q^T, column n = query head, k = head-dim index.
+  bf16x8_t qb[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    uint4 r = make_uint4(0u, 0u, 0u, 0u);
+    if (n < p.g)
+      r = *reinterpret_cast<const uint4*>(
+          p.q + ((int64_t)(pi.s * p.Hq + pi.kvh * p.g + n) * 128 + 32 * i + 8 * kb) * 2);
+    qb[i] = __builtin_bit_cast(bf16x8_t, r);
+  }
+
+  // fused append: lanes 0..15 carry the new K row, lanes 16..31 the new V row (16 bytes each)
+  uint4 newrow = make_uint4(0u, 0u, 0u, 0u);
+  if (pi.new_row >= 0 && lane < 32) {
+    const char* src = (lane < 16 ? p.new_k : p.new_v) +
+                      (int64_t)(pi.s * p.Hkv + pi.kvh) * 256 + ((lane & 15) << 4);
+    newrow = *reinterpret_cast<const uint4*>(src);
+  }
+  // rows the tile loads may touch: the resident rows that are already in the slab
+  const int last_slab_row = max((pi.new_row >= 0 ? pi.new_row : pi.L) - 1, 0);
+
+  f32x4_t O[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) O[j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  float m_run = kNegBig, l_run = 0.f;
+
+  const int ntiles = (pi.row_end - pi.row0 + kTileRows - 1) / kTileRows;
+  for (int tile = wave; tile < ntiles; tile += kLdsWaves) {
+    const int trow0 = pi.row0 + tile * kTileRows;
+    // ---- HBM -> LDS: 8 + 8 instructions, each 4 whole rows (1 KB), 16-byte units XOR-swizzled
+    {
+      const int r4 = lane >> 4, pos = lane & 15;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int row = 4 * j + r4;
+        const int grow = min(trow0 + row, last_slab_row);     // stay inside the slab rows
+        const int64_t goff = (int64_t)grow * 256 + ((pos ^ (row & 15)) << 4);
+        __builtin_amdgcn_global_load_lds((global_void_t*)(kbase + goff),
+                                         (lds_void_t*)(wk + j * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((global_void_t*)(vbase + goff),
+                                         (lds_void_t*)(wv + j * 1024), 16, 0, 0);
+      }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+
+    if (pi.new_row >= trow0 && pi.new_row < trow0 + kTileRows) {
+      // the appended row is not in the slab yet: place it in the tile, store it for later
+      // steps (unless this step's eviction drops it at once), clear the V rows behind it
+      const int ra = pi.new_row - trow0;
+      if (lane < 32) {
+        char* tile = lane < 16 ? wk : wv;
+        const int u = lane & 15;
+        *reinterpret_cast<uint4*>(tile + ra * 256 + ((u ^ (ra & 15)) << 4)) = newrow;
+        if (!(pi.evict_due && pi.w_att == 1)) {
+          char* slab = const_cast<char*>(lane < 16 ? kbase : vbase);
+          *reinterpret_cast<uint4*>(slab + (int64_t)pi.new_row * 256 + (u << 4)) = newrow;
+        }
+      }
+      for (int rr = ra + 1 + (lane >> 4); rr < kTileRows; rr += 4)
+        *reinterpret_cast<uint4*>(wv + rr * 256 + ((lane & 15) << 4)) = make_uint4(0u, 0u, 0u, 0u);
+    }
+
+    // ---- scores, transposed: S^T[key][head] = K . Q^T.  Row m of sub-tile t is key
+    //      8*(m/4) + 4*t + m%4, so that a lane ends up with 8 consecutive keys of one head.
+    f32x4_t S[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      S[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+      const int row = ((n >> 2) << 3) + 4 * t + (n & 3);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int u = 4 * i + kb;
+        const bf16x8_t a =
+            *reinterpret_cast<const bf16x8_t*>(wk + row * 256 + ((u ^ (row & 15)) << 4));
+        S[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qb[i], S[t], 0, 0, 0);
+      }
+    }
+    // lane (n, kb) now holds head n, keys trow0 + 8*kb + e, e = 4*t + r
+    float sv[8];
+    float tmax = kNegBig;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const bool valid = trow0 + 8 * kb + e < pi.row_end;
+      sv[e] = valid ? S[e >> 2][e & 3] * p.qscale : kNegBig;
+      tmax = fmaxf(tmax, sv[e]);
+    }
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+    const float m_new = fmaxf(m_run, tmax);
+    const float alpha = fast_exp2(m_run - m_new);
+    m_run = m_new;
+    float psum = 0.f;
+    uint32_t hi[4], lo[4];
+#pragma unroll
+    for (int e = 0; e < 8; e += 2) {
+      float pa = (trow0 + 8 * kb + e < pi.row_end) ? fast_exp2(sv[e] - m_new) : 0.f;
+      float pb = (trow0 + 8 * kb + e + 1 < pi.row_end) ? fast_exp2(sv[e + 1] - m_new) : 0.f;
+      psum += pa + pb;
+      // p = hi + lo with both parts bf16: the p.V product keeps ~16 bits of p
+      const uint32_t ha = __float_as_uint(pa) & 0xffff0000u, hb = __float_as_uint(pb) & 0xffff0000u;
+      const uint32_t la = bf16_rne_bits(pa - __uint_as_float(ha));
+      const uint32_t lb = bf16_rne_bits(pb - __uint_as_float(hb));
+      hi[e >> 1] = (ha >> 16) | hb;
+      lo[e >> 1] = la | (lb << 16);
+    }
+    l_run = l_run * alpha + psum;
+    const bf16x8_t phi = __builtin_bit_cast(bf16x8_t, make_uint4(hi[0], hi[1], hi[2], hi[3]));
+    const bf16x8_t plo = __builtin_bit_cast(bf16x8_t, make_uint4(lo[0], lo[1], lo[2], lo[3]));
+
+    // ---- O^T[dcol][head] += V^T . P^T ; V^T comes from the transposing LDS read: lane r of a
+    //      16-lane block points at 4 consecutive dcols of key 8*kb + r/4 (+4 for the 2nd read)
+    {
+      const int r = lane & 15;
+      const int key0 = 8 * kb + (r >> 2);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        O[j] *= alpha;
+        const int u = 2 * j + ((r & 3) >> 1);
+        const int sub = (r & 1) << 3;
+        const int rowa = key0, rowb = key0 + 4;
+        const s16x4_t a0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (lds_s16x4_t*)(wv + rowa * 256 + ((u ^ (rowa & 15)) << 4) + sub));
+        const s16x4_t a1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (lds_s16x4_t*)(wv + rowb * 256 + ((u ^ (rowb & 15)) << 4) + sub));
+        typedef __attribute__((ext_vector_type(8))) short s16x8_t;
+        const s16x8_t a = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
+        const bf16x8_t av = __builtin_bit_cast(bf16x8_t, a);
+        O[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, phi, O[j], 0, 0, 0);
+        O[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, plo, O[j], 0, 0, 0);
+      }
+    }
+  }
+
+  // denominators: sum the four k-blocks of each head
+  l_run += __shfl_xor(l_run, 16, 64);
+  l_run += __shfl_xor(l_run, 32, 64);
+
+  // ---- merge the waves through LDS (the tile regions are free once everyone is here)
+  __syncthreads();
+  float* s_acc = reinterpret_cast<float*>(lds);                    // [wave][8][128]
+  float* s_m = s_acc + kLdsWaves * 8 * 128;                        // [wave][8]
+  float* s_l = s_m + kLdsWaves * 8;
+  if (n < p.g) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      *reinterpret_cast<f32x4_t*>(s_acc + (wave * 8 + n) * 128 + 16 * j + 4 * kb) = O[j];
+    if (kb == 0) { s_m[wave * 8 + n] = m_run; s_l[wave * 8 + n] = l_run; }
+  }
+  __syncthreads();
+  merge_waves_and_store<kLdsWaves, 128>(p, pi, s_m, s_l, s_acc, 8);
+
+  // ---- fused step: the last workgroup of the sequence to get here (every other one has
+  //      finished reading the window) writes the beacon row and updates the tables
+  if (!pi.update) return;
+  __shared__ int s_last;
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (tid == 0) {
+    const int old = atomicAdd(p.tickets + pi.s, 1);
+    s_last = (old == p.Hkv * pi.nchunks - 1) ? 1 : 0;
+  }
+  __syncthreads();
+  if (!s_last) return;
+  if (pi.evict_due) {
+    const int n = p.Hkv * 16;                      // 16-byte units of one K (or V) entry
+    for (int i = tid; i < 2 * n; i += kLdsWaves * 64) {
+      const int which = i >= n, r = which ? i - n : i;
+      const int h = r >> 4, u = r & 15;
+      const char* src = (which ? p.bv : p.bk) + (int64_t)(pi.s * p.Hkv + h) * 256 + (u << 4);
+      char* slab = const_cast<char*>(which ? p.v_slab : p.k_slab);
+      const int64_t dst =
+          (p.base[pi.s] * p.Hkv + (int64_t)h * pi.cap + pi.P + pi.nb) * 256 + (u << 4);
+      *reinterpret_cast<uint4*>(slab + dst) = *reinterpret_cast<const uint4*>(src);
+    }
+  }
+  if (tid == 0) {
+    p.tickets[pi.s] = 0;
+    p.nb_rw[pi.s] = pi.nb + (pi.evict_due ? 1 : 0);
+    p.w_rw[pi.s] = pi.evict_due ? 0 : pi.w_att;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// generic VALU kernel: fp32 rows and d = 64
+// ---------------------------------------------------------------------------
+constexpr int kValuWaves = 4;
 
 template <typename T, int D, int G, int U>
-__global__ __launch_bounds__(256) void decode_kernel(DecodeParams p) {
+__global__ __launch_bounds__(256) void decode_valu_kernel(DecodeParams p) {
   constexpr int ES = Elem<T>::size;
   constexpr int EPL = Elem<T>::per16;   // elements per lane per row
   constexpr int LPR = D / EPL;          // lanes per row
   constexpr int RPI = 64 / LPR;         // rows per wave load instruction
   constexpr int RB = D * ES;            // row bytes
-  constexpr int ROWS_PER_PASS = kWaves * RPI * U;
+  constexpr int ROWS_PER_PASS = kValuWaves * RPI * U;
 
-  const int pair = blockIdx.y;
-  const int s = pair / p.Hkv, kvh = pair - s * p.Hkv;
-  if (p.active && !p.active[s]) return;
-  const int L = p.P[s] + p.nb[s] + p.w[s];
-  if (L <= 0) {
-    if (blockIdx.x == 0 && kvh == 0 && threadIdx.x == 0) atomicOr(p.err, BC_ERRBIT_STATE);
-    return;
-  }
-  const int R = p.rows_per_wg;
-  const int nchunks = (L + R - 1) / R;
-  const int chunk = blockIdx.x;
-  if (chunk >= nchunks) return;
-  const int row0 = chunk * R;
-  const int row_end = min(L, row0 + R);
+  const PairInfo pi = pair_info(p);
+  if (!pi.live) return;
+  const int L = pi.L, row_end = pi.row_end;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane / LPR, ls = lane - lr * LPR;
-  const int cap = p.cap[s];
-  const int64_t stream_off = (p.base[s] * p.Hkv + (int64_t)kvh * cap) * RB + ls * 16;
+  const int64_t stream_off = (p.base[pi.s] * p.Hkv + (int64_t)pi.kvh * pi.cap) * RB + ls * 16;
   const char* kbase = p.k_slab + stream_off;
   const char* vbase = p.v_slab + stream_off;
 
@@ -74,7 +384,7 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeParams p) {
   for (int h = 0; h < G; ++h) {
     if (h < p.g) {
       const uint4 r = *reinterpret_cast<const uint4*>(
-          p.q + ((int64_t)(s * p.Hq + kvh * p.g + h) * D) * ES + ls * 16);
+          p.q + ((int64_t)(pi.s * p.Hq + pi.kvh * p.g + h) * D) * ES + ls * 16);
       unpack16(r, qf[h], T{});
 #pragma unroll
       for (int e = 0; e < EPL; ++e) qf[h][e] *= p.qscale;
@@ -92,7 +402,7 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeParams p) {
     for (int e = 0; e < EPL; ++e) acc[h][e] = 0.f;
   }
 
-  for (int pr = row0 + wave * (RPI * U); pr < row_end; pr += ROWS_PER_PASS) {
+  for (int pr = pi.row0 + wave * (RPI * U); pr < row_end; pr += ROWS_PER_PASS) {
     uint4 kk[U], vv[U];
     bool valid[U];
 #pragma unroll
@@ -127,14 +437,14 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeParams p) {
       float mn = m[h];
 #pragma unroll
       for (int u = 0; u < U; ++u) mn = fmaxf(mn, sc[u][h]);
-      const float alpha = exp2f(m[h] - mn);
+      const float alpha = fast_exp2(m[h] - mn);
       m[h] = mn;
       l[h] *= alpha;
 #pragma unroll
       for (int e = 0; e < EPL; ++e) acc[h][e] *= alpha;
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        const float pw = valid[u] ? exp2f(sc[u][h] - mn) : 0.f;
+        const float pw = valid[u] ? fast_exp2(sc[u][h] - mn) : 0.f;
         sc[u][h] = pw;
         l[h] += pw;
       }
@@ -158,7 +468,7 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeParams p) {
       const float mo = __shfl_xor(m[h], off, 64);
       const float lo = __shfl_xor(l[h], off, 64);
       const float mn = fmaxf(m[h], mo);
-      const float a = exp2f(m[h] - mn), b = exp2f(mo - mn);
+      const float a = fast_exp2(m[h] - mn), b = fast_exp2(mo - mn);
       m[h] = mn;
       l[h] = l[h] * a + lo * b;
 #pragma unroll
@@ -169,66 +479,42 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeParams p) {
     }
   }
 
-  __shared__ float s_acc[kWaves][G][D];
-  __shared__ float s_m[kWaves][G], s_l[kWaves][G];
-  __shared__ int s_ticket;
+  __shared__ float s_acc[kValuWaves * G * D];
+  __shared__ float s_m[kValuWaves * G], s_l[kValuWaves * G];
   if (lr == 0) {
 #pragma unroll
     for (int h = 0; h < G; ++h) {
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) s_acc[wave][h][ls * EPL + e] = acc[h][e];
-      if (ls == 0) { s_m[wave][h] = m[h]; s_l[wave][h] = l[h]; }
+      for (int e = 0; e < EPL; ++e) s_acc[(wave * G + h) * D + ls * EPL + e] = acc[h][e];
+      if (ls == 0) { s_m[wave * G + h] = m[h]; s_l[wave * G + h] = l[h]; }
     }
   }
   __syncthreads();
+  merge_waves_and_store<kValuWaves, D>(p, pi, s_m, s_l, s_acc, G);
+}
 
-  // merge the waves: one output element (head, x) per thread per iteration
-  const int nout = p.g * D;
-  float* po = p.part_o + ((int64_t)pair * p.max_chunks + chunk) * (G * D);
-  float* pml = p.part_ml + ((int64_t)pair * p.max_chunks + chunk) * (2 * G);
+// ---------------------------------------------------------------------------
+// chunk merge: one workgroup per pair, partials combined in chunk order
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void decode_merge_kernel(DecodeParams p) {
+  const int pair = blockIdx.x;
+  const int s = pair / p.Hkv, kvh = pair - s * p.Hkv;
+  const int nchunks = p.part_n[pair];             // 0: nothing to do, 1: already final
+  if (nchunks <= 1) return;
+  const int D = p.D;
+  const float* ao = p.part_o + (int64_t)pair * p.max_chunks * (p.Gp * D);
+  const float* aml = p.part_ml + (int64_t)pair * p.max_chunks * (2 * p.Gp);
   float* outp = p.out + (int64_t)(s * p.Hq + kvh * p.g) * D;
-  for (int i = tid; i < nout; i += 256) {
-    const int h = i / D, x = i - h * D;
-    float mx = s_m[0][h];
-#pragma unroll
-    for (int wv = 1; wv < kWaves; ++wv) mx = fmaxf(mx, s_m[wv][h]);
-    float lsum = 0.f, o = 0.f;
-#pragma unroll
-    for (int wv = 0; wv < kWaves; ++wv) {
-      const float a = exp2f(s_m[wv][h] - mx);
-      lsum += s_l[wv][h] * a;
-      o += s_acc[wv][h][x] * a;
-    }
-    if (nchunks == 1) {
-      outp[i] = o / lsum;
-    } else {
-      po[i] = o;
-      if (x == 0) { pml[h] = mx; pml[G + h] = lsum; }
-    }
-  }
-  if (nchunks == 1) return;
-
-  // publish the partial, take a ticket; the last chunk of the pair merges all of them
-  __syncthreads();
-  if (tid == 0) {
-    __threadfence();
-    s_ticket = atomicAdd(p.counters + pair, 1);
-  }
-  __syncthreads();
-  if (s_ticket != nchunks - 1) return;
-  if (tid == 0) p.counters[pair] = 0;       // ready for the next launch
-  __threadfence();
-  const float* ao = p.part_o + (int64_t)pair * p.max_chunks * (G * D);
-  const float* aml = p.part_ml + (int64_t)pair * p.max_chunks * (2 * G);
-  for (int i = tid; i < nout; i += 256) {
+  const int nout = p.g * D;
+  for (int i = threadIdx.x; i < nout; i += blockDim.x) {
     const int h = i / D;
     float mx = kNegBig;
-    for (int ch = 0; ch < nchunks; ++ch) mx = fmaxf(mx, aml[ch * 2 * G + h]);
+    for (int ch = 0; ch < nchunks; ++ch) mx = fmaxf(mx, aml[ch * 2 * p.Gp + h]);
     float lsum = 0.f, o = 0.f;
     for (int ch = 0; ch < nchunks; ++ch) {
-      const float a = exp2f(aml[ch * 2 * G + h] - mx);
-      lsum += aml[ch * 2 * G + G + h] * a;
-      o += ao[(int64_t)ch * (G * D) + i] * a;
+      const float a = fast_exp2(aml[ch * 2 * p.Gp + h] - mx);
+      lsum += aml[ch * 2 * p.Gp + p.Gp + h] * a;
+      o += ao[(int64_t)ch * (p.Gp * D) + i] * a;
     }
     outp[i] = o / lsum;
   }
@@ -238,44 +524,142 @@ static int g_rows_per_wg = 0;
 static int g_variant = 0;
 
 struct DecodePlan {
-  int G;              // padded group size of the instantiated kernel
+  bool lds;           // LDS/MFMA kernel (bf16, d = 128) or the VALU kernel
+  int Gp;             // padded group size
   int rows_per_pass;  // rows one pass of a workgroup covers
   int R;              // rows per workgroup
   int max_chunks;
-  size_t counters_bytes, part_o_bytes, part_ml_bytes;
+  size_t tickets_bytes, part_n_bytes, part_o_bytes, part_ml_bytes;
+  size_t total() const { return tickets_bytes + part_n_bytes + part_o_bytes + part_ml_bytes; }
 };
 
 static int padded_group(int g) { return g <= 1 ? 1 : g <= 2 ? 2 : g <= 4 ? 4 : g <= 6 ? 6 : 8; }
+static size_t align256(size_t x) { return (x + 255) / 256 * 256; }
 
-static DecodePlan make_plan(const bc_shape* sh, int max_cap) {
+static DecodePlan make_plan(const bc_shape* sh, int max_cap, int rows_override, int variant) {
   DecodePlan pl;
-  pl.G = padded_group(sh->Hq / sh->Hkv);
-  const int epl = 16 / elem_size(sh->kv_dtype);
-  const int lpr = sh->d / epl, rpi = 64 / lpr;
-  const int U = 8;
-  pl.rows_per_pass = kWaves * rpi * U;
-  int R = g_rows_per_wg > 0 ? g_rows_per_wg : pl.rows_per_pass;
+  pl.lds = sh->kv_dtype == BC_BF16 && sh->d == 128 && variant != 1;
+  if (pl.lds) {
+    pl.Gp = 8;
+    pl.rows_per_pass = kLdsWaves * kTileRows;
+  } else {
+    pl.Gp = padded_group(sh->Hq / sh->Hkv);
+    const int epl = 16 / elem_size(sh->kv_dtype);
+    const int lpr = sh->d / epl, rpi = 64 / lpr;
+    pl.rows_per_pass = kValuWaves * rpi * 8;
+  }
+  int R;
+  if (rows_override > 0) {
+    R = rows_override;
+  } else {
+    // One workgroup per (sequence, KV head) pair when there are enough pairs: a long-running
+    // workgroup streams its rows at full rate and needs no merge launch.  With few pairs,
+    // split so that about 128 workgroups exist.
+    const long pairs = (long)sh->B * sh->Hkv;
+    long want = (128 + pairs - 1) / pairs;
+    if (want < 1) want = 1;
+    R = (int)((max_cap + want - 1) / want);
+    if (R < 4 * pl.rows_per_pass) R = 4 * pl.rows_per_pass;
+  }
   R = ((R + pl.rows_per_pass - 1) / pl.rows_per_pass) * pl.rows_per_pass;
-  // keep the number of chunk partials per pair bounded for long uncompressed caches
-  while ((max_cap + R - 1) / R > 64) R += pl.rows_per_pass;
+  while ((max_cap + R - 1) / R > 64) R += pl.rows_per_pass;   // bound the partials per pair
   pl.R = R;
   pl.max_chunks = (max_cap + R - 1) / R;
   const size_t pairs = (size_t)sh->B * sh->Hkv;
-  pl.counters_bytes = ((pairs * 4 + 255) / 256) * 256;
-  pl.part_o_bytes = pairs * pl.max_chunks * pl.G * sh->d * 4;
-  pl.part_ml_bytes = pairs * pl.max_chunks * 2 * pl.G * 4;
+  pl.tickets_bytes = align256((size_t)sh->B * 4);
+  pl.part_n_bytes = align256(pairs * 4);
+  pl.part_o_bytes = align256(pairs * pl.max_chunks * pl.Gp * sh->d * 4);
+  pl.part_ml_bytes = align256(pairs * pl.max_chunks * 2 * pl.Gp * 4);
   return pl;
 }
 
 template <typename T, int D>
-static void launch_decode(const DecodeParams& p, int G, dim3 grid, hipStream_t st) {
+static void launch_valu(const DecodeParams& p, int G, dim3 grid, hipStream_t st) {
   switch (G) {
-    case 1: decode_kernel<T, D, 1, 8><<<grid, 256, 0, st>>>(p); break;
-    case 2: decode_kernel<T, D, 2, 8><<<grid, 256, 0, st>>>(p); break;
-    case 4: decode_kernel<T, D, 4, 8><<<grid, 256, 0, st>>>(p); break;
-    case 6: decode_kernel<T, D, 6, 8><<<grid, 256, 0, st>>>(p); break;
-    default: decode_kernel<T, D, 8, 8><<<grid, 256, 0, st>>>(p); break;
+    case 1: decode_valu_kernel<T, D, 1, 8><<<grid, 256, 0, st>>>(p); break;
+    case 2: decode_valu_kernel<T, D, 2, 8><<<grid, 256, 0, st>>>(p); break;
+    case 4: decode_valu_kernel<T, D, 4, 8><<<grid, 256, 0, st>>>(p); break;
+    case 6: decode_valu_kernel<T, D, 6, 8><<<grid, 256, 0, st>>>(p); break;
+    default: decode_valu_kernel<T, D, 8, 8><<<grid, 256, 0, st>>>(p); break;
   }
+}
+
+// The LDS kernel needs 128 KB of dynamic LDS: opt in once per device.
+static int32_t enable_big_lds() {
+  static bool done[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return BC_ERR_HIP;
+  if (done[dev]) return BC_OK;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(decode_lds_kernel),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) != hipSuccess)
+    return BC_ERR_HIP;
+  done[dev] = true;
+  return BC_OK;
+}
+
+__global__ void fill_zero_kernel(uint32_t* p, int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+       i += (int64_t)gridDim.x * blockDim.x)
+    p[i] = 0u;
+}
+
+// Attention launch shared by bc_decode_attn (k = beacon_k = NULL) and the fused bc_decode_step.
+static int32_t launch_attention(const bc_shape* shape, const bc_cache* cache, const DecodePlan& pl,
+                                const void* q, float* out, const uint8_t* active, void* workspace,
+                                const void* k, const void* v, const void* bk, const void* bv,
+                                hipStream_t hs) {
+  DecodeParams p;
+  p.k_slab = static_cast<const char*>(cache->k_slab);
+  p.v_slab = static_cast<const char*>(cache->v_slab);
+  p.base = cache->base; p.cap = cache->cap; p.P = cache->P; p.nb = cache->nb; p.w = cache->w;
+  p.err = cache->err;
+  p.q = static_cast<const char*>(q);
+  p.out = out;
+  p.active = active;
+  char* ws = static_cast<char*>(workspace);
+  p.tickets = reinterpret_cast<int32_t*>(ws);
+  p.part_n = pl.max_chunks > 1 ? reinterpret_cast<int32_t*>(ws + pl.tickets_bytes) : nullptr;
+  p.part_o = reinterpret_cast<float*>(ws + pl.tickets_bytes + pl.part_n_bytes);
+  p.part_ml = reinterpret_cast<float*>(ws + pl.tickets_bytes + pl.part_n_bytes + pl.part_o_bytes);
+  p.c = cache->c; p.nb_rw = cache->nb; p.w_rw = cache->w;
+  p.new_k = static_cast<const char*>(k); p.new_v = static_cast<const char*>(v);
+  p.bk = static_cast<const char*>(bk); p.bv = static_cast<const char*>(bv);
+  p.Hq = shape->Hq; p.Hkv = shape->Hkv; p.g = shape->Hq / shape->Hkv;
+  p.Gp = pl.Gp;
+  p.D = shape->d;
+  p.rows_per_wg = pl.R;
+  p.max_chunks = pl.max_chunks;
+  p.qscale = shape->scale * kLog2e;
+
+  const int pairs = shape->B * shape->Hkv;
+  const dim3 grid(pl.max_chunks, pairs);
+  if (pl.lds) {
+    const int32_t st = enable_big_lds();
+    if (st != BC_OK) return st;
+    decode_lds_kernel<<<grid, kLdsWaves * 64, kLdsBytes, hs>>>(p);
+  } else if (shape->kv_dtype == BC_BF16) {
+    if (shape->d == 128) launch_valu<bf16_t, 128>(p, pl.Gp, grid, hs);
+    else launch_valu<bf16_t, 64>(p, pl.Gp, grid, hs);
+  } else {
+    if (shape->d == 128) launch_valu<float, 128>(p, pl.Gp, grid, hs);
+    else launch_valu<float, 64>(p, pl.Gp, grid, hs);
+  }
+  if (pl.max_chunks > 1) decode_merge_kernel<<<pairs, 256, 0, hs>>>(p);
+  return launch_status();
+}
+
+static int32_t check_attention_args(const bc_shape* shape, const bc_cache* cache, const void* q,
+                                    const float* out, const void* workspace, size_t workspace_bytes,
+                                    DecodePlan* pl) {
+  int32_t st = check_shape(shape);
+  if (st != BC_OK) return st;
+  st = check_cache(cache);
+  if (st != BC_OK) return st;
+  if (!q || !out || !aligned16(q) || !aligned16(out)) return BC_ERR_ARG;
+  *pl = make_plan(shape, cache->max_cap, g_rows_per_wg, g_variant);
+  if (g_variant == 2 && !pl->lds) return BC_ERR_SHAPE;
+  if (!workspace || !aligned16(workspace) || workspace_bytes < pl->total()) return BC_ERR_WORKSPACE;
+  return BC_OK;
 }
 
 }  // namespace bc
@@ -289,65 +673,49 @@ extern "C" void bc_set_decode_tuning(int32_t rows_per_workgroup, int32_t variant
 
 extern "C" size_t bc_decode_workspace_bytes(const bc_shape* shape, int32_t max_cap) {
   if (check_shape(shape) != BC_OK || max_cap < 1) return 0;
-  // sized for the smallest chunk any tuning can select, so a tuning change never outgrows it
-  const int saved = g_rows_per_wg;
-  g_rows_per_wg = 0;
-  const DecodePlan pl = make_plan(shape, max_cap);
-  g_rows_per_wg = saved;
-  return pl.counters_bytes + pl.part_o_bytes + pl.part_ml_bytes;
+  // sized for the smallest chunk any tuning can select, for either kernel
+  const DecodePlan a = make_plan(shape, max_cap, 1, 0), b = make_plan(shape, max_cap, 1, 1);
+  return a.total() > b.total() ? a.total() : b.total();
+}
+
+extern "C" int32_t bc_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 3u)) return BC_ERR_ARG;
+  const int64_t n = (int64_t)(workspace_bytes / 4);
+  if (n == 0) return BC_OK;
+  const int64_t blocks = (n + 255) / 256;
+  fill_zero_kernel<<<(int)(blocks < 4096 ? blocks : 4096), 256, 0, as_stream(stream)>>>(
+      static_cast<uint32_t*>(workspace), n);
+  return launch_status();
 }
 
 extern "C" int32_t bc_decode_attn(const bc_shape* shape, const bc_cache* cache, const void* q,
                                   float* out, const uint8_t* active, void* workspace,
                                   size_t workspace_bytes, void* stream) {
-  int32_t st = check_shape(shape);
+  DecodePlan pl;
+  const int32_t st = check_attention_args(shape, cache, q, out, workspace, workspace_bytes, &pl);
   if (st != BC_OK) return st;
-  st = check_cache(cache);
-  if (st != BC_OK) return st;
-  if (!q || !out || !aligned16(q) || !aligned16(out)) return BC_ERR_ARG;
-  const DecodePlan pl = make_plan(shape, cache->max_cap);
-  if (!workspace || !aligned16(workspace) ||
-      workspace_bytes < pl.counters_bytes + pl.part_o_bytes + pl.part_ml_bytes)
-    return BC_ERR_WORKSPACE;
-
-  DecodeParams p;
-  p.k_slab = static_cast<const char*>(cache->k_slab);
-  p.v_slab = static_cast<const char*>(cache->v_slab);
-  p.base = cache->base; p.cap = cache->cap; p.P = cache->P; p.nb = cache->nb; p.w = cache->w;
-  p.err = cache->err;
-  p.q = static_cast<const char*>(q);
-  p.out = out;
-  p.active = active;
-  char* ws = static_cast<char*>(workspace);
-  p.counters = reinterpret_cast<int32_t*>(ws);
-  p.part_o = reinterpret_cast<float*>(ws + pl.counters_bytes);
-  p.part_ml = reinterpret_cast<float*>(ws + pl.counters_bytes + pl.part_o_bytes);
-  p.Hq = shape->Hq; p.Hkv = shape->Hkv; p.g = shape->Hq / shape->Hkv;
-  p.rows_per_wg = pl.R;
-  p.max_chunks = pl.max_chunks;
-  p.qscale = shape->scale * kLog2e;
-
-  const dim3 grid(pl.max_chunks, shape->B * shape->Hkv);
-  hipStream_t hs = as_stream(stream);
-  if (shape->kv_dtype == BC_BF16) {
-    if (shape->d == 128) launch_decode<bf16_t, 128>(p, pl.G, grid, hs);
-    else launch_decode<bf16_t, 64>(p, pl.G, grid, hs);
-  } else {
-    if (shape->d == 128) launch_decode<float, 128>(p, pl.G, grid, hs);
-    else launch_decode<float, 64>(p, pl.G, grid, hs);
-  }
-  return launch_status();
+  return launch_attention(shape, cache, pl, q, out, active, workspace, nullptr, nullptr, nullptr,
+                          nullptr, as_stream(stream));
 }
 
 extern "C" int32_t bc_decode_step(const bc_shape* shape, const bc_cache* cache, const void* k,
                                   const void* v, const void* q, float* out, const void* beacon_k,
                                   const void* beacon_v, const uint8_t* active, void* workspace,
                                   size_t workspace_bytes, void* stream) {
-  int32_t st = bc_append_kv(shape, cache, k, v, active, BC_ROW_TOKEN, stream);
+  DecodePlan pl;
+  int32_t st = check_attention_args(shape, cache, q, out, workspace, workspace_bytes, &pl);
   if (st != BC_OK) return st;
-  st = bc_decode_attn(shape, cache, q, out, active, workspace, workspace_bytes, stream);
+  if (!k || !v || !aligned16(k) || !aligned16(v)) return BC_ERR_ARG;
+  if ((beacon_k == nullptr) != (beacon_v == nullptr)) return BC_ERR_ARG;
+  if (beacon_k && (!aligned16(beacon_k) || !aligned16(beacon_v))) return BC_ERR_ARG;
+  if (pl.lds)     // one launch: append, attention and eviction fused
+    return launch_attention(shape, cache, pl, q, out, active, workspace, k, v, beacon_k, beacon_v,
+                            as_stream(stream));
+  st = bc_append_kv(shape, cache, k, v, active, BC_ROW_TOKEN, stream);
   if (st != BC_OK) return st;
-  if (beacon_k || beacon_v)
-    st = bc_compress_evict(shape, cache, beacon_k, beacon_v, active, 1, stream);
+  st = launch_attention(shape, cache, pl, q, out, active, workspace, nullptr, nullptr, nullptr,
+                        nullptr, as_stream(stream));
+  if (st != BC_OK) return st;
+  if (beacon_k) st = bc_compress_evict(shape, cache, beacon_k, beacon_v, active, 1, stream);
   return st;
 }

@@ -81,7 +81,8 @@ def rollout(wl, rt, oc, steps, attn_steps, slab_steps, table_every=1, tail_form=
             o = rt.decode_step(k, v, q, bk, bv, active=act)
             oc.append(k, v, active=act)
             if need_attn:
-                worst = max(worst, check_attention(o.cpu().numpy(), q, oc, wl, seq_sample, t))
+                seqs = [s for s in (range(wl.B) if seq_sample is None else seq_sample) if active[s]]
+                worst = max(worst, check_attention(o.cpu().numpy(), q, oc, wl, seqs, t))
             oc.compress_evict(bk, bv, active=act)
         else:
             rt.append_kv(k, v, active=act)
@@ -138,6 +139,28 @@ def test_config1_fused_step_call(dev):
     rollout(wl, rt, oc, 64, range(1, 65), (16, 17, 64), use_step_call=True)
 
 
+@pytest.mark.parametrize("c,P", [(16, 256), (1, 5), (2, 0), (3, 31), (0, 40)])
+def test_fused_step_bf16_every_step(dev, c, P):
+    # bc_decode_step on the single-launch path (bf16, d = 128): tables, slabs, outputs each step
+    wl = W.Workload("fused", 70 + c, 6, 12, 2, 128, "bf16", np.full(6, P, np.int32),
+                    np.array([150, 150, 90, 150, 33, 150], np.int32), np.full(6, c, np.int32))
+    rt, oc = make(wl, dev)
+    steps = range(1, 151)
+    rollout(wl, rt, oc, 150, steps, steps, use_step_call=True)
+
+
+def test_fused_step_ragged_ratios_and_errors(dev):
+    c = np.array([1, 2, 4, 8, 16, 32, 0, 3], np.int32)
+    wl = W.Workload("fusedr", 80, 8, 12, 2, 128, "bf16",
+                    np.array([0, 1, 31, 32, 33, 64, 7, 100], np.int32), np.full(8, 200, np.int32), c)
+    cap = wl.capacity()
+    cap[3] = 32 + 5            # sequence 3 runs out of slab: capacity bit, then untouched
+    rt, oc = make(wl, dev, cap)
+    steps = range(1, 201)
+    rollout(wl, rt, oc, 200, steps, (1, 2, 3, 50, 200), use_step_call=True)
+    assert oc.err == ERR_CAPACITY
+
+
 @pytest.mark.parametrize("c", [16, 0])
 def test_config2_batch64_full_rollout(dev, c):
     wl = W.batch64(c=c)
@@ -146,7 +169,8 @@ def test_config2_batch64_full_rollout(dev, c):
     sample = sorted(set([1, 2, 15, 16, 17, 31, 32, 33, 255, 256, 257, 1000, 2047, 2048, 4095, 4096])
                     | set(int(x) for x in rng.integers(1, 4097, size=48)))
     seqs = [0, 1, 31, 63] + [int(x) for x in rng.integers(0, 64, size=4)]
-    worst = rollout(wl, rt, oc, 4096, sample, (16, 17, 1000, 4096), table_every=1, seq_sample=seqs)
+    worst = rollout(wl, rt, oc, 4096, sample, (16, 17, 1000, 4096), table_every=1, seq_sample=seqs,
+                    use_step_call=(c > 0))
     nb, w, _ = rt.tables()
     if c > 0:
         assert int(nb[0]) == 256 and int(w[0]) == 0          # 256 + 256 + 0 = 512 rows resident
