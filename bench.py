@@ -191,9 +191,8 @@ def main():
     total_bytes = sum(step_bytes) * NL
     value = total_bytes / elapsed / 1e9
 
-    # --- dominant kernel: bc_decode_attn launch durations by HIP events, same stream ----------
-    # Fresh pass over the same token range of the rollout with the three calls issued separately
-    # so that an event pair brackets the attention launch alone.
+    # --- dominant kernel: the fused step kernel (append + attention + eviction in one launch),
+    # timed by HIP event pairs on the launch stream, over the same token range of the rollout.
     n_samp = 0
     samp_bytes = 0
     samp_ms = 0.0
@@ -208,21 +207,18 @@ def main():
         stride = max(1, n_tok // 256)
         pairs = []
         for j in range(n_tok):
-            t = tok_first + j
             for li, rt in enumerate(layers):
                 x = pool[(j * NL + li) % n_pool]
-                rt.append_kv(x["k"], x["v"])
-                if j % stride == 0 and li == (j // stride) % NL:
+                sampled = j % stride == 0 and li == (j // stride) % NL
+                if sampled:
                     e0 = torch.cuda.Event(enable_timing=True)
                     e1 = torch.cuda.Event(enable_timing=True)
                     e0.record(stream)
-                    rt.decode_attn(x["q"])
+                rt.decode_step(x["k"], x["v"], x["q"], x["bk"] if c > 0 else None,
+                               x["bv"] if c > 0 else None)
+                if sampled:
                     e1.record(stream)
                     pairs.append((e0, e1, step_bytes[j]))
-                else:
-                    rt.decode_attn(x["q"])
-                if c > 0:
-                    rt.compress_evict(x["bk"], x["bv"])
         stream.synchronize()
     for e0, e1, nbytes in pairs:
         samp_ms += e0.elapsed_time(e1)
@@ -241,9 +237,9 @@ def main():
         "config": {"workload": "batch64 rollout: B=64, Hq=12, Hkv=2, d=128, bf16, P=256, G=4096, c=%s; "
                                "tokens %d..%d of the rollout" % (c if c > 0 else "inf", tok_first, t_end),
                    "layers_round_robin": NL, "hip_graph": bool(use_graph),
-                   "step": "append_kv + decode_attn + compress_evict for one layer",
+                   "step": "bc_decode_step for one layer: append_kv + decode_attn + compress_evict, one launch",
                    "kv_bytes_per_step_mean": int(np.mean(step_bytes))},
-        "roofline": {"bound": "hbm", "kernel": "bc::decode_kernel (bc_decode_attn)",
+        "roofline": {"bound": "hbm", "kernel": "bc::decode_lds_kernel (bc_decode_step: append + attention + eviction)",
                      "achieved": round(achieved, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
                      "avg_launch_us": round(samp_ms * 1e3 / max(n_samp, 1), 3),

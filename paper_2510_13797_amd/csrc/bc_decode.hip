@@ -43,6 +43,7 @@ struct DecodeParams {
   const char* bk;
   const char* bv;
   int32_t* tickets;    // [B], zero between launches
+  int32_t debug_stage; // experiments only: leave the kernel early (0 = run everything)
   int32_t Hq, Hkv, g;  // g = real group size
   int32_t Gp;          // padded group size of the partial layout
   int32_t D;
@@ -161,8 +162,10 @@ __device__ __forceinline__ uint32_t bf16_rne_bits(float x) {     // finite x onl
 
 __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams p) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
+  if (p.debug_stage == 1) return;
   const PairInfo pi = pair_info(p);
   if (!pi.live) return;
+  if (p.debug_stage == 2) { if (pi.L == 12345678) p.out[0] = 1.f; return; }
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, kb = lane >> 4;       // MFMA column / k-block of this lane
@@ -198,24 +201,53 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
   for (int j = 0; j < 8; ++j) O[j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
   float m_run = kNegBig, l_run = 0.f;
 
+  // Tiles wave, wave + 8, ... of the chunk belong to this wave.  The first goes from HBM to
+  // LDS by LDS-DMA; the second is requested at the same time into registers, so both are in
+  // flight from the start.  Afterwards: copy the register tile to LDS, request the next tile
+  // into the freed registers, compute - one tile always in flight behind the one in use.
   const int ntiles = (pi.row_end - pi.row0 + kTileRows - 1) / kTileRows;
+  const int r4 = lane >> 4, pos = lane & 15;
+  uint4 kreg[8], vreg[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) kreg[j] = vreg[j] = make_uint4(0u, 0u, 0u, 0u);
+#define BC_LOAD_TILE_REGS(TROW0)                                              \
+  _Pragma("unroll") for (int j = 0; j < 8; ++j) {                             \
+    const int grow_ = min((TROW0) + 4 * j + r4, last_slab_row);               \
+    const int64_t goff_ = (int64_t)grow_ * 256 + (pos << 4);                  \
+    kreg[j] = *reinterpret_cast<const uint4*>(kbase + goff_);                 \
+    vreg[j] = *reinterpret_cast<const uint4*>(vbase + goff_);                 \
+  }
+  if (wave < ntiles) {
+    // ---- HBM -> LDS: 8 + 8 instructions, each 4 whole rows (1 KB), 16-byte units XOR-swizzled
+    const int trow0 = pi.row0 + wave * kTileRows;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int row = 4 * j + r4;
+      const int grow = min(trow0 + row, last_slab_row);     // stay inside the slab rows
+      const int64_t goff = (int64_t)grow * 256 + ((pos ^ (row & 15)) << 4);
+      __builtin_amdgcn_global_load_lds((global_void_t*)(kbase + goff),
+                                       (lds_void_t*)(wk + j * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((global_void_t*)(vbase + goff),
+                                       (lds_void_t*)(wv + j * 1024), 16, 0, 0);
+    }
+    if (wave + kLdsWaves < ntiles) { BC_LOAD_TILE_REGS(trow0 + kLdsWaves * kTileRows) }
+  }
   for (int tile = wave; tile < ntiles; tile += kLdsWaves) {
     const int trow0 = pi.row0 + tile * kTileRows;
-    // ---- HBM -> LDS: 8 + 8 instructions, each 4 whole rows (1 KB), 16-byte units XOR-swizzled
-    {
-      const int r4 = lane >> 4, pos = lane & 15;
+    if (tile == wave) {
+      if (wave + kLdsWaves < ntiles) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+      else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    } else {
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         const int row = 4 * j + r4;
-        const int grow = min(trow0 + row, last_slab_row);     // stay inside the slab rows
-        const int64_t goff = (int64_t)grow * 256 + ((pos ^ (row & 15)) << 4);
-        __builtin_amdgcn_global_load_lds((global_void_t*)(kbase + goff),
-                                         (lds_void_t*)(wk + j * 1024), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((global_void_t*)(vbase + goff),
-                                         (lds_void_t*)(wv + j * 1024), 16, 0, 0);
+        const int o = row * 256 + ((pos ^ (row & 15)) << 4);
+        *reinterpret_cast<uint4*>(wk + o) = kreg[j];
+        *reinterpret_cast<uint4*>(wv + o) = vreg[j];
       }
+      if (tile + kLdsWaves < ntiles) { BC_LOAD_TILE_REGS(trow0 + kLdsWaves * kTileRows) }
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (p.debug_stage == 3) continue;
 
     if (pi.new_row >= trow0 && pi.new_row < trow0 + kTileRows) {
       // the appended row is not in the slab yet: place it in the tile, store it for later
@@ -305,15 +337,27 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
     }
   }
 
+  if (p.debug_stage == 3 || p.debug_stage == 4) { if (m_run == 123.f) p.out[0] = l_run + O[0][0]; return; }
+#undef BC_LOAD_TILE_REGS
   // denominators: sum the four k-blocks of each head
   l_run += __shfl_xor(l_run, 16, 64);
   l_run += __shfl_xor(l_run, 32, 64);
 
   // ---- merge the waves through LDS (the tile regions are free once everyone is here)
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // this wave's slab store has landed
   __syncthreads();
+  // fused step: every workgroup of the sequence takes a ticket once it has stopped reading
+  // the slab; the answer is only needed at the very end, so its latency hides behind the merge
+  int ticket = 0;
+  if (pi.update && tid == 0) {
+    const int one = 1;
+    asm volatile("global_atomic_add %0, %1, %2, off sc0"
+                 : "=v"(ticket) : "v"(p.tickets + pi.s), "v"(one) : "memory");
+  }
   float* s_acc = reinterpret_cast<float*>(lds);                    // [wave][8][128]
   float* s_m = s_acc + kLdsWaves * 8 * 128;                        // [wave][8]
   float* s_l = s_m + kLdsWaves * 8;
+  int* s_last = reinterpret_cast<int*>(s_l + kLdsWaves * 8);
   if (n < p.g) {
 #pragma unroll
     for (int j = 0; j < 8; ++j)
@@ -323,22 +367,18 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
   __syncthreads();
   merge_waves_and_store<kLdsWaves, 128>(p, pi, s_m, s_l, s_acc, 8);
 
-  // ---- fused step: the last workgroup of the sequence to get here (every other one has
-  //      finished reading the window) writes the beacon row and updates the tables
-  if (!pi.update) return;
-  __shared__ int s_last;
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();
+  // ---- the last workgroup of the sequence writes the beacon row and updates the tables
+  if (!pi.update || p.debug_stage == 5) return;
   if (tid == 0) {
-    const int old = atomicAdd(p.tickets + pi.s, 1);
-    s_last = (old == p.Hkv * pi.nchunks - 1) ? 1 : 0;
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(ticket) : : "memory");   // the ticket has arrived
+    *s_last = (ticket == p.Hkv * pi.nchunks - 1) ? 1 : 0;
   }
   __syncthreads();
-  if (!s_last) return;
+  if (!*s_last) return;
   if (pi.evict_due) {
-    const int n = p.Hkv * 16;                      // 16-byte units of one K (or V) entry
-    for (int i = tid; i < 2 * n; i += kLdsWaves * 64) {
-      const int which = i >= n, r = which ? i - n : i;
+    const int n16 = p.Hkv * 16;                    // 16-byte units of one K (or V) entry
+    for (int i = tid; i < 2 * n16; i += kLdsWaves * 64) {
+      const int which = i >= n16, r = which ? i - n16 : i;
       const int h = r >> 4, u = r & 15;
       const char* src = (which ? p.bv : p.bk) + (int64_t)(pi.s * p.Hkv + h) * 256 + (u << 4);
       char* slab = const_cast<char*>(which ? p.v_slab : p.k_slab);
@@ -630,6 +670,7 @@ static int32_t launch_attention(const bc_shape* shape, const bc_cache* cache, co
   p.rows_per_wg = pl.R;
   p.max_chunks = pl.max_chunks;
   p.qscale = shape->scale * kLog2e;
+  p.debug_stage = g_variant >= 10 ? g_variant - 10 : 0;
 
   const int pairs = shape->B * shape->Hkv;
   const dim3 grid(pl.max_chunks, pairs);
