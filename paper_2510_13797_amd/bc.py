@@ -303,3 +303,28 @@ class Runtime:
             blk = slab[lo:lo + cap * E].view(self.Hkv, cap, self.d)[:, :L, :]
             out.append(blk.permute(1, 0, 2).float().cpu().numpy())
         return out[0], out[1]
+
+
+def prefill_attn(q, k, v, row_offsets, P, c, Hq, Hkv, d, scale, want_lse=True):
+    """bc_prefill_attn on device tensors.
+
+    q [R, Hq, d], k, v [R, Hkv, d] bf16 device tensors (trajectories concatenated);
+    row_offsets [B+1] int64, P, c [B] int32 (host arrays).  Returns (out fp32 [R,Hq,d], lse or None).
+    """
+    import torch
+    load()
+    dev = q.device
+    row_offsets = np.asarray(row_offsets, dtype=np.int64)
+    B = len(row_offsets) - 1
+    shape = bc_shape(B, Hq, Hkv, d, BC_BF16, float(scale))
+    offd = torch.from_numpy(row_offsets).to(dev)
+    Pd = torch.from_numpy(np.asarray(P, dtype=np.int32)).to(dev)
+    cd = torch.from_numpy(np.asarray(c, dtype=np.int32)).to(dev)
+    R = int(row_offsets[-1])
+    out = torch.empty(R, Hq, d, dtype=torch.float32, device=dev)
+    lse = torch.empty(R, Hq, dtype=torch.float32, device=dev) if want_lse else None
+    max_rows = int(np.diff(row_offsets).max())
+    _check(bc_prefill_attn(shape, _ptr(q), _ptr(k), _ptr(v), _ptr(offd), _ptr(Pd), _ptr(cd), max_rows,
+                           _ptr(out), _ptr(lse), _stream_ptr()))
+    torch.cuda.current_stream().synchronize()      # offd/Pd/cd may be freed after this
+    return out, lse

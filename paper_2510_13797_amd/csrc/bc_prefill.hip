@@ -1,9 +1,314 @@
-// bc_prefill_attn: beacon-masked prefill attention (Fig. 2, Sec. 3.2).  Placeholder until the
-// MFMA kernel lands: reports the shape as unsupported instead of computing anything.
+// bc_prefill_attn: beacon-masked prefill attention, forward (Fig. 2, Sec. 3.2 of the paper).
+//
+// Training keeps every row and hides what eviction would have removed.  Seen from a tile of
+// 64 query rows that lies in the response, the visible keys are three runs:
+//   A  the prompt rows                                   (dense, nothing masked)
+//   B  the beacons of every window that ended before the tile's first window
+//      (one row every c+1 rows: a strided gather,         dense, nothing masked)
+//   C  the band from the start of the tile's first window to the tile's last row
+//      (block-diagonal windows plus the beacons inside:   masked by integer arithmetic)
+// so the kernel walks a compacted key list of about P + r/(c+1) + 64 + c rows per tile
+// instead of the r rows of causal attention, and never materialises a mask.  Tiles that
+// touch the prompt use run C alone with the same predicate (which is then plain causal).
+//
+// One workgroup = 64 query rows x all query heads of one KV head, 8 waves: wave (tg, hh)
+// owns 16 rows x half of the heads.  K/V tiles of 32 keys are gathered from HBM into LDS by
+// 16-byte LDS-DMA loads (double buffered, each row 256 contiguous bytes), shared by the 8
+// waves and fed to 16x16x32 bf16 MFMA: S^T = K.Q^T, O^T += V^T.P^T with P split into two
+// bf16 parts so that the softmax weights keep about 16 bits.  Softmax runs online in
+// registers in the accumulator layout.  The output tile goes through LDS so that every
+// row of 512 bytes is written to HBM as one burst.
 #include "bc_common.h"
 
-extern "C" int32_t bc_prefill_attn(const bc_shape*, const void*, const void*, const void*,
-                                   const int64_t*, const int32_t*, const int32_t*, int32_t, float*,
-                                   float*, void*) {
-  return BC_ERR_SHAPE;
+namespace bc {
+
+constexpr int kPfWaves = 8;
+constexpr int kPfBM = 64;                 // query rows per workgroup
+constexpr int kPfBN = 32;                 // keys per tile
+constexpr int kPfTile = kPfBN * 256;      // bytes of one K (or V) tile
+constexpr int kPfLds = 65536;
+
+typedef __attribute__((address_space(3))) void pf_lds_void_t;
+typedef __attribute__((address_space(1))) const void pf_global_void_t;
+typedef __attribute__((ext_vector_type(4))) short pf_s16x4_t;
+typedef __attribute__((ext_vector_type(8))) short pf_s16x8_t;
+typedef __attribute__((address_space(3))) pf_s16x4_t pf_lds_s16x4_t;
+typedef __attribute__((ext_vector_type(2))) float pf_f32x2_t;
+
+struct PrefillParams {
+  const char* q;
+  const char* k;
+  const char* v;
+  const int64_t* row_off;
+  const int32_t* P;
+  const int32_t* c;
+  float* out;
+  float* lse;
+  int32_t Hq, Hkv, g;
+  float qscale;       // softmax scale * log2(e)
+};
+
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {      // RNE, a in the low half
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(pf_f32x2_t{a, b}, bf16x2_t));
+}
+
+template <int HPW>     // query heads per wave (the group's heads are split over two wave sets)
+__global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillParams p) {
+  __shared__ __attribute__((aligned(1024))) char lds[kPfLds];
+  const int b = blockIdx.z, kvh = blockIdx.y;
+  const int64_t off0 = p.row_off[b];
+  const int S = (int)(p.row_off[b + 1] - off0);
+  const int qt = gridDim.x - 1 - blockIdx.x;        // long tiles first
+  const int r0 = qt * kPfBM;
+  if (r0 >= S) return;
+  const int r1 = min(r0 + kPfBM - 1, S - 1);
+  const int P = p.P[b], c = p.c[b];
+  const int cp1 = c + 1;
+  const uint32_t magic = c > 0 ? (uint32_t)(0x100000000ull / (uint32_t)cp1) + 1u : 0u;   // n/(c+1), n < 2^26
+
+  // compacted key list of this tile
+  int nA = 0, nB = 0, band_start = 0;
+  if (c > 0 && r0 >= P) {
+    const int m0 = (int)__umulhi((uint32_t)(r0 - P), magic);
+    nA = P; nB = m0; band_start = P + m0 * cp1;
+  }
+  const int nC = r1 - band_start + 1;
+  const int TA = (nA + kPfBN - 1) / kPfBN, TB = (nB + kPfBN - 1) / kPfBN;
+  const int NT = TA + TB + (nC + kPfBN - 1) / kPfBN;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n = lane & 15, kb = lane >> 4;
+  const int tg = wave & 3, hh = wave >> 2;
+  const int64_t kv_row_bytes = (int64_t)p.Hkv * 256;
+  const char* kbase = p.k + (off0 * p.Hkv + kvh) * 256;
+  const char* vbase = p.v + (off0 * p.Hkv + kvh) * 256;
+
+  // actual row of entry rr of key tile kt; invalid entries point at a row that exists
+  auto key_row = [&](int kt, int rr, bool& valid) -> int {
+    int j;
+    if (kt < TA) { j = kt * kPfBN + rr; valid = j < nA; }
+    else if (kt < TA + TB) { const int m = (kt - TA) * kPfBN + rr; valid = m < nB; j = P + m * cp1 + c; }
+    else { const int x = (kt - TA - TB) * kPfBN + rr; valid = x < nC; j = band_start + x; }
+    return valid ? j : r1;
+  };
+  // HBM -> LDS gather of tile kt: this wave brings rows 4*wave .. 4*wave+3 of K and of V
+  auto issue_tile = [&](int kt, int stage) {
+    const int rr = 4 * wave + (lane >> 4), pos = lane & 15;
+    bool valid;
+    const int j = key_row(kt, rr, valid);
+    const int64_t goff = (int64_t)j * kv_row_bytes + ((pos ^ (rr & 15)) << 4);
+    char* dst = lds + stage * (2 * kPfTile) + wave * 1024;
+    __builtin_amdgcn_global_load_lds((pf_global_void_t*)(kbase + goff), (pf_lds_void_t*)dst, 16, 0, 0);
+    __builtin_amdgcn_global_load_lds((pf_global_void_t*)(vbase + goff),
+                                     (pf_lds_void_t*)(dst + kPfTile), 16, 0, 0);
+  };
+
+  issue_tile(0, 0);
+
+  // this lane's query row and heads; Q^T as the B operand (column n = row, k = head-dim index)
+  const int r = r0 + 16 * tg + n;
+  const bool row_ok = r <= r1;
+  const int rq = row_ok ? r : r1;
+  bf16x8_t qb[HPW][4];
+#pragma unroll
+  for (int h = 0; h < HPW; ++h) {
+    const int head = hh * HPW + h;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      uint4 x = make_uint4(0u, 0u, 0u, 0u);
+      if (head < p.g)
+        x = *reinterpret_cast<const uint4*>(
+            p.q + (((off0 + rq) * p.Hq + kvh * p.g + head) * 128 + 32 * i + 8 * kb) * 2);
+      qb[h][i] = __builtin_bit_cast(bf16x8_t, x);
+    }
+  }
+  const int win_r = (c > 0 && r >= P) ? (int)__umulhi((uint32_t)(r - P), magic) : -1;
+
+  f32x4_t O[HPW][8];
+  float m_run[HPW], l_run[HPW];
+#pragma unroll
+  for (int h = 0; h < HPW; ++h) {
+    m_run[h] = kNegBig; l_run[h] = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) O[h][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  }
+
+  for (int kt = 0; kt < NT; ++kt) {
+    const int stage = kt & 1;
+    if (kt + 1 < NT) {
+      issue_tile(kt + 1, stage ^ 1);
+      asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+    } else {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    __syncthreads();
+    const char* tk = lds + stage * (2 * kPfTile);
+    const char* tv = tk + kPfTile;
+
+    // which of this lane's 8 keys (tile rows 8*kb + e) may its query row see?
+    bool vis[8];
+    {
+      const bool predicate = kt >= TA + TB;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        bool valid;
+        const int j = key_row(kt, 8 * kb + e, valid);
+        bool ok = valid && row_ok;
+        if (predicate) {
+          bool see = j < P || c <= 0;
+          if (!see) {
+            const uint32_t u = (uint32_t)(j - P);
+            const uint32_t qd = __umulhi(u, magic);
+            see = (int)(u - qd * (uint32_t)cp1) == c || (int)qd == win_r;
+          }
+          ok = ok && j <= r && see;
+        }
+        vis[e] = ok;
+      }
+    }
+
+    // S^T = K . Q^T ; row m of sub-tile t is tile row 8*(m/4) + 4*t + m%4
+    bf16x8_t ka[2][4];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int row = ((n >> 2) << 3) + 4 * t + (n & 3);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        ka[t][i] = *reinterpret_cast<const bf16x8_t*>(tk + row * 256 + (((4 * i + kb) ^ (row & 15)) << 4));
+    }
+    bf16x8_t phi[HPW], plo[HPW];
+    float alpha[HPW];
+    bool any_rescale = false;
+#pragma unroll
+    for (int h = 0; h < HPW; ++h) {
+      f32x4_t Sx[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        Sx[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          Sx[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[t][i], qb[h][i], Sx[t], 0, 0, 0);
+      }
+      float sv[8];
+      float tmax = kNegBig;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        sv[e] = vis[e] ? Sx[e >> 2][e & 3] * p.qscale : kNegBig;
+        tmax = fmaxf(tmax, sv[e]);
+      }
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+      const float m_new = fmaxf(m_run[h], tmax);
+      alpha[h] = fast_exp2(m_run[h] - m_new);
+      any_rescale = any_rescale || (m_new != m_run[h]);
+      m_run[h] = m_new;
+      float psum = 0.f;
+      uint32_t hi[4], lo[4];
+#pragma unroll
+      for (int e = 0; e < 8; e += 2) {
+        const float pa = vis[e] ? fast_exp2(sv[e] - m_new) : 0.f;
+        const float pb = vis[e + 1] ? fast_exp2(sv[e + 1] - m_new) : 0.f;
+        psum += pa + pb;
+        const uint32_t hp = pack_bf16(pa, pb);
+        hi[e >> 1] = hp;
+        lo[e >> 1] = pack_bf16(pa - __uint_as_float(hp << 16), pb - __uint_as_float(hp & 0xffff0000u));
+      }
+      l_run[h] = l_run[h] * alpha[h] + psum;
+      phi[h] = __builtin_bit_cast(bf16x8_t, make_uint4(hi[0], hi[1], hi[2], hi[3]));
+      plo[h] = __builtin_bit_cast(bf16x8_t, make_uint4(lo[0], lo[1], lo[2], lo[3]));
+    }
+    if (__any(any_rescale)) {
+#pragma unroll
+      for (int h = 0; h < HPW; ++h)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) O[h][j] *= alpha[h];
+    }
+
+    // O^T += V^T . P^T ; V^T through the transposing LDS read
+    {
+      const int rl = lane & 15;
+      const int rowa = 8 * kb + (rl >> 2), rowb = rowa + 4;
+      const int sub = (rl & 1) << 3;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int u = 2 * j + ((rl & 3) >> 1);
+        const pf_s16x4_t a0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (pf_lds_s16x4_t*)(tv + rowa * 256 + ((u ^ (rowa & 15)) << 4) + sub));
+        const pf_s16x4_t a1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (pf_lds_s16x4_t*)(tv + rowb * 256 + ((u ^ (rowb & 15)) << 4) + sub));
+        const bf16x8_t av = __builtin_bit_cast(
+            bf16x8_t, (pf_s16x8_t)__builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7));
+#pragma unroll
+        for (int h = 0; h < HPW; ++h) {
+          O[h][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, phi[h], O[h][j], 0, 0, 0);
+          O[h][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, plo[h], O[h][j], 0, 0, 0);
+        }
+      }
+    }
+    __syncthreads();        // everyone is done with this stage before it is refilled
+  }
+
+  // ---- epilogue: normalise, transpose through LDS, write each 512-byte row as one burst
+  float* my = reinterpret_cast<float*>(lds + wave * 8192);        // [16 rows][128] fp32, swizzled
+#pragma unroll
+  for (int h = 0; h < HPW; ++h) {
+    const int head = hh * HPW + h;
+    float l = l_run[h];
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+    const float inv = 1.0f / l;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int unit = (4 * j + kb) ^ n;                // 16-byte units of a 512-byte row
+      *reinterpret_cast<f32x4_t*>(my + n * 128 + unit * 4) = O[h][j] * inv;
+    }
+    if (head < p.g) {
+      // 32 lanes cover one row (16 bytes each), two rows per pass
+#pragma unroll
+      for (int pass = 0; pass < 8; ++pass) {
+        const int t = 2 * pass + (lane >> 5), unit = lane & 31;
+        const f32x4_t val = *reinterpret_cast<const f32x4_t*>(my + t * 128 + ((unit ^ t) << 2));
+        const int rr = r0 + 16 * tg + t;
+        if (rr <= r1)
+          *reinterpret_cast<f32x4_t*>(
+              p.out + ((off0 + rr) * p.Hq + kvh * p.g + head) * 128 + unit * 4) = val;
+      }
+      if (p.lse && kb == 0 && row_ok)
+        p.lse[(off0 + r) * p.Hq + kvh * p.g + head] = (m_run[h] + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
+    }
+  }
+}
+
+}  // namespace bc
+
+using namespace bc;
+
+extern "C" int32_t bc_prefill_attn(const bc_shape* shape, const void* q, const void* k,
+                                   const void* v, const int64_t* row_offsets, const int32_t* P,
+                                   const int32_t* c, int32_t max_rows, float* out, float* lse,
+                                   void* stream) {
+  int32_t st = check_shape(shape);
+  if (st != BC_OK) return st;
+  if (shape->kv_dtype != BC_BF16 || shape->d != 128) return BC_ERR_SHAPE;
+  if (!q || !k || !v || !row_offsets || !P || !c || !out) return BC_ERR_ARG;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return BC_ERR_ARG;
+  if (max_rows < 1 || max_rows >= (1 << 26)) return BC_ERR_ARG;
+  PrefillParams p;
+  p.q = static_cast<const char*>(q);
+  p.k = static_cast<const char*>(k);
+  p.v = static_cast<const char*>(v);
+  p.row_off = row_offsets; p.P = P; p.c = c;
+  p.out = out; p.lse = lse;
+  p.Hq = shape->Hq; p.Hkv = shape->Hkv; p.g = shape->Hq / shape->Hkv;
+  p.qscale = shape->scale * kLog2e;
+  const dim3 grid((max_rows + kPfBM - 1) / kPfBM, shape->Hkv, shape->B);
+  hipStream_t hs = as_stream(stream);
+  const int hpw = (p.g + 1) / 2;
+  switch (hpw) {
+    case 1: prefill_kernel<1><<<grid, kPfWaves * 64, 0, hs>>>(p); break;
+    case 2: prefill_kernel<2><<<grid, kPfWaves * 64, 0, hs>>>(p); break;
+    case 3: prefill_kernel<3><<<grid, kPfWaves * 64, 0, hs>>>(p); break;
+    default: prefill_kernel<4><<<grid, kPfWaves * 64, 0, hs>>>(p); break;
+  }
+  return launch_status();
 }

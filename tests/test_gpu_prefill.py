@@ -1,0 +1,134 @@
+"""GPU parity: bc_prefill_attn (beacon-masked prefill attention, forward) against the dense
+masked-attention oracle, and against bc_decode_attn over the evicted cache (training-time
+masking simulates the eviction).  bf16 inputs, fp32 accumulation: max-abs-error 2e-3."""
+import numpy as np
+import pytest
+
+from oracle import attention as OA
+from paper_2510_13797_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-3
+
+
+@pytest.fixture(scope="module")
+def dev():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return torch.device("cuda:0")
+
+
+def _run(pw, dev, want_lse=True):
+    from paper_2510_13797_amd import bc
+    bc.load()
+    qkv = [pw.qkv(b) for b in range(pw.B)]
+    off = np.zeros(pw.B + 1, np.int64)
+    off[1:] = np.cumsum(pw.S)
+    q = bc.to_device(np.concatenate([x[0] for x in qkv]), "bf16", dev)
+    k = bc.to_device(np.concatenate([x[1] for x in qkv]), "bf16", dev)
+    v = bc.to_device(np.concatenate([x[2] for x in qkv]), "bf16", dev)
+    out, lse = bc.prefill_attn(q, k, v, off, pw.P, pw.c, pw.Hq, pw.Hkv, pw.d, pw.scale, want_lse)
+    return qkv, off, out.cpu().numpy(), None if lse is None else lse.cpu().numpy()
+
+
+def _check_rows(pw, qkv, off, out, lse, b, rows):
+    q, k, v = qkv[b]
+    ref, ref_lse = OA.masked_prefill_attention(q, k, v, int(pw.P[b]), int(pw.c[b]), pw.scale, rows=rows)
+    got = out[off[b] + np.asarray(rows)]
+    err = float(np.abs(got - ref).max())
+    assert err <= TOL, (b, err)
+    if lse is not None:
+        lerr = float(np.abs(lse[off[b] + np.asarray(rows)] - ref_lse).max())
+        assert lerr <= 1e-3, (b, lerr)
+    return err
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(12, 2), (4, 1), (8, 8), (2, 2)])
+def test_prefill_small_ragged_all_rows(dev, Hq, Hkv):
+    pw = W.PrefillWorkload("pf_small", 50 + Hq, 6, Hq, Hkv, 128, "bf16",
+                           np.array([0, 5, 64, 70, 33, 200], np.int32),      # prompt rows
+                           np.array([150, 64, 1, 130, 97, 0], np.int32),     # response tokens
+                           np.array([16, 2, 4, 0, 1, 16], np.int32))         # c (0: plain causal)
+    qkv, off, out, lse = _run(pw, dev)
+    assert np.isfinite(out).all()
+    for b in range(pw.B):
+        _check_rows(pw, qkv, off, out, lse, b, list(range(int(pw.S[b]))))
+
+
+def test_prefill_ratios_and_long_beacon_runs(dev):
+    # many beacons (several gathered beacon tiles) and every ratio the paper uses
+    pw = W.PrefillWorkload("pf_ratios", 61, 5, 12, 2, 128, "bf16", np.array([3, 40, 128, 7, 256], np.int32),
+                           np.array([700, 900, 1000, 1100, 1200], np.int32),
+                           np.array([2, 4, 8, 16, 32], np.int32))
+    qkv, off, out, lse = _run(pw, dev)
+    rng = np.random.default_rng(0)
+    for b in range(pw.B):
+        S = int(pw.S[b])
+        rows = sorted(set([0, 1, S - 1, S - 2, int(pw.P[b]), max(int(pw.P[b]) - 1, 0)])
+                      | set(int(x) for x in rng.integers(0, S, size=150)))
+        _check_rows(pw, qkv, off, out, lse, b, rows)
+
+
+def test_config5_full_size(dev):
+    pw = W.prefill_train()
+    assert int(pw.S[0]) == 8688
+    qkv, off, out, lse = _run(pw, dev)
+    assert np.isfinite(out).all()
+    rng = np.random.default_rng(1)
+    # a band of consecutive rows across tile and window borders, every beacon-tile border, and
+    # random rows of every trajectory
+    worst = _check_rows(pw, qkv, off, out, lse, 0, list(range(0, 400)) + list(range(8300, 8688)))
+    for b in range(pw.B):
+        rows = sorted(set(int(x) for x in rng.integers(0, 8688, size=120)))
+        worst = max(worst, _check_rows(pw, qkv, off, out, lse, b, rows))
+    print("config5 worst", worst)
+
+
+def test_prefill_rows_equal_decode_over_evicted_cache(dev):
+    # Sec. 3.2: masking simulates eviction.  Feed the same q/k/v through the decode path
+    # (append, attend, beacon append at the tail, attend with the beacon's query, evict) and
+    # compare every row with the prefill output.
+    from paper_2510_13797_amd import bc
+    P, c, R = 37, 8, 475
+    pw = W.PrefillWorkload("pf_eq", 62, 2, 12, 2, 128, "bf16", np.full(2, P, np.int32),
+                           np.full(2, R, np.int32), np.full(2, c, np.int32))
+    qkv, off, out, _ = _run(pw, dev, want_lse=False)
+    S = int(pw.S[0])
+    assert S == P + R + R // c
+    B = pw.B
+    q = np.stack([x[0] for x in qkv]); k = np.stack([x[1] for x in qkv]); v = np.stack([x[2] for x in qkv])
+    cap = np.full(B, P + R // c + c + 1, np.int32)
+    rt = bc.Runtime(B, pw.Hq, pw.Hkv, pw.d, "bf16", pw.scale, pw.P, pw.c, cap, dev)
+    rt.cache_init([k[b, :P] for b in range(B)], [v[b, :P] for b in range(B)])
+    worst = 0.0
+    row = P
+    for t in range(1, R + 1):
+        rt.append_kv(k[:, row], v[:, row])
+        o = rt.decode_attn(q[:, row]).cpu().numpy()
+        for b in range(B):
+            worst = max(worst, float(np.abs(o[b] - out[off[b] + row]).max()))
+        row += 1
+        if t % c == 0:                                   # beacon row
+            rt.append_kv(k[:, row], v[:, row], kind=bc.BC_ROW_BEACON)
+            o = rt.decode_attn(q[:, row]).cpu().numpy()
+            for b in range(B):
+                worst = max(worst, float(np.abs(o[b] - out[off[b] + row]).max()))
+            rt.compress_evict()
+            row += 1
+    assert row == S
+    assert rt.tables()[2] == 0
+    assert worst <= TOL, worst
+    print("prefill vs decode worst", worst)
+
+
+def test_prefill_argument_errors(dev):
+    from paper_2510_13797_amd import bc
+    import ctypes as C
+    import torch
+    x = torch.zeros(64, dtype=torch.float32, device=dev)
+    p = C.c_void_p(x.data_ptr())
+    sh32 = bc.bc_shape(1, 4, 1, 128, bc.BC_F32, 0.1)
+    assert bc.bc_prefill_attn(sh32, p, p, p, p, p, p, 4, p, None, None) == -2      # bf16 only
+    sh = bc.bc_shape(1, 4, 1, 128, bc.BC_BF16, 0.1)
+    assert bc.bc_prefill_attn(sh, None, p, p, p, p, p, 4, p, None, None) == -1
+    assert bc.bc_prefill_attn(sh, p, p, p, p, p, p, 0, p, None, None) == -1
