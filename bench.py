@@ -28,6 +28,27 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0
 
 
+def stored_traffic():
+    """HBM bytes per launch of the decode kernel as measured by the committed rocprofv3 PMC runs
+    (FETCH_SIZE and WRITE_SIZE, each scaled by a plain copy of known size); None if absent.
+    bench.py cannot run the profiler around itself, so it reports the stored measurement."""
+    path = os.path.join(ROOT, "profiles", "decode_batch64_c16_hbm_traffic.txt")
+    try:
+        vals = {}
+        with open(path) as f:
+            for line in f:
+                line = line.split("#")[0]
+                if "=" in line:
+                    k, v = line.split("=")
+                    vals[k.strip()] = float(v)
+        return {"bytes_per_launch": int(vals["fetch_bytes_per_launch"] + vals["write_bytes_per_launch"]),
+                "algorithmic_bytes_per_launch": int(vals["algorithmic_kv_bytes_per_launch"]),
+                "ratio": vals["traffic_over_algorithmic"],
+                "source": "profiles/decode_batch64_c16_hbm_traffic.txt (tokens 3825..4096 of the rollout)"}
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def kv_bytes_per_step(wl, t):
     """Algorithmic K+V bytes decode attention reads at token-step t: every resident row once."""
     es = 2 if wl.dtype == "bf16" else 4
@@ -66,8 +87,97 @@ def cpu_baseline(wl, budget_s=12.0):
                       "fp64 NumPy oracle, %.1f s" % (steps, L, wl.B, wl.Hq, wall)}
 
 
+def visible_pairs(S, P, c):
+    """Number of (query row, visible key) pairs of one trajectory: sum over rows of |vis(r)|."""
+    r = np.arange(S, dtype=np.int64)
+    if c <= 0:
+        return int((r + 1).sum())
+    u = np.maximum(r - P, 0)
+    resp = P + u // (c + 1) + u % (c + 1) + 1
+    return int(np.where(r < P, r + 1, resp).sum())
+
+
+def bench_prefill(args):
+    """Config 5: beacon-masked prefill attention forward, B=16, 12/2 heads, d=128, bf16,
+    8192 tokens (256 prompt) + one beacon per 16 response tokens = 8688 rows per trajectory."""
+    import torch
+    from paper_2510_13797_amd import bc, workloads
+    bc.load()
+    dev = torch.device("cuda:0")
+    pw = workloads.prefill_train()
+    S = int(pw.S[0])
+    R = int(pw.S.sum())
+    off = np.zeros(pw.B + 1, np.int64)
+    off[1:] = np.cumsum(pw.S)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(workloads.BASE_SEED)
+    q = torch.randn(R, pw.Hq, pw.d, generator=gen, device=dev).to(torch.bfloat16)
+    k = torch.randn(R, pw.Hkv, pw.d, generator=gen, device=dev).to(torch.bfloat16)
+    v = torch.randn(R, pw.Hkv, pw.d, generator=gen, device=dev).to(torch.bfloat16)
+    shape = bc.bc_shape(pw.B, pw.Hq, pw.Hkv, pw.d, bc.BC_BF16, pw.scale)
+    offd = torch.from_numpy(off).to(dev)
+    Pd = torch.from_numpy(pw.P).to(dev)
+    cd = torch.from_numpy(pw.c).to(dev)
+    out = torch.empty(R, pw.Hq, pw.d, dtype=torch.float32, device=dev)
+    lse = torch.empty(R, pw.Hq, dtype=torch.float32, device=dev)
+    import ctypes as C
+    ptr = lambda t: C.c_void_p(t.data_ptr())
+    stream = torch.cuda.current_stream()
+
+    def step():
+        st = bc.bc_prefill_attn(shape, ptr(q), ptr(k), ptr(v), ptr(offd), ptr(Pd), ptr(cd), S, ptr(out),
+                                ptr(lse), C.c_void_p(stream.cuda_stream))
+        assert st == 0, st
+
+    W_ = args.warmup if args.warmup >= 0 else 3
+    K_ = args.steps if args.steps >= 0 else 20
+    for _ in range(W_):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    wall0 = time.perf_counter()
+    e0.record(stream)
+    for _ in range(K_):
+        step()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - wall0
+    ms = max(e0.elapsed_time(e1), wall * 1e3) / K_
+    assert torch.isfinite(out).all()
+    pairs = sum(visible_pairs(int(pw.S[b]), int(pw.P[b]), int(pw.c[b])) for b in range(pw.B))
+    flops = 4.0 * pw.d * pairs * pw.Hq               # q.k and p.v, 2 flop per multiply-add
+    tflops = flops / (ms * 1e-3) / 1e12
+    rec = {"metric": "prefill_attn_TFLOPs", "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1,
+           "steps": K_, "warmup": W_, "ms_per_step": round(ms, 4), "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": "beacon-masked prefill forward: B=16, Hq=12, Hkv=2, d=128, bf16, "
+                                  "8192 tokens (P=256) + 496 beacons = 8688 rows, c=16",
+                      "algorithmic_GFLOP": round(flops / 1e9, 1)},
+           "roofline": {"bound": "mfma", "kernel": "bc::prefill_kernel<3>", "achieved": round(tflops, 2),
+                        "peak": 2500.0, "unit": "TFLOP/s", "frac": round(tflops / 2500.0, 4),
+                        "traffic": None}}
+    print(json.dumps(rec))
+
+
+def bench_copy(args):
+    """Plain device copy of known size: calibrates the FETCH_SIZE / WRITE_SIZE counters."""
+    import torch
+    dev = torch.device("cuda:0")
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, device=dev).fill_(1)
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    reps = 8
+    for _ in range(reps):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    print(json.dumps({"workload": "copy", "bytes_read_per_copy": n, "bytes_written_per_copy": n,
+                      "copies": reps}))
+
+
 def main():
     ap = argparse.ArgumentParser()
+    ap.add_argument("--workload", default="decode", choices=["decode", "prefill", "copy"])
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=-1)
     ap.add_argument("--warmup", type=int, default=-1)
@@ -88,6 +198,10 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.workload == "prefill":
+        return bench_prefill(args)
+    if args.workload == "copy":
+        return bench_copy(args)
     if args.rows_per_wg:
         bc.bc_set_decode_tuning(args.rows_per_wg, 0)
 
@@ -225,6 +339,14 @@ def main():
         samp_bytes += nbytes
         n_samp += 1
     achieved = samp_bytes / (samp_ms / 1e3) / 1e9 if samp_ms > 0 else 0.0
+    avg_launch_us = samp_ms * 1e3 / max(n_samp, 1)
+    method = "HIP event pair around each of %d sampled launches (eager)" % n_samp
+    if use_graph:
+        # The timed region is K back-to-back launches of this one kernel and nothing else, so the
+        # region's own event pair gives the average launch duration without per-pair event cost.
+        avg_launch_us = gpu_ms * 1e3 / K
+        achieved = total_bytes / (gpu_ms / 1e3) / 1e9
+        method = "HIP events over the timed region / %d launches (graph replay, one kernel per step)" % K
 
     rec = {
         "metric": "decode_attn_kv_GBps", "value": round(value, 2), "unit": "GB/s",
@@ -241,10 +363,11 @@ def main():
                    "kv_bytes_per_step_mean": int(np.mean(step_bytes))},
         "roofline": {"bound": "hbm", "kernel": "bc::decode_lds_kernel (bc_decode_step: append + attention + eviction)",
                      "achieved": round(achieved, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
-                     "avg_launch_us": round(samp_ms * 1e3 / max(n_samp, 1), 3),
-                     "launches_sampled": n_samp,
-                     "bytes_per_launch_mean": int(samp_bytes / max(n_samp, 1))},
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": (stored_traffic() or {}).get("bytes_per_launch"),
+                     "traffic_detail": stored_traffic(),
+                     "avg_launch_us": round(avg_launch_us, 3), "method": method,
+                     "avg_launch_us_event_pairs_eager": round(samp_ms * 1e3 / max(n_samp, 1), 3),
+                     "bytes_per_launch_mean": int(total_bytes / K)},
     }
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(wl)
