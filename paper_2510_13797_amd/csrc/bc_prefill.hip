@@ -13,7 +13,7 @@
 //
 // One workgroup = 64 query rows x all query heads of one KV head, 8 waves: wave (tg, hh)
 // owns 16 rows x half of the heads.  K/V tiles of 32 keys are gathered from HBM into LDS by
-// 16-byte LDS-DMA loads (double buffered, each row 256 contiguous bytes), shared by the 8
+// 16-byte LDS-DMA loads (3-stage ring, one barrier per tile, each row 256 contiguous bytes), shared by the 8
 // waves and fed to 16x16x32 bf16 MFMA: S^T = K.Q^T, O^T += V^T.P^T with P split into two
 // bf16 parts so that the softmax weights keep about 16 bits.  Softmax runs online in
 // registers in the accumulator layout.  The output tile goes through LDS so that every
@@ -26,7 +26,8 @@ constexpr int kPfWaves = 8;
 constexpr int kPfBM = 64;                 // query rows per workgroup
 constexpr int kPfBN = 32;                 // keys per tile
 constexpr int kPfTile = kPfBN * 256;      // bytes of one K (or V) tile
-constexpr int kPfLds = 65536;
+constexpr int kPfStages = 3;
+constexpr int kPfLds = 65536;               // 3 stages of 16 KB in the loop, 8 x 8 KB in the epilogue
 
 typedef __attribute__((address_space(3))) void pf_lds_void_t;
 typedef __attribute__((address_space(1))) const void pf_global_void_t;
@@ -83,20 +84,29 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillParams p)
   const char* kbase = p.k + (off0 * p.Hkv + kvh) * 256;
   const char* vbase = p.v + (off0 * p.Hkv + kvh) * 256;
 
-  // actual row of entry rr of key tile kt; invalid entries point at a row that exists
-  auto key_row = [&](int kt, int rr, bool& valid) -> int {
-    int j;
-    if (kt < TA) { j = kt * kPfBN + rr; valid = j < nA; }
-    else if (kt < TA + TB) { const int m = (kt - TA) * kPfBN + rr; valid = m < nB; j = P + m * cp1 + c; }
-    else { const int x = (kt - TA - TB) * kPfBN + rr; valid = x < nC; j = band_start + x; }
-    return valid ? j : r1;
+  // Key tile kt covers 32 consecutive entries of one run.  Entry rr is row j0 + rr*step;
+  // entries at and beyond nvalid do not exist (their loads are redirected to row r1).
+  struct TileDesc { int j0, step, nvalid; bool predicate; };
+  auto tile_desc = [&](int kt) -> TileDesc {
+    TileDesc t;
+    if (kt < TA) { t.j0 = kt * kPfBN; t.step = 1; t.nvalid = nA - kt * kPfBN; t.predicate = false; }
+    else if (kt < TA + TB) {
+      const int m = (kt - TA) * kPfBN;
+      t.j0 = P + m * cp1 + c; t.step = cp1; t.nvalid = nB - m; t.predicate = false;
+    } else {
+      const int x = (kt - TA - TB) * kPfBN;
+      t.j0 = band_start + x; t.step = 1; t.nvalid = nC - x; t.predicate = true;
+    }
+    t.nvalid = min(t.nvalid, kPfBN);
+    return t;
   };
-  // HBM -> LDS gather of tile kt: this wave brings rows 4*wave .. 4*wave+3 of K and of V
+  // HBM -> LDS gather of tile kt: this wave brings entries 4*wave .. 4*wave+3 of K and of V
+  const int ld_rr = 4 * wave + (lane >> 4);
+  const int ld_unit = ((lane & 15) ^ (ld_rr & 15)) << 4;
   auto issue_tile = [&](int kt, int stage) {
-    const int rr = 4 * wave + (lane >> 4), pos = lane & 15;
-    bool valid;
-    const int j = key_row(kt, rr, valid);
-    const int64_t goff = (int64_t)j * kv_row_bytes + ((pos ^ (rr & 15)) << 4);
+    const TileDesc t = tile_desc(kt);
+    const int j = ld_rr < t.nvalid ? t.j0 + ld_rr * t.step : r1;
+    const int64_t goff = (int64_t)j * kv_row_bytes + ld_unit;
     char* dst = lds + stage * (2 * kPfTile) + wave * 1024;
     __builtin_amdgcn_global_load_lds((pf_global_void_t*)(kbase + goff), (pf_lds_void_t*)dst, 16, 0, 0);
     __builtin_amdgcn_global_load_lds((pf_global_void_t*)(vbase + goff),
@@ -104,6 +114,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillParams p)
   };
 
   issue_tile(0, 0);
+  if (NT > 1) issue_tile(1, 1);
 
   // this lane's query row and heads; Q^T as the B operand (column n = row, k = head-dim index)
   const int r = r0 + 16 * tg + n;
@@ -133,37 +144,37 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillParams p)
     for (int j = 0; j < 8; ++j) O[h][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
   }
 
+  int stage = 0;
   for (int kt = 0; kt < NT; ++kt) {
-    const int stage = kt & 1;
-    if (kt + 1 < NT) {
-      issue_tile(kt + 1, stage ^ 1);
-      asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
-    } else {
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    }
+    // tile kt has landed (this wave's part); after the barrier everyone's part has, and
+    // everyone has finished tile kt-1, whose stage is the one tile kt+2 goes into
+    if (kt + 1 < NT) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
+    if (kt + 2 < NT) issue_tile(kt + 2, stage >= 1 ? stage - 1 : kPfStages - 1);
     const char* tk = lds + stage * (2 * kPfTile);
     const char* tv = tk + kPfTile;
+    stage = stage + 1 == kPfStages ? 0 : stage + 1;
 
-    // which of this lane's 8 keys (tile rows 8*kb + e) may its query row see?
+    // which of this lane's 8 keys (tile entries 8*kb + e) may its query row see?
+    const TileDesc td = tile_desc(kt);
     bool vis[8];
     {
-      const bool predicate = kt >= TA + TB;
+      const int lim = row_ok ? td.nvalid - 8 * kb : 0;      // entries e < lim exist
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        bool valid;
-        const int j = key_row(kt, 8 * kb + e, valid);
-        bool ok = valid && row_ok;
-        if (predicate) {
+      for (int e = 0; e < 8; ++e) vis[e] = e < lim;
+      if (td.predicate) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int j = td.j0 + 8 * kb + e;
           bool see = j < P || c <= 0;
           if (!see) {
             const uint32_t u = (uint32_t)(j - P);
             const uint32_t qd = __umulhi(u, magic);
             see = (int)(u - qd * (uint32_t)cp1) == c || (int)qd == win_r;
           }
-          ok = ok && j <= r && see;
+          vis[e] = vis[e] && j <= r && see;
         }
-        vis[e] = ok;
       }
     }
 
@@ -245,8 +256,8 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillParams p)
         }
       }
     }
-    __syncthreads();        // everyone is done with this stage before it is refilled
   }
+  __syncthreads();          // the tile stages are free: the epilogue reuses LDS
 
   // ---- epilogue: normalise, transpose through LDS, write each 512-byte row as one burst
   float* my = reinterpret_cast<float*>(lds + wave * 8192);        // [16 rows][128] fp32, swizzled
