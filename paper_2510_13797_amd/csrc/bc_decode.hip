@@ -55,6 +55,7 @@ struct DecodeParams {
 struct PairInfo {
   int s, kvh, L, nchunks, chunk, row0, row_end;
   int P, nb, w_att, cap, c;   // tables as the attention of this launch sees them
+  int64_t base;               // first entry of the sequence in the slabs
   int new_row;                // slot of the row appended by this launch, or -1
   bool evict_due;             // this launch ends with beacon append + eviction
   bool update;                // tables change at the end of this launch
@@ -74,6 +75,7 @@ __device__ __forceinline__ PairInfo pair_info(const DecodeParams& p) {
   pi.nb = p.nb[pi.s];
   const int w = p.w[pi.s];
   pi.cap = p.cap[pi.s];
+  pi.base = p.base[pi.s];
   pi.c = p.c ? p.c[pi.s] : 0;
   const bool herald = blockIdx.x == 0 && pi.kvh == 0 && threadIdx.x == 0;   // reports errors
   pi.live = false;
@@ -134,7 +136,7 @@ __device__ __forceinline__ void merge_waves_and_store(const DecodeParams& p, con
       o += s_acc[(wv * gstride + h) * D + x] * a;
     }
     if (pi.nchunks == 1) {
-      outp[i] = o / lsum;
+      __builtin_nontemporal_store(o / lsum, outp + i);   // streamed out: nothing left dirty in L2
     } else {
       po[i] = o;
       if (x == 0) { pml[h] = mx; pml[p.Gp + h] = lsum; }
@@ -169,7 +171,7 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, kb = lane >> 4;       // MFMA column / k-block of this lane
-  const int64_t stream_off = (p.base[pi.s] * p.Hkv + (int64_t)pi.kvh * pi.cap) * 256;
+  const int64_t stream_off = (pi.base * p.Hkv + (int64_t)pi.kvh * pi.cap) * 256;
   const char* kbase = p.k_slab + stream_off;
   const char* vbase = p.v_slab + stream_off;
   char* wk = lds + wave * (2 * kTileBytes);
@@ -383,7 +385,7 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
       const char* src = (which ? p.bv : p.bk) + (int64_t)(pi.s * p.Hkv + h) * 256 + (u << 4);
       char* slab = const_cast<char*>(which ? p.v_slab : p.k_slab);
       const int64_t dst =
-          (p.base[pi.s] * p.Hkv + (int64_t)h * pi.cap + pi.P + pi.nb) * 256 + (u << 4);
+          (pi.base * p.Hkv + (int64_t)h * pi.cap + pi.P + pi.nb) * 256 + (u << 4);
       *reinterpret_cast<uint4*>(slab + dst) = *reinterpret_cast<const uint4*>(src);
     }
   }
@@ -414,7 +416,7 @@ __global__ __launch_bounds__(256) void decode_valu_kernel(DecodeParams p) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane / LPR, ls = lane - lr * LPR;
-  const int64_t stream_off = (p.base[pi.s] * p.Hkv + (int64_t)pi.kvh * pi.cap) * RB + ls * 16;
+  const int64_t stream_off = (pi.base * p.Hkv + (int64_t)pi.kvh * pi.cap) * RB + ls * 16;
   const char* kbase = p.k_slab + stream_off;
   const char* vbase = p.v_slab + stream_off;
 
