@@ -163,7 +163,7 @@ int32_t bc_decode_step(const bc_shape *shape, const bc_cache *cache, const void 
  * q: [total_rows, Hq, d]; k, v: [total_rows, Hkv, d] (kv_dtype must be BC_BF16);
  * out: [total_rows, Hq, d] fp32; lse (nullable): [total_rows, Hq] fp32, natural log of
  * the softmax denominator.  row_offsets: device [B+1] int64; P, c: device [B] int32;
- * max_rows: HOST value >= the longest trajectory (sizes the grid). */
+ * max_rows: HOST value >= the longest trajectory (sizes the grid), < 2^26.  scale must be > 0. */
 int32_t bc_prefill_attn(const bc_shape *shape, const void *q, const void *k, const void *v,
                         const int64_t *row_offsets, const int32_t *P, const int32_t *c,
                         int32_t max_rows, float *out, float *lse, void *stream);

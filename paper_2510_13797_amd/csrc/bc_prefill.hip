@@ -11,23 +11,26 @@
 // instead of the r rows of causal attention, and never materialises a mask.  Tiles that
 // touch the prompt use run C alone with the same predicate (which is then plain causal).
 //
-// One workgroup = 64 query rows x all query heads of one KV head, 8 waves: wave (tg, hh)
-// owns 16 rows x half of the heads.  K/V tiles of 32 keys are gathered from HBM into LDS by
-// 16-byte LDS-DMA loads (3-stage ring, one barrier per tile, each row 256 contiguous bytes), shared by the 8
+// One workgroup = 64 query rows x half of the query heads of one KV head, 4 waves of 16 rows
+// each; two workgroups share a CU, so one group's matrix phase overlaps the other's vector
+// (softmax) phase.  K/V tiles of 32 keys are gathered from HBM into LDS by
+// 16-byte LDS-DMA loads (3-stage ring, one barrier per tile, each row 256 contiguous bytes), shared by the 4
 // waves and fed to 16x16x32 bf16 MFMA: S^T = K.Q^T, O^T += V^T.P^T with P split into two
 // bf16 parts so that the softmax weights keep about 16 bits.  Softmax runs online in
 // registers in the accumulator layout.  The output tile goes through LDS so that every
 // row of 512 bytes is written to HBM as one burst.
+#include <type_traits>
+
 #include "bc_common.h"
 
 namespace bc {
 
-constexpr int kPfWaves = 8;
+constexpr int kPfWaves = 4;
 constexpr int kPfBM = 64;                 // query rows per workgroup
 constexpr int kPfBN = 32;                 // keys per tile
 constexpr int kPfTile = kPfBN * 256;      // bytes of one K (or V) tile
 constexpr int kPfStages = 3;
-constexpr int kPfLds = 65536;               // 3 stages of 16 KB in the loop, 8 x 8 KB in the epilogue
+constexpr int kPfLds = 49152;               // 3 stages of 16 KB in the loop, 4 x 8 KB in the epilogue
 
 typedef __attribute__((address_space(3))) void pf_lds_void_t;
 typedef __attribute__((address_space(1))) const void pf_global_void_t;
@@ -54,9 +57,10 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {      // RNE, a
 }
 
 template <int HPW>     // query heads per wave (the group's heads are split over two wave sets)
-__global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillParams p) {
+__global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams p) {
   __shared__ __attribute__((aligned(1024))) char lds[kPfLds];
-  const int b = blockIdx.z, kvh = blockIdx.y;
+  const int b = blockIdx.z, kvh = blockIdx.y >> 1, hh = blockIdx.y & 1;
+  if (hh * HPW >= p.g) return;                      // this half holds no head of the group
   const int64_t off0 = p.row_off[b];
   const int S = (int)(p.row_off[b + 1] - off0);
   const int qt = gridDim.x - 1 - blockIdx.x;        // long tiles first
@@ -79,7 +83,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillParams p)
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, kb = lane >> 4;
-  const int tg = wave & 3, hh = wave >> 2;
+  const int tg = wave;
   const int64_t kv_row_bytes = (int64_t)p.Hkv * 256;
   const char* kbase = p.k + (off0 * p.Hkv + kvh) * 256;
   const char* vbase = p.v + (off0 * p.Hkv + kvh) * 256;
@@ -101,16 +105,20 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillParams p)
     return t;
   };
   // HBM -> LDS gather of tile kt: this wave brings entries 4*wave .. 4*wave+3 of K and of V
-  const int ld_rr = 4 * wave + (lane >> 4);
-  const int ld_unit = ((lane & 15) ^ (ld_rr & 15)) << 4;
+  const int ld_rr = 4 * wave + (lane >> 4);             // and ld_rr + 16 in the second pass
+  const int ld_unit = ((lane & 15) ^ (ld_rr & 15)) << 4;  // (row + 16) & 15 == row & 15
   auto issue_tile = [&](int kt, int stage) {
     const TileDesc t = tile_desc(kt);
-    const int j = ld_rr < t.nvalid ? t.j0 + ld_rr * t.step : r1;
-    const int64_t goff = (int64_t)j * kv_row_bytes + ld_unit;
-    char* dst = lds + stage * (2 * kPfTile) + wave * 1024;
-    __builtin_amdgcn_global_load_lds((pf_global_void_t*)(kbase + goff), (pf_lds_void_t*)dst, 16, 0, 0);
-    __builtin_amdgcn_global_load_lds((pf_global_void_t*)(vbase + goff),
-                                     (pf_lds_void_t*)(dst + kPfTile), 16, 0, 0);
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      const int rr = ld_rr + 16 * half;
+      const int j = rr < t.nvalid ? t.j0 + rr * t.step : r1;
+      const int64_t goff = (int64_t)j * kv_row_bytes + ld_unit;
+      char* dst = lds + stage * (2 * kPfTile) + (wave + 4 * half) * 1024;
+      __builtin_amdgcn_global_load_lds((pf_global_void_t*)(kbase + goff), (pf_lds_void_t*)dst, 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((pf_global_void_t*)(vbase + goff),
+                                       (pf_lds_void_t*)(dst + kPfTile), 16, 0, 0);
+    }
   };
 
   issue_tile(0, 0);
@@ -144,22 +152,12 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillParams p)
     for (int j = 0; j < 8; ++j) O[h][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
   }
 
-  int stage = 0;
-  for (int kt = 0; kt < NT; ++kt) {
-    // tile kt has landed (this wave's part); after the barrier everyone's part has, and
-    // everyone has finished tile kt-1, whose stage is the one tile kt+2 goes into
-    if (kt + 1 < NT) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (kt + 2 < NT) issue_tile(kt + 2, stage >= 1 ? stage - 1 : kPfStages - 1);
-    const char* tk = lds + stage * (2 * kPfTile);
-    const char* tv = tk + kPfTile;
-    stage = stage + 1 == kPfStages ? 0 : stage + 1;
-
-    // which of this lane's 8 keys (tile entries 8*kb + e) may its query row see?
-    const TileDesc td = tile_desc(kt);
+  // Body of one key tile.  Scores stay unscaled; the softmax scale enters through one fused
+  // multiply-add per key: p = 2^(s*qs - m), qs > 0.
+  auto tile_body = [&](const char* tk, const char* tv, const TileDesc& td, auto masked_tag) {
+    constexpr bool MASKED = decltype(masked_tag)::value;
     bool vis[8];
-    {
+    if constexpr (MASKED) {
       const int lim = row_ok ? td.nvalid - 8 * kb : 0;      // entries e < lim exist
 #pragma unroll
       for (int e = 0; e < 8; ++e) vis[e] = e < lim;
@@ -178,7 +176,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillParams p)
       }
     }
 
-    // S^T = K . Q^T ; row m of sub-tile t is tile row 8*(m/4) + 4*t + m%4
+    // S^T = K . Q^T ; row m of sub-tile t is tile entry 8*(m/4) + 4*t + m%4
     bf16x8_t ka[2][4];
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
@@ -201,30 +199,35 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillParams p)
           Sx[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[t][i], qb[h][i], Sx[t], 0, 0, 0);
       }
       float sv[8];
-      float tmax = kNegBig;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        sv[e] = vis[e] ? Sx[e >> 2][e & 3] * p.qscale : kNegBig;
-        tmax = fmaxf(tmax, sv[e]);
+        sv[e] = Sx[e >> 2][e & 3];
+        if constexpr (MASKED) sv[e] = vis[e] ? sv[e] : kNegBig;
       }
+      float tmax = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])),
+                         fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
       tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
       tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-      const float m_new = fmaxf(m_run[h], tmax);
+      const float m_new = fmaxf(m_run[h], tmax * p.qscale);     // kNegBig * qs stays hugely negative
       alpha[h] = fast_exp2(m_run[h] - m_new);
       any_rescale = any_rescale || (m_new != m_run[h]);
       m_run[h] = m_new;
-      float psum = 0.f;
+      float pe[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        pe[e] = fast_exp2(fmaf(sv[e], p.qscale, -m_new));
+        if constexpr (MASKED) pe[e] = vis[e] ? pe[e] : 0.f;
+      }
+      const float psum = ((pe[0] + pe[1]) + (pe[2] + pe[3])) + ((pe[4] + pe[5]) + (pe[6] + pe[7]));
       uint32_t hi[4], lo[4];
 #pragma unroll
       for (int e = 0; e < 8; e += 2) {
-        const float pa = vis[e] ? fast_exp2(sv[e] - m_new) : 0.f;
-        const float pb = vis[e + 1] ? fast_exp2(sv[e + 1] - m_new) : 0.f;
-        psum += pa + pb;
-        const uint32_t hp = pack_bf16(pa, pb);
+        const uint32_t hp = pack_bf16(pe[e], pe[e + 1]);
         hi[e >> 1] = hp;
-        lo[e >> 1] = pack_bf16(pa - __uint_as_float(hp << 16), pb - __uint_as_float(hp & 0xffff0000u));
+        lo[e >> 1] = pack_bf16(pe[e] - __uint_as_float(hp << 16),
+                               pe[e + 1] - __uint_as_float(hp & 0xffff0000u));
       }
-      l_run[h] = l_run[h] * alpha[h] + psum;
+      l_run[h] = fmaf(l_run[h], alpha[h], psum);
       phi[h] = __builtin_bit_cast(bf16x8_t, make_uint4(hi[0], hi[1], hi[2], hi[3]));
       plo[h] = __builtin_bit_cast(bf16x8_t, make_uint4(lo[0], lo[1], lo[2], lo[3]));
     }
@@ -256,6 +259,21 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_kernel(PrefillParams p)
         }
       }
     }
+  };
+
+  int stage = 0;
+  for (int kt = 0; kt < NT; ++kt) {
+    // tile kt has landed (this wave's part); after the barrier everyone's part has, and
+    // everyone has finished tile kt-1, whose stage is the one tile kt+2 goes into
+    if (kt + 1 < NT) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (kt + 2 < NT) issue_tile(kt + 2, stage >= 1 ? stage - 1 : kPfStages - 1);
+    const char* tk = lds + stage * (2 * kPfTile);
+    const char* tv = tk + kPfTile;
+    stage = stage + 1 == kPfStages ? 0 : stage + 1;
+    const TileDesc td = tile_desc(kt);
+    tile_body(tk, tv, td, std::true_type{});
   }
   __syncthreads();          // the tile stages are free: the epilogue reuses LDS
 
@@ -304,6 +322,7 @@ extern "C" int32_t bc_prefill_attn(const bc_shape* shape, const void* q, const v
   if (!q || !k || !v || !row_offsets || !P || !c || !out) return BC_ERR_ARG;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return BC_ERR_ARG;
   if (max_rows < 1 || max_rows >= (1 << 26)) return BC_ERR_ARG;
+  if (!(shape->scale > 0.f)) return BC_ERR_ARG;       // the kernel takes maxima of unscaled scores
   PrefillParams p;
   p.q = static_cast<const char*>(q);
   p.k = static_cast<const char*>(k);
@@ -312,7 +331,7 @@ extern "C" int32_t bc_prefill_attn(const bc_shape* shape, const void* q, const v
   p.out = out; p.lse = lse;
   p.Hq = shape->Hq; p.Hkv = shape->Hkv; p.g = shape->Hq / shape->Hkv;
   p.qscale = shape->scale * kLog2e;
-  const dim3 grid((max_rows + kPfBM - 1) / kPfBM, shape->Hkv, shape->B);
+  const dim3 grid((max_rows + kPfBM - 1) / kPfBM, 2 * shape->Hkv, shape->B);
   hipStream_t hs = as_stream(stream);
   const int hpw = (p.g + 1) / 2;
   switch (hpw) {
