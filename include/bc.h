@@ -79,7 +79,7 @@ typedef struct {
   const int64_t *base;   /* [B] first entry of sequence s (in entries of Hkv*d)   */
   const int32_t *cap;    /* [B] rows per KV head                                  */
   const int32_t *P;      /* [B] prompt length                                     */
-  const int32_t *c;      /* [B] compression ratio; <= 0: never compress           */
+  int32_t *c;            /* [B] compression ratio; <= 0: never compress (bc_set_ratio) */
   int32_t *nb;           /* [B] beacons so far           (updated by the library) */
   int32_t *w;            /* [B] rows after the beacons   (updated by the library) */
   int32_t *err;          /* [1] sticky error bits                                 */
@@ -153,6 +153,26 @@ int32_t bc_decode_step(const bc_shape *shape, const bc_cache *cache, const void 
                        const void *v, const void *q, float *out, const void *beacon_k,
                        const void *beacon_v, const uint8_t *active, void *workspace,
                        size_t workspace_bytes, void *stream);
+
+/* bc_decode_step under the evaluation rule of the paper (Sec. 4, Evaluation: the cache size is
+ * capped - 1,000 entries there - and generation is interrupted when the cap is reached).
+ * budget: device [B] int32, cap on the generation entries nb + w (prompt rows not counted);
+ * live: device [B] bytes, read as the `active` mask and updated: a sequence whose attention in
+ * this step saw nb + w >= budget[s] entries is finished, live[s] becomes 0 and later calls skip
+ * it - no host round trip.  The step in which the cap is reached is still carried out in full. */
+int32_t bc_decode_step_budget(const bc_shape *shape, const bc_cache *cache, const void *k,
+                              const void *v, const void *q, float *out, const void *beacon_k,
+                              const void *beacon_v, const int32_t *budget, uint8_t *live,
+                              void *workspace, size_t workspace_bytes, void *stream);
+
+/* Change the compression ratio of active sequences in the middle of a generation (the paper
+ * fixes c per generation and names dynamic ratios as future work, Sec. 6).  new_c: device [B]
+ * int32.  Allowed when the current window fits the new ratio (w < new_c, or new_c <= 0, or a
+ * window boundary w == 0); otherwise the state bit is set and c[s] is left unchanged.  From the
+ * next append on, windows close at the new ratio; beacons already written are unaffected.
+ * Capacity is the caller's business: cap[s] must cover the longest window still to come. */
+int32_t bc_set_ratio(const bc_shape *shape, const bc_cache *cache, const int32_t *new_c,
+                     const uint8_t *active, void *stream);
 
 /* Training-time forward (Fig. 2, Sec. 3.2): attention over beacon-interleaved
  * trajectories where eviction is simulated by the mask.  Rows of trajectory b are

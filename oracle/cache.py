@@ -129,6 +129,25 @@ class BatchCache:
                     self.beacons[s].append((bk[s], bv[s]))
                     self.window[s] = []
 
+    def set_ratio(self, new_c, active=None):
+        """Mid-generation ratio change (the paper fixes c per generation; dynamic ratios are its
+        stated future work, Sec. 6): allowed when the current window fits the new ratio."""
+        for s in range(self.B):
+            if not self._active(active, s):
+                continue
+            nc, w = int(new_c[s]), len(self.window[s])
+            if nc > 0 and w >= nc and w != 0:
+                self.err |= ERR_STATE
+                continue
+            self.c[s] = nc
+
+    def apply_budget(self, budget, live):
+        """Evaluation rule (Sec. 4, Evaluation): generation is interrupted when the cache cap is
+        reached.  Called at attention time; budget caps the generation entries nb + w."""
+        for s in range(self.B):
+            if live[s] and len(self.beacons[s]) + len(self.window[s]) >= budget[s]:
+                live[s] = 0
+
     # -- views --------------------------------------------------------------
     def resident(self, s):
         """(K, V) [L, Hkv, d] of sequence s in cache order."""

@@ -26,7 +26,8 @@ BC_ROW_TOKEN, BC_ROW_BEACON = 0, 1
 EXPORTS = [
     "bc_status_str", "bc_version", "bc_cache_init", "bc_append_kv",
     "bc_decode_workspace_bytes", "bc_workspace_init", "bc_decode_attn",
-    "bc_compress_evict", "bc_decode_step", "bc_prefill_attn", "bc_tables_to_host",
+    "bc_compress_evict", "bc_decode_step", "bc_decode_step_budget", "bc_set_ratio",
+    "bc_prefill_attn", "bc_tables_to_host",
     "bc_set_decode_tuning",
 ]
 
@@ -80,6 +81,10 @@ def load():
     lib.bc_compress_evict.argtypes = [sp, cp, vp, vp, vp, i32, vp]
     lib.bc_decode_step.restype = i32
     lib.bc_decode_step.argtypes = [sp, cp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.bc_decode_step_budget.restype = i32
+    lib.bc_decode_step_budget.argtypes = [sp, cp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.bc_set_ratio.restype = i32
+    lib.bc_set_ratio.argtypes = [sp, cp, vp, vp, vp]
     lib.bc_prefill_attn.restype = i32
     lib.bc_prefill_attn.argtypes = [sp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp]
     lib.bc_tables_to_host.restype = i32
@@ -132,6 +137,16 @@ def bc_compress_evict(shape, cache, beacon_k, beacon_v, active, require_full_win
 def bc_decode_step(shape, cache, k, v, q, out, beacon_k, beacon_v, active, ws, ws_bytes, stream):
     return load().bc_decode_step(C.byref(shape), C.byref(cache), k, v, q, out, beacon_k, beacon_v,
                                  active, ws, ws_bytes, stream)
+
+
+def bc_decode_step_budget(shape, cache, k, v, q, out, beacon_k, beacon_v, budget, live, ws, ws_bytes,
+                          stream):
+    return load().bc_decode_step_budget(C.byref(shape), C.byref(cache), k, v, q, out, beacon_k, beacon_v,
+                                        budget, live, ws, ws_bytes, stream)
+
+
+def bc_set_ratio(shape, cache, new_c, active, stream):
+    return load().bc_set_ratio(C.byref(shape), C.byref(cache), new_c, active, stream)
 
 
 def bc_prefill_attn(shape, q, k, v, row_offsets, P, c, max_rows, out, lse, stream):
@@ -274,6 +289,23 @@ class Runtime:
                               _ptr(bk), _ptr(bv), _ptr(a), _ptr(self.ws), self.ws_bytes,
                               _stream_ptr()))
         return out
+
+    def decode_step_budget(self, k, v, q, bk, bv, budget, live, out=None):
+        """budget: int32 device tensor [B]; live: uint8 device tensor [B] (read and updated)."""
+        k, v, q = self.dev(k), self.dev(v), self.dev(q)
+        bk = None if bk is None else self.dev(bk)
+        bv = None if bv is None else self.dev(bv)
+        out = self.out if out is None else out
+        _check(bc_decode_step_budget(self.shape, self.cache, _ptr(k), _ptr(v), _ptr(q), _ptr(out),
+                                     _ptr(bk), _ptr(bv), _ptr(budget), _ptr(live), _ptr(self.ws),
+                                     self.ws_bytes, _stream_ptr()))
+        return out
+
+    def set_ratio(self, new_c, active=None):
+        nc = self.torch.from_numpy(np.asarray(new_c, dtype=np.int32)).to(self.device)
+        a = self.mask(active)
+        _check(bc_set_ratio(self.shape, self.cache, _ptr(nc), _ptr(a), _stream_ptr()))
+        self.torch.cuda.current_stream().synchronize()
 
     def tables(self):
         nb = np.empty(self.B, dtype=np.int32)

@@ -11,7 +11,7 @@ struct CacheView {
   const int64_t* base;
   const int32_t* cap;
   const int32_t* P;
-  const int32_t* c;
+  int32_t* c;
   int32_t* nb;
   int32_t* w;
   int32_t* err;
@@ -161,9 +161,57 @@ __global__ void compress_evict_kernel(CacheView cv, const char* __restrict__ bk,
   }
 }
 
+__global__ void set_ratio_kernel(CacheView cv, const int32_t* __restrict__ new_c,
+                                 const uint8_t* __restrict__ active, int B) {
+  const int s = blockIdx.x * blockDim.x + threadIdx.x;
+  if (s >= B || (active && !active[s])) return;
+  const int nc = new_c[s], wv = cv.w[s];
+  if (nc > 0 && wv >= nc && wv != 0) { atomicOr(cv.err, BC_ERRBIT_STATE); return; }
+  cv.c[s] = nc;
+}
+
+// Evaluation rule for the shapes whose decode step is not fused: mark the sequences whose
+// attention saw nb + w >= budget entries (before the eviction), clear their mask after it.
+__global__ void budget_mark_kernel(CacheView cv, const int32_t* __restrict__ budget,
+                                   const uint8_t* __restrict__ live, int32_t* __restrict__ mark, int B) {
+  const int s = blockIdx.x * blockDim.x + threadIdx.x;
+  if (s >= B) return;
+  mark[s] = (live[s] && cv.nb[s] + cv.w[s] >= budget[s]) ? 1 : 0;
+}
+
+__global__ void budget_apply_kernel(uint8_t* __restrict__ live, int32_t* __restrict__ mark, int B) {
+  const int s = blockIdx.x * blockDim.x + threadIdx.x;
+  if (s >= B) return;
+  if (mark[s]) { live[s] = 0; mark[s] = 0; }
+}
+
+int32_t launch_budget_mark(const bc_shape* shape, const bc_cache* cache, const int32_t* budget,
+                           const uint8_t* live, int32_t* mark, hipStream_t hs) {
+  CacheView cv = make_view(shape, cache);
+  budget_mark_kernel<<<(shape->B + 255) / 256, 256, 0, hs>>>(cv, budget, live, mark, shape->B);
+  return launch_status();
+}
+
+int32_t launch_budget_apply(const bc_shape* shape, uint8_t* live, int32_t* mark, hipStream_t hs) {
+  budget_apply_kernel<<<(shape->B + 255) / 256, 256, 0, hs>>>(live, mark, shape->B);
+  return launch_status();
+}
+
 }  // namespace bc
 
 using namespace bc;
+
+extern "C" int32_t bc_set_ratio(const bc_shape* shape, const bc_cache* cache, const int32_t* new_c,
+                                const uint8_t* active, void* stream) {
+  int32_t st = check_shape(shape);
+  if (st != BC_OK) return st;
+  st = check_cache(cache);
+  if (st != BC_OK) return st;
+  if (!new_c) return BC_ERR_ARG;
+  CacheView cv = make_view(shape, cache);
+  set_ratio_kernel<<<(shape->B + 255) / 256, 256, 0, as_stream(stream)>>>(cv, new_c, active, shape->B);
+  return launch_status();
+}
 
 extern "C" int32_t bc_cache_init(const bc_shape* shape, const bc_cache* cache, const void* k_prompt,
                                  const void* v_prompt, const int64_t* prompt_offsets,

@@ -43,6 +43,8 @@ struct DecodeParams {
   const char* bk;
   const char* bv;
   int32_t* tickets;    // [B], zero between launches
+  const int32_t* budget;   // [B] cap on nb + w (nullable), with
+  uint8_t* live;           // [B] cleared when the cap is reached
   int32_t debug_stage; // experiments only: leave the kernel early (0 = run everything)
   int32_t Hq, Hkv, g;  // g = real group size
   int32_t Gp;          // padded group size of the partial layout
@@ -393,6 +395,7 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
     p.tickets[pi.s] = 0;
     p.nb_rw[pi.s] = pi.nb + (pi.evict_due ? 1 : 0);
     p.w_rw[pi.s] = pi.evict_due ? 0 : pi.w_att;
+    if (p.budget && pi.nb + pi.w_att >= p.budget[pi.s]) p.live[pi.s] = 0;   // generation interrupted
   }
 }
 
@@ -649,7 +652,8 @@ __global__ void fill_zero_kernel(uint32_t* p, int64_t n) {
 static int32_t launch_attention(const bc_shape* shape, const bc_cache* cache, const DecodePlan& pl,
                                 const void* q, float* out, const uint8_t* active, void* workspace,
                                 const void* k, const void* v, const void* bk, const void* bv,
-                                hipStream_t hs) {
+                                hipStream_t hs, const int32_t* budget = nullptr,
+                                uint8_t* live = nullptr) {
   DecodeParams p;
   p.k_slab = static_cast<const char*>(cache->k_slab);
   p.v_slab = static_cast<const char*>(cache->v_slab);
@@ -666,6 +670,7 @@ static int32_t launch_attention(const bc_shape* shape, const bc_cache* cache, co
   p.c = cache->c; p.nb_rw = cache->nb; p.w_rw = cache->w;
   p.new_k = static_cast<const char*>(k); p.new_v = static_cast<const char*>(v);
   p.bk = static_cast<const char*>(bk); p.bv = static_cast<const char*>(bv);
+  p.budget = budget; p.live = live;
   p.Hq = shape->Hq; p.Hkv = shape->Hkv; p.g = shape->Hq / shape->Hkv;
   p.Gp = pl.Gp;
   p.D = shape->d;
@@ -704,6 +709,11 @@ static int32_t check_attention_args(const bc_shape* shape, const bc_cache* cache
   if (!workspace || !aligned16(workspace) || workspace_bytes < pl->total()) return BC_ERR_WORKSPACE;
   return BC_OK;
 }
+
+// bc_cache_ops.hip
+int32_t launch_budget_mark(const bc_shape* shape, const bc_cache* cache, const int32_t* budget,
+                           const uint8_t* live, int32_t* mark, hipStream_t hs);
+int32_t launch_budget_apply(const bc_shape* shape, uint8_t* live, int32_t* mark, hipStream_t hs);
 
 }  // namespace bc
 
@@ -761,4 +771,37 @@ extern "C" int32_t bc_decode_step(const bc_shape* shape, const bc_cache* cache, 
   if (st != BC_OK) return st;
   if (beacon_k) st = bc_compress_evict(shape, cache, beacon_k, beacon_v, active, 1, stream);
   return st;
+}
+
+extern "C" int32_t bc_decode_step_budget(const bc_shape* shape, const bc_cache* cache, const void* k,
+                                         const void* v, const void* q, float* out,
+                                         const void* beacon_k, const void* beacon_v,
+                                         const int32_t* budget, uint8_t* live, void* workspace,
+                                         size_t workspace_bytes, void* stream) {
+  DecodePlan pl;
+  int32_t st = check_attention_args(shape, cache, q, out, workspace, workspace_bytes, &pl);
+  if (st != BC_OK) return st;
+  if (!k || !v || !aligned16(k) || !aligned16(v) || !budget || !live) return BC_ERR_ARG;
+  if ((beacon_k == nullptr) != (beacon_v == nullptr)) return BC_ERR_ARG;
+  if (beacon_k && (!aligned16(beacon_k) || !aligned16(beacon_v))) return BC_ERR_ARG;
+  if (pl.lds)
+    return launch_attention(shape, cache, pl, q, out, live, workspace, k, v, beacon_k, beacon_v,
+                            as_stream(stream), budget, live);
+  // other shapes: the same steps as separate launches.  The cap is tested on the state the
+  // attention saw (before the eviction); the mask changes only after the eviction has used it.
+  // The per-sequence counters at the head of the workspace (unused on this path) hold the marks.
+  int32_t* mark = static_cast<int32_t*>(workspace);
+  hipStream_t hs = as_stream(stream);
+  st = bc_append_kv(shape, cache, k, v, live, BC_ROW_TOKEN, stream);
+  if (st != BC_OK) return st;
+  st = launch_attention(shape, cache, pl, q, out, live, workspace, nullptr, nullptr, nullptr,
+                        nullptr, hs);
+  if (st != BC_OK) return st;
+  st = launch_budget_mark(shape, cache, budget, live, mark, hs);
+  if (st != BC_OK) return st;
+  if (beacon_k) {
+    st = bc_compress_evict(shape, cache, beacon_k, beacon_v, live, 1, stream);
+    if (st != BC_OK) return st;
+  }
+  return launch_budget_apply(shape, live, mark, hs);
 }

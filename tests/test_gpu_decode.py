@@ -303,3 +303,71 @@ def test_deterministic_and_split_invariant(dev):
         bc.bc_set_decode_tuning(0, 0)
     assert float((a - c).abs().max()) < 1e-5               # independent of the split factor
     assert not torch.equal(a, torch.zeros_like(a))
+
+
+# ---------------------------------------------------------------------------
+# next rows: evaluation budget rule and mid-generation ratio change
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64)])
+def test_budget_rule_interrupts_generation_on_device(dev, dtype, d):
+    import torch
+    B = 6
+    c = np.array([1, 2, 4, 16, 0, 3], np.int32)
+    wl = W.Workload("budget", 91, B, 12 if d == 128 else 4, 2 if d == 128 else 1, d, dtype,
+                    np.array([3, 0, 17, 32, 5, 64], np.int32), np.full(B, 200, np.int32), c)
+    rt, oc = make(wl, dev)
+    budget = np.array([10, 12, 7, 20, 9, 15], np.int32)
+    bud_d = torch.from_numpy(budget).to(dev)
+    live_d = torch.ones(B, dtype=torch.uint8, device=dev)
+    live = [1] * B
+    last = [None] * B
+    for t in range(1, 121):
+        k, v = wl.step_kv(t)
+        q = wl.step_q(t)
+        bk, bv = wl.beacon_kv(t)
+        rt.out.fill_(77.0)
+        o = rt.decode_step_budget(k, v, q, bk, bv, bud_d, live_d).cpu().numpy()
+        was = list(live)
+        oc.append(k, v, active=was)
+        act = [s for s in range(B) if was[s]]
+        if act:
+            check_attention(o, q, oc, wl, act, t)
+        for s in range(B):
+            if not was[s]:
+                assert np.all(o[s] == 77.0), (s, t)          # finished sequences are skipped
+        oc.apply_budget(budget, live)
+        oc.compress_evict(bk, bv, active=was)
+        assert live_d.cpu().tolist() == live, t
+        check_tables(rt, oc, t)
+        for s in range(B):
+            if was[s] and not live[s]:
+                last[s] = t
+    check_slabs(rt, oc)
+    for s in range(B):
+        assert last[s] == OR.first_step_reaching(int(budget[s]), int(c[s])), (s, last[s])
+
+
+def test_ratio_change_mid_generation(dev):
+    B = 4
+    wl = W.Workload("ratio", 92, B, 12, 2, 128, "bf16", np.array([8, 0, 40, 3], np.int32),
+                    np.full(B, 120, np.int32), np.array([4, 16, 0, 2], np.int32))
+    cap = np.full(B, 40 + 120 + 40, np.int32)
+    rt, oc = make(wl, dev, cap)
+    changes = {9: [2, 16, 0, 2], 17: [2, 4, 0, 2], 30: [8, 4, 0, 0], 31: [1, 1, 1, 1], 70: [0, 5, 0, 16],
+               90: [3, 5, 200, 200]}
+    for t in range(1, 121):
+        if t in changes:
+            rt.set_ratio(changes[t])
+            oc.set_ratio(changes[t])
+            assert rt.c.cpu().tolist() == oc.c, t
+        k, v = wl.step_kv(t)
+        q = wl.step_q(t)
+        bk, bv = wl.beacon_kv(t)
+        o = rt.decode_step(k, v, q, bk, bv).cpu().numpy()
+        oc.append(k, v)
+        check_attention(o, q, oc, wl, None, t)
+        oc.compress_evict(bk, bv)
+        check_tables(rt, oc, t)
+        if t in (9, 17, 30, 31, 32, 70, 90, 120):
+            check_slabs(rt, oc)
+    assert oc.err == ERR_STATE          # the change at step 31 did not fit some windows
