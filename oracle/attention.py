@@ -128,3 +128,40 @@ def masked_prefill_attention(q, k, v, P: int, c: int, scale, rows=None):
             o[n, h] = (p @ v[vis, kvh, :]) / den
             lse[n, h] = mx + np.log(den)
     return o, lse
+
+
+def masked_prefill_attention_bwd(q, k, v, do, P: int, c: int, scale):
+    """Gradients of the beacon-masked attention of one trajectory (Sec. 3.2: training
+    differentiates through the masked forward; only the student's parameters get gradients).
+
+    With S = scale * Q K^T on the visible pairs, A = softmax(S) row-wise, O = A V and an
+    upstream gradient dO:  dV = A^T dO,  dA = dO V^T,  dS = A * (dA - rowsum(dO * O)),
+    dQ = scale * dS K,  dK = scale * dS^T Q; K/V gradients sum over the query heads of a group.
+    q, do [S, Hq, d]; k, v [S, Hkv, d] -> (dq [S, Hq, d], dk [S, Hkv, d], dv [S, Hkv, d]) fp64.
+    """
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    do = np.asarray(do, dtype=np.float64)
+    S, Hq, d = q.shape
+    Hkv = k.shape[1]
+    g = Hq // Hkv
+    mask = np.zeros((S, S), dtype=bool)
+    for r in range(S):
+        mask[r, visible_row(r, P, c)] = True
+    dq = np.zeros_like(q)
+    dk = np.zeros_like(k)
+    dv = np.zeros_like(v)
+    for h in range(Hq):
+        kvh = h // g
+        s = scale * (q[:, h, :] @ k[:, kvh, :].T)
+        s = np.where(mask, s, -np.inf)
+        a = np.exp(s - s.max(axis=1, keepdims=True))
+        a /= a.sum(axis=1, keepdims=True)
+        o = a @ v[:, kvh, :]
+        dv[:, kvh, :] += a.T @ do[:, h, :]
+        da = do[:, h, :] @ v[:, kvh, :].T
+        ds = a * (da - (do[:, h, :] * o).sum(axis=1, keepdims=True))
+        dq[:, h, :] = scale * (ds @ k[:, kvh, :])
+        dk[:, kvh, :] += scale * (ds.T @ q[:, h, :])
+    return dq, dk, dv

@@ -124,3 +124,44 @@ def test_mutants_of_the_predicate_are_caught():
     strict_diag = mask(lambda r, j: j < r and A.visible(r, j, P, c))
     for bad in (hide_beacons, off_by_one, strict_diag):
         assert not np.array_equal(bad, good)
+
+
+def test_backward_matches_autograd_and_finite_differences():
+    # the gradient formulas against torch autograd (fp64) on a dense masked attention written
+    # with library ops, and against central finite differences of the forward oracle
+    rng = np.random.default_rng(5)
+    S, Hq, Hkv, d, P, c = 23, 4, 2, 6, 4, 3
+    q, do = rng.standard_normal((S, Hq, d)), rng.standard_normal((S, Hq, d))
+    k, v = rng.standard_normal((S, Hkv, d)), rng.standard_normal((S, Hkv, d))
+    scale = 0.45
+    dq, dk, dv = A.masked_prefill_attention_bwd(q, k, v, do, P, c, scale)
+    tq, tk, tv = (torch.tensor(x, requires_grad=True) for x in (q, k, v))
+    mask = torch.from_numpy(A.visible_mask(S, P, c))
+    kk = tk.repeat_interleave(Hq // Hkv, dim=1)
+    vv = tv.repeat_interleave(Hq // Hkv, dim=1)
+    s = torch.einsum("rhd,jhd->hrj", tq, kk) * scale
+    a = torch.softmax(s.masked_fill(~mask, -math.inf), dim=-1)
+    o = torch.einsum("hrj,jhd->rhd", a, vv)
+    (o * torch.from_numpy(do)).sum().backward()
+    assert np.abs(dq - tq.grad.numpy()).max() < 1e-12
+    assert np.abs(dk - tk.grad.numpy()).max() < 1e-12
+    assert np.abs(dv - tv.grad.numpy()).max() < 1e-12
+
+    def loss(q_, k_, v_):
+        return float((A.masked_prefill_attention(q_, k_, v_, P, c, scale)[0] * do).sum())
+    eps = 1e-6
+    for arr, grad in ((q, dq), (k, dk), (v, dv)):
+        for _ in range(6):
+            idx = tuple(int(rng.integers(0, n)) for n in arr.shape)
+            x0 = arr[idx]
+            arr[idx] = x0 + eps; lp = loss(q, k, v)
+            arr[idx] = x0 - eps; lm = loss(q, k, v)
+            arr[idx] = x0
+            assert abs((lp - lm) / (2 * eps) - grad[idx]) < 1e-6
+    # hidden keys get no gradient from rows that cannot see them: a regular token of window 0
+    # is seen only inside its window, so rows of later windows do not contribute
+    do2 = np.zeros_like(do)
+    do2[P + (c + 1) * 2:] = do[P + (c + 1) * 2:]          # upstream gradient on later windows only
+    _, dk2, dv2 = A.masked_prefill_attention_bwd(q, k, v, do2, P, c, scale)
+    assert np.all(dk2[P:P + c] == 0) and np.all(dv2[P:P + c] == 0)        # window-0 tokens
+    assert np.abs(dv2[P + c]).max() > 0                                   # its beacon is visible
