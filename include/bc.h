@@ -188,6 +188,20 @@ int32_t bc_prefill_attn(const bc_shape *shape, const void *q, const void *k, con
                         const int64_t *row_offsets, const int32_t *P, const int32_t *c,
                         int32_t max_rows, float *out, float *lse, void *stream);
 
+/* Gradients of bc_prefill_attn (Sec. 3.2: the student is trained through the masked forward;
+ * gradients flow to its parameters only).  Same tensors and tables as the forward, plus
+ * out / lse as the forward wrote them and dout: [total_rows, Hq, d] in bf16.  Results, fp32:
+ * dq [total_rows, Hq, d], dk and dv [total_rows, Hkv, d] (summed over the query heads of a
+ * group); every element is written, nothing needs zeroing.  total_rows: HOST copy of
+ * row_offsets[B].  workspace: bc_prefill_bwd_workspace_bytes() bytes, no initialisation.
+ * No atomics: results are reproducible.  scale must be > 0. */
+size_t bc_prefill_bwd_workspace_bytes(const bc_shape *shape, int64_t total_rows);
+int32_t bc_prefill_attn_bwd(const bc_shape *shape, const void *q, const void *k, const void *v,
+                            const float *out, const float *lse, const void *dout,
+                            const int64_t *row_offsets, const int32_t *P, const int32_t *c,
+                            int32_t max_rows, int64_t total_rows, float *dq, float *dk, float *dv,
+                            void *workspace, size_t workspace_bytes, void *stream);
+
 /* Copy nb[B], w[B] and err[1] to HOST arrays (any may be NULL) and wait for the stream. */
 int32_t bc_tables_to_host(const bc_shape *shape, const bc_cache *cache, int32_t *nb_host,
                           int32_t *w_host, int32_t *err_host, void *stream);

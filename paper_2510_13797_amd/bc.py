@@ -27,7 +27,7 @@ EXPORTS = [
     "bc_status_str", "bc_version", "bc_cache_init", "bc_append_kv",
     "bc_decode_workspace_bytes", "bc_workspace_init", "bc_decode_attn",
     "bc_compress_evict", "bc_decode_step", "bc_decode_step_budget", "bc_set_ratio",
-    "bc_prefill_attn", "bc_tables_to_host",
+    "bc_prefill_attn", "bc_prefill_bwd_workspace_bytes", "bc_prefill_attn_bwd", "bc_tables_to_host",
     "bc_set_decode_tuning",
 ]
 
@@ -87,6 +87,10 @@ def load():
     lib.bc_set_ratio.argtypes = [sp, cp, vp, vp, vp]
     lib.bc_prefill_attn.restype = i32
     lib.bc_prefill_attn.argtypes = [sp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp]
+    lib.bc_prefill_bwd_workspace_bytes.restype = sz
+    lib.bc_prefill_bwd_workspace_bytes.argtypes = [sp, i64]
+    lib.bc_prefill_attn_bwd.restype = i32
+    lib.bc_prefill_attn_bwd.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i64, vp, vp, vp, vp, sz, vp]
     lib.bc_tables_to_host.restype = i32
     lib.bc_tables_to_host.argtypes = [sp, cp, vp, vp, vp, vp]
     lib.bc_set_decode_tuning.restype = None
@@ -152,6 +156,16 @@ def bc_set_ratio(shape, cache, new_c, active, stream):
 def bc_prefill_attn(shape, q, k, v, row_offsets, P, c, max_rows, out, lse, stream):
     return load().bc_prefill_attn(C.byref(shape), q, k, v, row_offsets, P, c, max_rows, out, lse,
                                   stream)
+
+
+def bc_prefill_bwd_workspace_bytes(shape, total_rows):
+    return load().bc_prefill_bwd_workspace_bytes(C.byref(shape), total_rows)
+
+
+def bc_prefill_attn_bwd(shape, q, k, v, out, lse, dout, row_offsets, P, c, max_rows, total_rows, dq, dk,
+                        dv, ws, ws_bytes, stream):
+    return load().bc_prefill_attn_bwd(C.byref(shape), q, k, v, out, lse, dout, row_offsets, P, c,
+                                      max_rows, total_rows, dq, dk, dv, ws, ws_bytes, stream)
 
 
 def bc_tables_to_host(shape, cache, nb_host, w_host, err_host, stream):
@@ -360,3 +374,28 @@ def prefill_attn(q, k, v, row_offsets, P, c, Hq, Hkv, d, scale, want_lse=True):
                            _ptr(out), _ptr(lse), _stream_ptr()))
     torch.cuda.current_stream().synchronize()      # offd/Pd/cd may be freed after this
     return out, lse
+
+
+def prefill_attn_bwd(q, k, v, out, lse, dout, row_offsets, P, c, Hq, Hkv, d, scale):
+    """bc_prefill_attn_bwd on device tensors (see prefill_attn); returns (dq, dk, dv) fp32."""
+    import torch
+    load()
+    dev = q.device
+    row_offsets = np.asarray(row_offsets, dtype=np.int64)
+    B = len(row_offsets) - 1
+    R = int(row_offsets[-1])
+    shape = bc_shape(B, Hq, Hkv, d, BC_BF16, float(scale))
+    offd = torch.from_numpy(row_offsets).to(dev)
+    Pd = torch.from_numpy(np.asarray(P, dtype=np.int32)).to(dev)
+    cd = torch.from_numpy(np.asarray(c, dtype=np.int32)).to(dev)
+    dq = torch.full((R, Hq, d), float("nan"), dtype=torch.float32, device=dev)
+    dk = torch.full((R, Hkv, d), float("nan"), dtype=torch.float32, device=dev)
+    dv = torch.full((R, Hkv, d), float("nan"), dtype=torch.float32, device=dev)
+    ws_bytes = int(bc_prefill_bwd_workspace_bytes(shape, R))
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    max_rows = int(np.diff(row_offsets).max())
+    _check(bc_prefill_attn_bwd(shape, _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), _ptr(dout),
+                               _ptr(offd), _ptr(Pd), _ptr(cd), max_rows, R, _ptr(dq), _ptr(dk), _ptr(dv),
+                               _ptr(ws), ws_bytes, _stream_ptr()))
+    torch.cuda.current_stream().synchronize()
+    return dq, dk, dv

@@ -1,0 +1,519 @@
+// bc_prefill_attn_bwd: gradients of the beacon-masked prefill attention (Fig. 2, Sec. 3.2 of the
+// paper: training runs the masked forward in parallel and differentiates through it).
+//
+// With S = scale*Q.K^T on the visible pairs, A = softmax(S), O = A.V and upstream dO:
+//   Delta_r = sum_x dO[r,x]*O[r,x]        dV = A^T.dO        dA = dO.V^T
+//   dS = A*(dA - Delta)                   dQ = scale*dS.K    dK = scale*dS^T.Q
+// A is recomputed from the saved log-sum-exp.  Two kernels, both on the compacted structure of
+// the mask, no atomics (every output element has exactly one owner, results are reproducible):
+//
+//  dq kernel   one workgroup = 64 query rows x 2 query heads, walking the same key list as the
+//              forward kernel (prompt run, gathered beacon run, masked band).  Also writes
+//              (lse*log2e, Delta) per row, head-major, for the second kernel.
+//  dkv kernel  one workgroup = 64 keys of one KV head; three kinds of key block:
+//                prompt keys      -> stream every later row of every head of the group (dense)
+//                gathered beacons -> the same, from the first beacon's row on (dense)
+//                response tokens  -> only the rows up to the end of their window (masked band)
+//              so the dense part of the work is spent on the ~P + S/(c+1) keys every row sees.
+//
+// All contractions are 16x16x32 bf16 MFMA; A and dS are split into two bf16 parts before they
+// enter a product (their rounding would otherwise dominate the error); tiles of 32 rows are
+// gathered into LDS by 16-byte LDS-DMA loads (3-stage ring, one barrier per tile).
+#include "bc_common.h"
+
+namespace bc {
+
+constexpr int kBwWaves = 4;
+constexpr int kBwBM = 64;                 // rows (dq kernel) or keys (dkv kernel) per workgroup
+constexpr int kBwBN = 32;                 // streamed entries per tile
+constexpr int kBwTile = kBwBN * 256;
+constexpr int kBwStages = 3;
+constexpr int kBwLds = kBwStages * 2 * kBwTile;      // 48 KB; the epilogues need 4 x 8 KB
+
+typedef __attribute__((address_space(3))) void bw_lds_void_t;
+typedef __attribute__((address_space(1))) const void bw_global_void_t;
+typedef __attribute__((ext_vector_type(4))) short bw_s16x4_t;
+typedef __attribute__((ext_vector_type(8))) short bw_s16x8_t;
+typedef __attribute__((address_space(3))) bw_s16x4_t bw_lds_s16x4_t;
+typedef __attribute__((ext_vector_type(2))) float bw_f32x2_t;
+
+struct BwdParams {
+  const char* q;
+  const char* k;
+  const char* v;
+  const float* out;
+  const float* lse;
+  const char* dout;
+  const int64_t* row_off;
+  const int32_t* P;
+  const int32_t* c;
+  float* dq;
+  float* dk;
+  float* dv;
+  float* stat;          // [Hq][total_rows][2]: lse*log2(e), Delta
+  int64_t total_rows;
+  int32_t Hq, Hkv, g;
+  float scale;
+  float qscale;         // scale * log2(e)
+};
+
+__device__ __forceinline__ uint32_t bw_pack(float a, float b) {       // two floats -> bf16x2, RNE
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(bw_f32x2_t{a, b}, bf16x2_t));
+}
+
+// 8 floats (consecutive k indices) -> hi and lo bf16x8 operands with hi + lo ~ x to 16 bits
+__device__ __forceinline__ void bw_split(const float (&x)[8], bf16x8_t& hi, bf16x8_t& lo) {
+  uint32_t h[4], l[4];
+#pragma unroll
+  for (int e = 0; e < 8; e += 2) {
+    const uint32_t hp = bw_pack(x[e], x[e + 1]);
+    h[e >> 1] = hp;
+    l[e >> 1] = bw_pack(x[e] - __uint_as_float(hp << 16), x[e + 1] - __uint_as_float(hp & 0xffff0000u));
+  }
+  hi = __builtin_bit_cast(bf16x8_t, make_uint4(h[0], h[1], h[2], h[3]));
+  lo = __builtin_bit_cast(bf16x8_t, make_uint4(l[0], l[1], l[2], l[3]));
+}
+
+// A operand "rows of the tile": lane (m = lane&15, kb = lane>>4) of sub-tile t reads tile entry
+// 8*(m/4) + 4*t + m%4, head-dim bytes 64*i + 16*kb (tile is row-major, 16-byte units swizzled)
+__device__ __forceinline__ bf16x8_t bw_rows_operand(const char* tile, int t, int i, int n, int kb) {
+  const int row = ((n >> 2) << 3) + 4 * t + (n & 3);
+  return *reinterpret_cast<const bf16x8_t*>(tile + row * 256 + (((4 * i + kb) ^ (row & 15)) << 4));
+}
+
+// A operand "tile transposed": M = 16 head-dim columns 16*j .., K = the 32 tile entries
+__device__ __forceinline__ bf16x8_t bw_cols_operand(const char* tile, int j, int lane) {
+  const int rl = lane & 15, kb = lane >> 4;
+  const int rowa = 8 * kb + (rl >> 2), rowb = rowa + 4;
+  const int sub = (rl & 1) << 3;
+  const int u = 2 * j + ((rl & 3) >> 1);
+  const bw_s16x4_t a0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (bw_lds_s16x4_t*)(tile + rowa * 256 + ((u ^ (rowa & 15)) << 4) + sub));
+  const bw_s16x4_t a1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (bw_lds_s16x4_t*)(tile + rowb * 256 + ((u ^ (rowb & 15)) << 4) + sub));
+  return __builtin_bit_cast(bf16x8_t, (bw_s16x8_t)__builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+// [16 entries][128] fp32 accumulators of one wave (accumulator layout: lane (n, kb) holds
+// columns 16*j + 4*kb .. +3 of entry n) -> LDS -> one 512-byte burst per entry.
+// dst_row(t) returns the destination pointer of entry t or nullptr.
+template <typename F>
+__device__ __forceinline__ void bw_store_tile(float* my, const f32x4_t (&acc)[8], float mul, int lane,
+                                              F dst_row) {
+  const int n = lane & 15, kb = lane >> 4;
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+    *reinterpret_cast<f32x4_t*>(my + n * 128 + (((4 * j + kb) ^ n) << 2)) = acc[j] * mul;
+#pragma unroll
+  for (int pass = 0; pass < 8; ++pass) {
+    const int t = 2 * pass + (lane >> 5), unit = lane & 31;
+    const f32x4_t val = *reinterpret_cast<const f32x4_t*>(my + t * 128 + ((unit ^ t) << 2));
+    float* dst = dst_row(t);
+    if (dst) *reinterpret_cast<f32x4_t*>(dst + unit * 4) = val;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// dq kernel
+// ---------------------------------------------------------------------------
+constexpr int kDqHeads = 2;      // query heads per workgroup
+
+__global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dq_kernel(BwdParams p) {
+  __shared__ __attribute__((aligned(1024))) char lds[kBwLds];
+  const int nhg = (p.g + kDqHeads - 1) / kDqHeads;
+  const int b = blockIdx.z, kvh = blockIdx.y / nhg, hh = blockIdx.y - kvh * nhg;
+  const int64_t off0 = p.row_off[b];
+  const int S = (int)(p.row_off[b + 1] - off0);
+  const int qt = gridDim.x - 1 - blockIdx.x;
+  const int r0 = qt * kBwBM;
+  if (r0 >= S) return;
+  const int r1 = min(r0 + kBwBM - 1, S - 1);
+  const int P = p.P[b], c = p.c[b];
+  const int cp1 = c + 1;
+  const uint32_t magic = c > 0 ? (uint32_t)(0x100000000ull / (uint32_t)cp1) + 1u : 0u;
+
+  int nA = 0, nB = 0, band_start = 0;
+  if (c > 0 && r0 >= P) {
+    const int m0 = (int)__umulhi((uint32_t)(r0 - P), magic);
+    nA = P; nB = m0; band_start = P + m0 * cp1;
+  }
+  const int nC = r1 - band_start + 1;
+  const int TA = (nA + kBwBN - 1) / kBwBN, TB = (nB + kBwBN - 1) / kBwBN;
+  const int NT = TA + TB + (nC + kBwBN - 1) / kBwBN;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n = lane & 15, kb = lane >> 4;
+  const int64_t kv_row_bytes = (int64_t)p.Hkv * 256;
+  const char* kbase = p.k + (off0 * p.Hkv + kvh) * 256;
+  const char* vbase = p.v + (off0 * p.Hkv + kvh) * 256;
+
+  struct TileDesc { int j0, step, nvalid; bool predicate; };
+  auto tile_desc = [&](int kt) -> TileDesc {
+    TileDesc t;
+    if (kt < TA) { t.j0 = kt * kBwBN; t.step = 1; t.nvalid = nA - kt * kBwBN; t.predicate = false; }
+    else if (kt < TA + TB) {
+      const int m = (kt - TA) * kBwBN;
+      t.j0 = P + m * cp1 + c; t.step = cp1; t.nvalid = nB - m; t.predicate = false;
+    } else {
+      const int x = (kt - TA - TB) * kBwBN;
+      t.j0 = band_start + x; t.step = 1; t.nvalid = nC - x; t.predicate = true;
+    }
+    t.nvalid = min(t.nvalid, kBwBN);
+    return t;
+  };
+  const int ld_rr = 4 * wave + (lane >> 4);
+  const int ld_unit = ((lane & 15) ^ (ld_rr & 15)) << 4;
+  auto issue_tile = [&](int kt, int stage) {
+    const TileDesc t = tile_desc(kt);
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      const int rr = ld_rr + 16 * half;
+      const int j = rr < t.nvalid ? t.j0 + rr * t.step : r1;
+      const int64_t goff = (int64_t)j * kv_row_bytes + ld_unit;
+      char* dst = lds + stage * (2 * kBwTile) + (wave + 4 * half) * 1024;
+      __builtin_amdgcn_global_load_lds((bw_global_void_t*)(kbase + goff), (bw_lds_void_t*)dst, 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((bw_global_void_t*)(vbase + goff),
+                                       (bw_lds_void_t*)(dst + kBwTile), 16, 0, 0);
+    }
+  };
+  issue_tile(0, 0);
+  if (NT > 1) issue_tile(1, 1);
+
+  // this lane's query row; Q^T and dO^T as B operands; log-sum-exp and Delta of the row
+  const int r = r0 + 16 * wave + n;
+  const bool row_ok = r <= r1;
+  const int rq = row_ok ? r : r1;
+  bf16x8_t qb[kDqHeads][4], dob[kDqHeads][4];
+  float lse2[kDqHeads], delta[kDqHeads];
+#pragma unroll
+  for (int h = 0; h < kDqHeads; ++h) {
+    const int head = hh * kDqHeads + h;
+    const bool head_ok = head < p.g;
+    const int64_t rh = (off0 + rq) * p.Hq + kvh * p.g + (head_ok ? head : 0);
+    float part = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      uint4 x = make_uint4(0u, 0u, 0u, 0u), y = make_uint4(0u, 0u, 0u, 0u);
+      if (head_ok) {
+        x = *reinterpret_cast<const uint4*>(p.q + (rh * 128 + 32 * i + 8 * kb) * 2);
+        y = *reinterpret_cast<const uint4*>(p.dout + (rh * 128 + 32 * i + 8 * kb) * 2);
+        const float4 o0 = *reinterpret_cast<const float4*>(p.out + rh * 128 + 32 * i + 8 * kb);
+        const float4 o1 = *reinterpret_cast<const float4*>(p.out + rh * 128 + 32 * i + 8 * kb + 4);
+        float dy[8];
+        unpack16(y, dy, bf16_t{});
+        part += dy[0] * o0.x + dy[1] * o0.y + dy[2] * o0.z + dy[3] * o0.w +
+                dy[4] * o1.x + dy[5] * o1.y + dy[6] * o1.z + dy[7] * o1.w;
+      }
+      qb[h][i] = __builtin_bit_cast(bf16x8_t, x);
+      dob[h][i] = __builtin_bit_cast(bf16x8_t, y);
+    }
+    part += __shfl_xor(part, 16, 64);
+    part += __shfl_xor(part, 32, 64);
+    delta[h] = part;
+    lse2[h] = head_ok ? p.lse[rh] * kLog2e : 0.f;
+    if (head_ok && row_ok && kb == 0) {
+      float* st = p.stat + ((int64_t)(kvh * p.g + head) * p.total_rows + off0 + r) * 2;
+      st[0] = lse2[h];
+      st[1] = delta[h];
+    }
+  }
+  const int win_r = (c > 0 && r >= P) ? (int)__umulhi((uint32_t)(r - P), magic) : -1;
+
+  f32x4_t dQ[kDqHeads][8];
+#pragma unroll
+  for (int h = 0; h < kDqHeads; ++h)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) dQ[h][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+  int stage = 0;
+  for (int kt = 0; kt < NT; ++kt) {
+    if (kt + 1 < NT) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (kt + 2 < NT) issue_tile(kt + 2, stage >= 1 ? stage - 1 : kBwStages - 1);
+    const char* tk = lds + stage * (2 * kBwTile);
+    const char* tv = tk + kBwTile;
+    stage = stage + 1 == kBwStages ? 0 : stage + 1;
+    const TileDesc td = tile_desc(kt);
+
+    bool vis[8];
+    {
+      const int lim = row_ok ? td.nvalid - 8 * kb : 0;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) vis[e] = e < lim;
+      if (td.predicate) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int j = td.j0 + 8 * kb + e;
+          bool see = j < P || c <= 0;
+          if (!see) {
+            const uint32_t u = (uint32_t)(j - P);
+            const uint32_t qd = __umulhi(u, magic);
+            see = (int)(u - qd * (uint32_t)cp1) == c || (int)qd == win_r;
+          }
+          vis[e] = vis[e] && j <= r && see;
+        }
+      }
+    }
+
+    bf16x8_t dshi[kDqHeads], dslo[kDqHeads];
+#pragma unroll
+    for (int h = 0; h < kDqHeads; ++h) {
+      f32x4_t Sx[2], dPx[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        Sx[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        dPx[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          Sx[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bw_rows_operand(tk, t, i, n, kb), qb[h][i], Sx[t], 0, 0, 0);
+          dPx[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bw_rows_operand(tv, t, i, n, kb), dob[h][i], dPx[t], 0, 0, 0);
+        }
+      }
+      float ds[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float a = vis[e] ? fast_exp2(fmaf(Sx[e >> 2][e & 3], p.qscale, -lse2[h])) : 0.f;
+        ds[e] = a * (dPx[e >> 2][e & 3] - delta[h]);
+      }
+      bw_split(ds, dshi[h], dslo[h]);
+    }
+    // dQ^T += K^T . dS^T
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const bf16x8_t kt_op = bw_cols_operand(tk, j, lane);
+#pragma unroll
+      for (int h = 0; h < kDqHeads; ++h) {
+        dQ[h][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kt_op, dshi[h], dQ[h][j], 0, 0, 0);
+        dQ[h][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kt_op, dslo[h], dQ[h][j], 0, 0, 0);
+      }
+    }
+  }
+  __syncthreads();
+
+  float* my = reinterpret_cast<float*>(lds + wave * 8192);
+#pragma unroll
+  for (int h = 0; h < kDqHeads; ++h) {
+    const int head = hh * kDqHeads + h;
+    if (head >= p.g) continue;
+    bw_store_tile(my, dQ[h], p.scale, lane, [&](int t) -> float* {
+      const int rr = r0 + 16 * wave + t;
+      return rr <= r1 ? p.dq + ((off0 + rr) * p.Hq + kvh * p.g + head) * 128 : nullptr;
+    });
+  }
+}
+
+// ---------------------------------------------------------------------------
+// dkv kernel
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dkv_kernel(BwdParams p) {
+  __shared__ __attribute__((aligned(1024))) char lds[kBwLds];
+  const int b = blockIdx.z, kvh = blockIdx.y;
+  const int64_t off0 = p.row_off[b];
+  const int S = (int)(p.row_off[b + 1] - off0);
+  const int P0 = p.P[b], c = p.c[b];
+  const int cp1 = c + 1;
+  const uint32_t magic = c > 0 ? (uint32_t)(0x100000000ull / (uint32_t)cp1) + 1u : 0u;
+  // key blocks of this (trajectory, KV head): prompt keys | gathered beacons | response rows.
+  // Without compression every row behaves like a prompt row (plain causal).
+  const int Pk = c > 0 ? min(P0, S) : S;                        // keys treated as dense-causal
+  const int nresp = S - Pk;                                     // response rows (tokens and beacons)
+  const int nbeac = c > 0 ? (int)__umulhi((uint32_t)nresp, magic) : 0;   // complete windows
+  const int NPB = (Pk + kBwBM - 1) / kBwBM, NBB = (nbeac + kBwBM - 1) / kBwBM;
+  const int NLB = (nresp + kBwBM - 1) / kBwBM;
+  const int blk = blockIdx.x;
+  if (blk >= NPB + NBB + NLB) return;
+  const int kind = blk < NPB ? 0 : blk < NPB + NBB ? 1 : 2;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n = lane & 15, kb = lane >> 4;
+
+  // this lane's key (column n of the wave's 16 keys) and the row range the block streams
+  int jkey;            // row of the key
+  bool key_ok;
+  int rs, re;          // first and last streamed row
+  if (kind == 0) {
+    const int j0 = blk * kBwBM;
+    jkey = j0 + 16 * wave + n; key_ok = jkey < Pk;
+    rs = j0; re = S - 1;
+  } else if (kind == 1) {
+    const int m0 = (blk - NPB) * kBwBM;
+    const int m = m0 + 16 * wave + n;
+    key_ok = m < nbeac; jkey = Pk + m * cp1 + c;
+    rs = Pk + m0 * cp1 + c; re = S - 1;
+  } else {
+    const int j0 = Pk + (blk - NPB - NBB) * kBwBM;
+    jkey = j0 + 16 * wave + n; key_ok = jkey < S;
+    if (key_ok) {                              // beacon rows belong to the beacon blocks
+      const uint32_t u = (uint32_t)(jkey - Pk);
+      const uint32_t qd = __umulhi(u, magic);
+      if ((int)(u - qd * (uint32_t)cp1) == c) key_ok = false;
+    }
+    const int jl = min(j0 + kBwBM - 1, S - 1);
+    const int wl = (int)__umulhi((uint32_t)(jl - Pk), magic);
+    rs = j0; re = min(S - 1, Pk + (wl + 1) * cp1 - 1);      // through the closing beacon
+  }
+  if (!key_ok) jkey = rs;                      // loads stay in range; contributions are masked
+  const int win_j = (c > 0 && jkey >= Pk) ? (int)__umulhi((uint32_t)(jkey - Pk), magic) : -1;
+
+  // K^T and V^T of the wave's keys as B operands (column n = key, k = head-dim index)
+  bf16x8_t kop[4], vop[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int64_t e = ((off0 + jkey) * p.Hkv + kvh) * 128 + 32 * i + 8 * kb;
+    kop[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(p.k + e * 2));
+    vop[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(p.v + e * 2));
+  }
+
+  const int ntile = (re - rs) / kBwBN + 1;     // row tiles per head
+  const int NT = ntile * p.g;                  // streamed tiles: head-major
+  const int64_t q_row_bytes = (int64_t)p.Hq * 256;
+  const int ld_rr = 4 * wave + (lane >> 4);
+  const int ld_unit = ((lane & 15) ^ (ld_rr & 15)) << 4;
+  auto issue_tile = [&](int it, int stage) {
+    const int h = it / ntile, rt = it - h * ntile;
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      const int rr = min(rs + rt * kBwBN + ld_rr + 16 * half, S - 1);
+      const int64_t goff = ((off0 + rr) * p.Hq + kvh * p.g + h) * 256 + ld_unit;
+      char* dst = lds + stage * (2 * kBwTile) + (wave + 4 * half) * 1024;
+      __builtin_amdgcn_global_load_lds((bw_global_void_t*)(p.q + goff), (bw_lds_void_t*)dst, 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((bw_global_void_t*)(p.dout + goff),
+                                       (bw_lds_void_t*)(dst + kBwTile), 16, 0, 0);
+    }
+  };
+  (void)q_row_bytes;
+  issue_tile(0, 0);
+  if (NT > 1) issue_tile(1, 1);
+
+  f32x4_t dK[8], dV[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) { dK[j] = f32x4_t{0.f, 0.f, 0.f, 0.f}; dV[j] = f32x4_t{0.f, 0.f, 0.f, 0.f}; }
+
+  int stage = 0;
+  for (int it = 0; it < NT; ++it) {
+    if (it + 1 < NT) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (it + 2 < NT) issue_tile(it + 2, stage >= 1 ? stage - 1 : kBwStages - 1);
+    const char* tq = lds + stage * (2 * kBwTile);
+    const char* tdo = tq + kBwTile;
+    stage = stage + 1 == kBwStages ? 0 : stage + 1;
+    const int h = it / ntile, rt = it - h * ntile;
+    const int row0 = rs + rt * kBwBN + 8 * kb;          // this lane's 8 rows: row0 + e
+
+    // per-row statistics of this lane's rows (head-major, 8 rows = 64 contiguous bytes)
+    float st[16];
+    {
+      const float* sp = p.stat + ((int64_t)(kvh * p.g + h) * p.total_rows + off0) * 2;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int rr = min(row0 + e, S - 1);
+        const float2 x = *reinterpret_cast<const float2*>(sp + (int64_t)rr * 2);
+        st[2 * e] = x.x; st[2 * e + 1] = x.y;
+      }
+    }
+    bool vis[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int r = row0 + e;
+      bool ok = key_ok && r <= re && r >= jkey;
+      if (kind == 2 && ok) {
+        // a response token is seen inside its own window (the closing beacon included)
+        const int wr = (int)__umulhi((uint32_t)(r - Pk), magic);
+        ok = wr == win_j;
+      }
+      vis[e] = ok;
+    }
+
+    f32x4_t Sx[2], dPx[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      Sx[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+      dPx[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        Sx[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bw_rows_operand(tq, t, i, n, kb), kop[i], Sx[t], 0, 0, 0);
+        dPx[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bw_rows_operand(tdo, t, i, n, kb), vop[i], dPx[t], 0, 0, 0);
+      }
+    }
+    float a[8], ds[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      a[e] = vis[e] ? fast_exp2(fmaf(Sx[e >> 2][e & 3], p.qscale, -st[2 * e])) : 0.f;
+      ds[e] = a[e] * (dPx[e >> 2][e & 3] - st[2 * e + 1]);
+    }
+    bf16x8_t ahi, alo, dshi, dslo;
+    bw_split(a, ahi, alo);
+    bw_split(ds, dshi, dslo);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const bf16x8_t dot = bw_cols_operand(tdo, j, lane);      // dO^T
+      dV[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dot, ahi, dV[j], 0, 0, 0);
+      dV[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dot, alo, dV[j], 0, 0, 0);
+      const bf16x8_t qt_op = bw_cols_operand(tq, j, lane);     // Q^T
+      dK[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qt_op, dshi, dK[j], 0, 0, 0);
+      dK[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qt_op, dslo, dK[j], 0, 0, 0);
+    }
+  }
+  __syncthreads();
+
+  // every key row is owned by exactly one lane column of one block: plain stores
+  float* my = reinterpret_cast<float*>(lds + wave * 8192);
+  // key row and validity of entry t of this wave, taken from the lane that owns it
+  auto dst_of = [&](float* base, int t) -> float* {
+    const int jk = __shfl(jkey, t, 64);
+    const int ok = __shfl((int)key_ok, t, 64);
+    return ok ? base + ((off0 + jk) * p.Hkv + kvh) * 128 : nullptr;
+  };
+  bw_store_tile(my, dK, p.scale, lane, [&](int t) { return dst_of(p.dk, t); });
+  bw_store_tile(my, dV, 1.0f, lane, [&](int t) { return dst_of(p.dv, t); });
+}
+
+}  // namespace bc
+
+using namespace bc;
+
+extern "C" size_t bc_prefill_bwd_workspace_bytes(const bc_shape* shape, int64_t total_rows) {
+  if (check_shape(shape) != BC_OK || total_rows < 1) return 0;
+  return (size_t)total_rows * shape->Hq * 2 * sizeof(float);
+}
+
+extern "C" int32_t bc_prefill_attn_bwd(const bc_shape* shape, const void* q, const void* k,
+                                       const void* v, const float* out, const float* lse,
+                                       const void* dout, const int64_t* row_offsets,
+                                       const int32_t* P, const int32_t* c, int32_t max_rows,
+                                       int64_t total_rows, float* dq, float* dk, float* dv,
+                                       void* workspace, size_t workspace_bytes, void* stream) {
+  int32_t st = check_shape(shape);
+  if (st != BC_OK) return st;
+  if (shape->kv_dtype != BC_BF16 || shape->d != 128) return BC_ERR_SHAPE;
+  if (!q || !k || !v || !out || !lse || !dout || !row_offsets || !P || !c || !dq || !dk || !dv)
+    return BC_ERR_ARG;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(dout) ||
+      !aligned16(dq) || !aligned16(dk) || !aligned16(dv))
+    return BC_ERR_ARG;
+  if (max_rows < 1 || max_rows >= (1 << 26) || total_rows < max_rows) return BC_ERR_ARG;
+  if (!(shape->scale > 0.f)) return BC_ERR_ARG;
+  if (!workspace || !aligned16(workspace) ||
+      workspace_bytes < bc_prefill_bwd_workspace_bytes(shape, total_rows))
+    return BC_ERR_WORKSPACE;
+  BwdParams p;
+  p.q = static_cast<const char*>(q); p.k = static_cast<const char*>(k);
+  p.v = static_cast<const char*>(v); p.out = out; p.lse = lse;
+  p.dout = static_cast<const char*>(dout);
+  p.row_off = row_offsets; p.P = P; p.c = c;
+  p.dq = dq; p.dk = dk; p.dv = dv;
+  p.stat = static_cast<float*>(workspace);
+  p.total_rows = total_rows;
+  p.Hq = shape->Hq; p.Hkv = shape->Hkv; p.g = shape->Hq / shape->Hkv;
+  p.scale = shape->scale;
+  p.qscale = shape->scale * kLog2e;
+  hipStream_t hs = as_stream(stream);
+  const int tiles = (max_rows + kBwBM - 1) / kBwBM;
+  const int nhg = (p.g + kDqHeads - 1) / kDqHeads;
+  prefill_bwd_dq_kernel<<<dim3(tiles, shape->Hkv * nhg, shape->B), kBwWaves * 64, 0, hs>>>(p);
+  // key blocks: at most `tiles` dense-causal blocks + the gathered beacons + `tiles` response blocks
+  prefill_bwd_dkv_kernel<<<dim3(3 * tiles + 2, shape->Hkv, shape->B), kBwWaves * 64, 0, hs>>>(p);
+  return launch_status();
+}

@@ -221,6 +221,12 @@ class PrefillWorkload:
         return (round_to_dtype(q, self.dtype), round_to_dtype(k, self.dtype),
                 round_to_dtype(v, self.dtype))
 
+    def dout(self, b: int):
+        """Upstream gradient dO [S, Hq, d] of trajectory b (N(0,1), as the rest)."""
+        r = np.random.default_rng([self.seed, self.wid, _STREAM_PREFILL, b, 1])
+        return round_to_dtype(r.standard_normal((int(self.S[b]), self.Hq, self.d), dtype=np.float32),
+                              self.dtype)
+
 
 def prefill_train(B: int = 16, tokens: int = 8192, P: int = 256, c: int = 16,
                   seed: int = BASE_SEED) -> PrefillWorkload:
