@@ -159,6 +159,69 @@ def bench_prefill(args):
     print(json.dumps(rec))
 
 
+def bench_prefill_bwd(args):
+    """Config 5, backward of the beacon-masked attention (dq, dk, dv), after one forward."""
+    import ctypes as C
+    import torch
+    from paper_2510_13797_amd import bc, workloads
+    bc.load()
+    dev = torch.device("cuda:0")
+    pw = workloads.prefill_train()
+    S = int(pw.S[0])
+    R = int(pw.S.sum())
+    off = np.zeros(pw.B + 1, np.int64)
+    off[1:] = np.cumsum(pw.S)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(workloads.BASE_SEED)
+    mk = lambda h: torch.randn(R, h, pw.d, generator=gen, device=dev).to(torch.bfloat16)
+    q, k, v, do = mk(pw.Hq), mk(pw.Hkv), mk(pw.Hkv), mk(pw.Hq)
+    out, lse = bc.prefill_attn(q, k, v, off, pw.P, pw.c, pw.Hq, pw.Hkv, pw.d, pw.scale, True)
+    shape = bc.bc_shape(pw.B, pw.Hq, pw.Hkv, pw.d, bc.BC_BF16, pw.scale)
+    offd = torch.from_numpy(off).to(dev)
+    Pd, cd = torch.from_numpy(pw.P).to(dev), torch.from_numpy(pw.c).to(dev)
+    dq = torch.empty(R, pw.Hq, pw.d, dtype=torch.float32, device=dev)
+    dk = torch.empty(R, pw.Hkv, pw.d, dtype=torch.float32, device=dev)
+    dv = torch.empty_like(dk)
+    ws_bytes = int(bc.bc_prefill_bwd_workspace_bytes(shape, R))
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    ptr = lambda t: C.c_void_p(t.data_ptr())
+    stream = torch.cuda.current_stream()
+
+    def step():
+        st = bc.bc_prefill_attn_bwd(shape, ptr(q), ptr(k), ptr(v), ptr(out), ptr(lse), ptr(do), ptr(offd),
+                                    ptr(Pd), ptr(cd), S, R, ptr(dq), ptr(dk), ptr(dv), ptr(ws), ws_bytes,
+                                    C.c_void_p(stream.cuda_stream))
+        assert st == 0, st
+
+    W_ = args.warmup if args.warmup >= 0 else 2
+    K_ = args.steps if args.steps >= 0 else 10
+    for _ in range(W_):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    wall0 = time.perf_counter()
+    e0.record(stream)
+    for _ in range(K_):
+        step()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - wall0
+    ms = max(e0.elapsed_time(e1), wall * 1e3) / K_
+    assert torch.isfinite(dq).all() and torch.isfinite(dk).all() and torch.isfinite(dv).all()
+    pairs = sum(visible_pairs(int(pw.S[b]), int(pw.P[b]), int(pw.c[b])) for b in range(pw.B))
+    flops = 10.0 * pw.d * pairs * pw.Hq              # recompute q.k, dO.v; dv, dq, dk: 5 products
+    tflops = flops / (ms * 1e-3) / 1e12
+    print(json.dumps({"metric": "prefill_attn_bwd_TFLOPs", "value": round(tflops, 2), "unit": "TFLOP/s",
+                      "n_gpus": 1, "steps": K_, "warmup": W_, "ms_per_step": round(ms, 4),
+                      "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+                      "data": "synthetic",
+                      "config": {"workload": "backward of the beacon-masked prefill attention, config 5 shape",
+                                 "algorithmic_GFLOP": round(flops / 1e9, 1)},
+                      "roofline": {"bound": "mfma", "kernel": "bc::prefill_bwd_dq_kernel + bc::prefill_bwd_dkv_kernel",
+                                   "achieved": round(tflops, 2), "peak": 2500.0, "unit": "TFLOP/s",
+                                   "frac": round(tflops / 2500.0, 4), "traffic": None}}))
+
+
 def bench_copy(args):
     """Plain device copy of known size: calibrates the FETCH_SIZE / WRITE_SIZE counters."""
     import torch
@@ -177,7 +240,7 @@ def bench_copy(args):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--workload", default="decode", choices=["decode", "prefill", "copy"])
+    ap.add_argument("--workload", default="decode", choices=["decode", "prefill", "prefill_bwd", "copy"])
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=-1)
     ap.add_argument("--warmup", type=int, default=-1)
@@ -200,6 +263,8 @@ def main():
     torch.cuda.set_device(dev)
     if args.workload == "prefill":
         return bench_prefill(args)
+    if args.workload == "prefill_bwd":
+        return bench_prefill_bwd(args)
     if args.workload == "copy":
         return bench_copy(args)
     if args.rows_per_wg:

@@ -24,6 +24,15 @@ template <> struct Elem<bf16_t> { static constexpr int size = 2; static constexp
 // 2^x by the hardware instruction (inputs here are <= 0 or moderate; -1e30 gives 0)
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Swizzle of the 16-byte units of a 256-byte tile row in LDS (tiles of 32 rows): unit u of row
+// `row` lives at position u ^ lds_swz(row).  Chosen so that both access patterns of the MFMA
+// operands are conflict-free: the 128-bit reads of one unit from the 16 rows {a + 8b} get 16
+// different positions, and the transposing 64-bit reads, which take two adjacent units from
+// the 8 rows {a + 8*b0} per half wave, get 8 different unit pairs.
+__device__ __forceinline__ int lds_swz(int row) {
+  return ((row & 3) << 1) | (((row >> 3) & 1) << 3) | ((row >> 4) & 1);
+}
+
 // 16 bytes of a row -> floats
 __device__ __forceinline__ void unpack16(const uint4& r, float (&f)[4], float) {
   f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y);

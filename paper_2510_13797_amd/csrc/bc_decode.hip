@@ -228,7 +228,7 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
     for (int j = 0; j < 8; ++j) {
       const int row = 4 * j + r4;
       const int grow = min(trow0 + row, last_slab_row);     // stay inside the slab rows
-      const int64_t goff = (int64_t)grow * 256 + ((pos ^ (row & 15)) << 4);
+      const int64_t goff = (int64_t)grow * 256 + ((pos ^ lds_swz(row)) << 4);
       __builtin_amdgcn_global_load_lds((global_void_t*)(kbase + goff),
                                        (lds_void_t*)(wk + j * 1024), 16, 0, 0);
       __builtin_amdgcn_global_load_lds((global_void_t*)(vbase + goff),
@@ -245,7 +245,7 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         const int row = 4 * j + r4;
-        const int o = row * 256 + ((pos ^ (row & 15)) << 4);
+        const int o = row * 256 + ((pos ^ lds_swz(row)) << 4);
         *reinterpret_cast<uint4*>(wk + o) = kreg[j];
         *reinterpret_cast<uint4*>(wv + o) = vreg[j];
       }
@@ -260,7 +260,7 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
       if (lane < 32) {
         char* tile = lane < 16 ? wk : wv;
         const int u = lane & 15;
-        *reinterpret_cast<uint4*>(tile + ra * 256 + ((u ^ (ra & 15)) << 4)) = newrow;
+        *reinterpret_cast<uint4*>(tile + ra * 256 + ((u ^ lds_swz(ra)) << 4)) = newrow;
         if (!(pi.evict_due && pi.w_att == 1)) {
           char* slab = const_cast<char*>(lane < 16 ? kbase : vbase);
           *reinterpret_cast<uint4*>(slab + (int64_t)pi.new_row * 256 + (u << 4)) = newrow;
@@ -281,7 +281,7 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
       for (int i = 0; i < 4; ++i) {
         const int u = 4 * i + kb;
         const bf16x8_t a =
-            *reinterpret_cast<const bf16x8_t*>(wk + row * 256 + ((u ^ (row & 15)) << 4));
+            *reinterpret_cast<const bf16x8_t*>(wk + row * 256 + ((u ^ lds_swz(row)) << 4));
         S[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qb[i], S[t], 0, 0, 0);
       }
     }
@@ -329,9 +329,9 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
         const int sub = (r & 1) << 3;
         const int rowa = key0, rowb = key0 + 4;
         const s16x4_t a0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (lds_s16x4_t*)(wv + rowa * 256 + ((u ^ (rowa & 15)) << 4) + sub));
+            (lds_s16x4_t*)(wv + rowa * 256 + ((u ^ lds_swz(rowa)) << 4) + sub));
         const s16x4_t a1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (lds_s16x4_t*)(wv + rowb * 256 + ((u ^ (rowb & 15)) << 4) + sub));
+            (lds_s16x4_t*)(wv + rowb * 256 + ((u ^ lds_swz(rowb)) << 4) + sub));
         typedef __attribute__((ext_vector_type(8))) short s16x8_t;
         const s16x8_t a = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
         const bf16x8_t av = __builtin_bit_cast(bf16x8_t, a);

@@ -106,14 +106,13 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
   };
   // HBM -> LDS gather of tile kt: this wave brings entries 4*wave .. 4*wave+3 of K and of V
   const int ld_rr = 4 * wave + (lane >> 4);             // and ld_rr + 16 in the second pass
-  const int ld_unit = ((lane & 15) ^ (ld_rr & 15)) << 4;  // (row + 16) & 15 == row & 15
   auto issue_tile = [&](int kt, int stage) {
     const TileDesc t = tile_desc(kt);
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
       const int rr = ld_rr + 16 * half;
       const int j = rr < t.nvalid ? t.j0 + rr * t.step : r1;
-      const int64_t goff = (int64_t)j * kv_row_bytes + ld_unit;
+      const int64_t goff = (int64_t)j * kv_row_bytes + (((lane & 15) ^ lds_swz(rr)) << 4);
       char* dst = lds + stage * (2 * kPfTile) + (wave + 4 * half) * 1024;
       __builtin_amdgcn_global_load_lds((pf_global_void_t*)(kbase + goff), (pf_lds_void_t*)dst, 16, 0, 0);
       __builtin_amdgcn_global_load_lds((pf_global_void_t*)(vbase + goff),
@@ -183,7 +182,7 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
       const int row = ((n >> 2) << 3) + 4 * t + (n & 3);
 #pragma unroll
       for (int i = 0; i < 4; ++i)
-        ka[t][i] = *reinterpret_cast<const bf16x8_t*>(tk + row * 256 + (((4 * i + kb) ^ (row & 15)) << 4));
+        ka[t][i] = *reinterpret_cast<const bf16x8_t*>(tk + row * 256 + (((4 * i + kb) ^ lds_swz(row)) << 4));
     }
     bf16x8_t phi[HPW], plo[HPW];
     float alpha[HPW];
@@ -247,9 +246,9 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
       for (int j = 0; j < 8; ++j) {
         const int u = 2 * j + ((rl & 3) >> 1);
         const pf_s16x4_t a0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (pf_lds_s16x4_t*)(tv + rowa * 256 + ((u ^ (rowa & 15)) << 4) + sub));
+            (pf_lds_s16x4_t*)(tv + rowa * 256 + ((u ^ lds_swz(rowa)) << 4) + sub));
         const pf_s16x4_t a1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (pf_lds_s16x4_t*)(tv + rowb * 256 + ((u ^ (rowb & 15)) << 4) + sub));
+            (pf_lds_s16x4_t*)(tv + rowb * 256 + ((u ^ lds_swz(rowb)) << 4) + sub));
         const bf16x8_t av = __builtin_bit_cast(
             bf16x8_t, (pf_s16x8_t)__builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7));
 #pragma unroll

@@ -29,6 +29,7 @@ constexpr int kBwBN = 32;                 // streamed entries per tile
 constexpr int kBwTile = kBwBN * 256;
 constexpr int kBwStages = 3;
 constexpr int kBwLds = kBwStages * 2 * kBwTile;      // 48 KB; the epilogues need 4 x 8 KB
+constexpr int kBwStatLds = kBwStages * 256;          // per-row statistics of the staged tiles (dkv kernel)
 
 typedef __attribute__((address_space(3))) void bw_lds_void_t;
 typedef __attribute__((address_space(1))) const void bw_global_void_t;
@@ -78,7 +79,7 @@ __device__ __forceinline__ void bw_split(const float (&x)[8], bf16x8_t& hi, bf16
 // 8*(m/4) + 4*t + m%4, head-dim bytes 64*i + 16*kb (tile is row-major, 16-byte units swizzled)
 __device__ __forceinline__ bf16x8_t bw_rows_operand(const char* tile, int t, int i, int n, int kb) {
   const int row = ((n >> 2) << 3) + 4 * t + (n & 3);
-  return *reinterpret_cast<const bf16x8_t*>(tile + row * 256 + (((4 * i + kb) ^ (row & 15)) << 4));
+  return *reinterpret_cast<const bf16x8_t*>(tile + row * 256 + (((4 * i + kb) ^ lds_swz(row)) << 4));
 }
 
 // A operand "tile transposed": M = 16 head-dim columns 16*j .., K = the 32 tile entries
@@ -88,9 +89,9 @@ __device__ __forceinline__ bf16x8_t bw_cols_operand(const char* tile, int j, int
   const int sub = (rl & 1) << 3;
   const int u = 2 * j + ((rl & 3) >> 1);
   const bw_s16x4_t a0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-      (bw_lds_s16x4_t*)(tile + rowa * 256 + ((u ^ (rowa & 15)) << 4) + sub));
+      (bw_lds_s16x4_t*)(tile + rowa * 256 + ((u ^ lds_swz(rowa)) << 4) + sub));
   const bw_s16x4_t a1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-      (bw_lds_s16x4_t*)(tile + rowb * 256 + ((u ^ (rowb & 15)) << 4) + sub));
+      (bw_lds_s16x4_t*)(tile + rowb * 256 + ((u ^ lds_swz(rowb)) << 4) + sub));
   return __builtin_bit_cast(bf16x8_t, (bw_s16x8_t)__builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
@@ -162,14 +163,13 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dq_kernel(BwdPar
     return t;
   };
   const int ld_rr = 4 * wave + (lane >> 4);
-  const int ld_unit = ((lane & 15) ^ (ld_rr & 15)) << 4;
   auto issue_tile = [&](int kt, int stage) {
     const TileDesc t = tile_desc(kt);
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
       const int rr = ld_rr + 16 * half;
       const int j = rr < t.nvalid ? t.j0 + rr * t.step : r1;
-      const int64_t goff = (int64_t)j * kv_row_bytes + ld_unit;
+      const int64_t goff = (int64_t)j * kv_row_bytes + (((lane & 15) ^ lds_swz(rr)) << 4);
       char* dst = lds + stage * (2 * kBwTile) + (wave + 4 * half) * 1024;
       __builtin_amdgcn_global_load_lds((bw_global_void_t*)(kbase + goff), (bw_lds_void_t*)dst, 16, 0, 0);
       __builtin_amdgcn_global_load_lds((bw_global_void_t*)(vbase + goff),
@@ -307,7 +307,7 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dq_kernel(BwdPar
 // dkv kernel
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dkv_kernel(BwdParams p) {
-  __shared__ __attribute__((aligned(1024))) char lds[kBwLds];
+  __shared__ __attribute__((aligned(1024))) char lds[kBwLds + kBwStatLds];
   const int b = blockIdx.z, kvh = blockIdx.y;
   const int64_t off0 = p.row_off[b];
   const int S = (int)(p.row_off[b + 1] - off0);
@@ -369,17 +369,24 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dkv_kernel(BwdPa
   const int NT = ntile * p.g;                  // streamed tiles: head-major
   const int64_t q_row_bytes = (int64_t)p.Hq * 256;
   const int ld_rr = 4 * wave + (lane >> 4);
-  const int ld_unit = ((lane & 15) ^ (ld_rr & 15)) << 4;
   auto issue_tile = [&](int it, int stage) {
     const int h = it / ntile, rt = it - h * ntile;
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
-      const int rr = min(rs + rt * kBwBN + ld_rr + 16 * half, S - 1);
-      const int64_t goff = ((off0 + rr) * p.Hq + kvh * p.g + h) * 256 + ld_unit;
+      const int tr = ld_rr + 16 * half;                       // entry of the tile
+      const int rr = min(rs + rt * kBwBN + tr, S - 1);
+      const int64_t goff = ((off0 + rr) * p.Hq + kvh * p.g + h) * 256 + (((lane & 15) ^ lds_swz(tr)) << 4);
       char* dst = lds + stage * (2 * kBwTile) + (wave + 4 * half) * 1024;
       __builtin_amdgcn_global_load_lds((bw_global_void_t*)(p.q + goff), (bw_lds_void_t*)dst, 16, 0, 0);
       __builtin_amdgcn_global_load_lds((bw_global_void_t*)(p.dout + goff),
                                        (bw_lds_void_t*)(dst + kBwTile), 16, 0, 0);
+    }
+    if (wave == 0) {
+      // (lse*log2e, Delta) of the tile's 32 rows: 64 floats, one 4-byte LDS-DMA load per lane
+      const int rr = min(rs + rt * kBwBN + (lane >> 1), S - 1);
+      const float* sp = p.stat + ((int64_t)(kvh * p.g + h) * p.total_rows + off0 + rr) * 2 + (lane & 1);
+      __builtin_amdgcn_global_load_lds((bw_global_void_t*)sp,
+                                       (bw_lds_void_t*)(lds + kBwLds + stage * 256), 4, 0, 0);
     }
   };
   (void)q_row_bytes;
@@ -392,26 +399,24 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dkv_kernel(BwdPa
 
   int stage = 0;
   for (int it = 0; it < NT; ++it) {
-    if (it + 1 < NT) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (it + 1 >= NT) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    else if (wave == 0) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");     // one more load per tile
+    else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
     __syncthreads();
     if (it + 2 < NT) issue_tile(it + 2, stage >= 1 ? stage - 1 : kBwStages - 1);
     const char* tq = lds + stage * (2 * kBwTile);
     const char* tdo = tq + kBwTile;
+    const float* tstat = reinterpret_cast<const float*>(lds + kBwLds + stage * 256);
     stage = stage + 1 == kBwStages ? 0 : stage + 1;
-    const int h = it / ntile, rt = it - h * ntile;
+    const int rt = it % ntile;
     const int row0 = rs + rt * kBwBN + 8 * kb;          // this lane's 8 rows: row0 + e
 
     // per-row statistics of this lane's rows (head-major, 8 rows = 64 contiguous bytes)
     float st[16];
-    {
-      const float* sp = p.stat + ((int64_t)(kvh * p.g + h) * p.total_rows + off0) * 2;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int rr = min(row0 + e, S - 1);
-        const float2 x = *reinterpret_cast<const float2*>(sp + (int64_t)rr * 2);
-        st[2 * e] = x.x; st[2 * e + 1] = x.y;
-      }
+    for (int e4 = 0; e4 < 4; ++e4) {
+      const f32x4_t x = *reinterpret_cast<const f32x4_t*>(tstat + 16 * kb + 4 * e4);
+      st[4 * e4] = x[0]; st[4 * e4 + 1] = x[1]; st[4 * e4 + 2] = x[2]; st[4 * e4 + 3] = x[3];
     }
     bool vis[8];
 #pragma unroll

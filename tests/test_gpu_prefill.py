@@ -182,3 +182,13 @@ def test_prefill_bwd_many_beacons(dev):
     for b in range(pw.B):
         worst = [max(a, e) for a, e in zip(worst, _check_bwd(pw, qkv, dos, off, dq, dk, dv, b))]
     print("bwd worst dq/dk/dv", worst)
+
+
+def test_config5_bwd_full_size(dev):
+    # B = 2 trajectories of the config-5 shape (8688 rows each); the dense fp64 oracle is run
+    # on the first one in full
+    pw = W.prefill_train(B=2)
+    qkv, dos, off, dq, dk, dv = _run_bwd(pw, dev)
+    assert np.isfinite(dq).all() and np.isfinite(dk).all() and np.isfinite(dv).all()
+    errs = _check_bwd(pw, qkv, dos, off, dq, dk, dv, 0)
+    print("config5 bwd dq/dk/dv", errs)
