@@ -59,11 +59,13 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {      // RNE, a
 template <int HPW>     // query heads per wave (the group's heads are split over two wave sets)
 __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams p) {
   __shared__ __attribute__((aligned(1024))) char lds[kPfLds];
-  const int b = blockIdx.z, kvh = blockIdx.y >> 1, hh = blockIdx.y & 1;
+  // grid: x = (trajectory, KV head, head half), y = query tile; workgroups are dispatched
+  // x-fastest, so the longest tiles of every trajectory start first
+  const int hh = blockIdx.x & 1, kvh = (blockIdx.x >> 1) % p.Hkv, b = (blockIdx.x >> 1) / p.Hkv;
   if (hh * HPW >= p.g) return;                      // this half holds no head of the group
   const int64_t off0 = p.row_off[b];
   const int S = (int)(p.row_off[b + 1] - off0);
-  const int qt = gridDim.x - 1 - blockIdx.x;        // long tiles first
+  const int qt = gridDim.y - 1 - blockIdx.y;        // long tiles first
   const int r0 = qt * kPfBM;
   if (r0 >= S) return;
   const int r1 = min(r0 + kPfBM - 1, S - 1);
@@ -330,7 +332,7 @@ extern "C" int32_t bc_prefill_attn(const bc_shape* shape, const void* q, const v
   p.out = out; p.lse = lse;
   p.Hq = shape->Hq; p.Hkv = shape->Hkv; p.g = shape->Hq / shape->Hkv;
   p.qscale = shape->scale * kLog2e;
-  const dim3 grid((max_rows + kPfBM - 1) / kPfBM, 2 * shape->Hkv, shape->B);
+  const dim3 grid(2 * shape->Hkv * shape->B, (max_rows + kPfBM - 1) / kPfBM);
   hipStream_t hs = as_stream(stream);
   const int hpw = (p.g + 1) / 2;
   switch (hpw) {

@@ -121,11 +121,13 @@ constexpr int kDqHeads = 2;      // query heads per workgroup
 
 __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dq_kernel(BwdParams p) {
   __shared__ __attribute__((aligned(1024))) char lds[kBwLds];
+  // grid: x = (trajectory, KV head, head pair), y = query tile, longest tiles of every
+  // trajectory first (workgroups are dispatched x-fastest)
   const int nhg = (p.g + kDqHeads - 1) / kDqHeads;
-  const int b = blockIdx.z, kvh = blockIdx.y / nhg, hh = blockIdx.y - kvh * nhg;
+  const int hh = blockIdx.x % nhg, kvh = (blockIdx.x / nhg) % p.Hkv, b = blockIdx.x / (nhg * p.Hkv);
   const int64_t off0 = p.row_off[b];
   const int S = (int)(p.row_off[b + 1] - off0);
-  const int qt = gridDim.x - 1 - blockIdx.x;
+  const int qt = gridDim.y - 1 - blockIdx.y;
   const int r0 = qt * kBwBM;
   if (r0 >= S) return;
   const int r1 = min(r0 + kBwBM - 1, S - 1);
@@ -308,7 +310,9 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dq_kernel(BwdPar
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dkv_kernel(BwdParams p) {
   __shared__ __attribute__((aligned(1024))) char lds[kBwLds + kBwStatLds];
-  const int b = blockIdx.z, kvh = blockIdx.y;
+  // grid: x = (trajectory, KV head), y = key block; the long dense blocks of every trajectory
+  // are dispatched before any short one
+  const int kvh = blockIdx.x % p.Hkv, b = blockIdx.x / p.Hkv;
   const int64_t off0 = p.row_off[b];
   const int S = (int)(p.row_off[b + 1] - off0);
   const int P0 = p.P[b], c = p.c[b];
@@ -321,7 +325,7 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dkv_kernel(BwdPa
   const int nbeac = c > 0 ? (int)__umulhi((uint32_t)nresp, magic) : 0;   // complete windows
   const int NPB = (Pk + kBwBM - 1) / kBwBM, NBB = (nbeac + kBwBM - 1) / kBwBM;
   const int NLB = (nresp + kBwBM - 1) / kBwBM;
-  const int blk = blockIdx.x;
+  const int blk = blockIdx.y;
   if (blk >= NPB + NBB + NLB) return;
   const int kind = blk < NPB ? 0 : blk < NPB + NBB ? 1 : 2;
 
@@ -517,8 +521,8 @@ extern "C" int32_t bc_prefill_attn_bwd(const bc_shape* shape, const void* q, con
   hipStream_t hs = as_stream(stream);
   const int tiles = (max_rows + kBwBM - 1) / kBwBM;
   const int nhg = (p.g + kDqHeads - 1) / kDqHeads;
-  prefill_bwd_dq_kernel<<<dim3(tiles, shape->Hkv * nhg, shape->B), kBwWaves * 64, 0, hs>>>(p);
+  prefill_bwd_dq_kernel<<<dim3(shape->B * shape->Hkv * nhg, tiles), kBwWaves * 64, 0, hs>>>(p);
   // key blocks: at most `tiles` dense-causal blocks + the gathered beacons + `tiles` response blocks
-  prefill_bwd_dkv_kernel<<<dim3(3 * tiles + 2, shape->Hkv, shape->B), kBwWaves * 64, 0, hs>>>(p);
+  prefill_bwd_dkv_kernel<<<dim3(shape->B * shape->Hkv, 3 * tiles + 2), kBwWaves * 64, 0, hs>>>(p);
   return launch_status();
 }
