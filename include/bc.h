@@ -207,7 +207,9 @@ int32_t bc_tables_to_host(const bc_shape *shape, const bc_cache *cache, int32_t 
                           int32_t *w_host, int32_t *err_host, void *stream);
 
 /* Tuning override for experiments: rows of one (sequence, KV head) stream handled by one
- * workgroup of bc_decode_attn (0 = automatic), and kernel variant (0 = automatic). */
+ * workgroup of bc_decode_attn (0 = automatic), and kernel variant: 0 = automatic, 1 = always the
+ * plain-ALU kernel, 2 = the LDS/MFMA kernel or BC_ERR_SHAPE; 11..15 = timing probes that leave
+ * the LDS/MFMA kernel after a given stage (outputs are then meaningless). */
 void bc_set_decode_tuning(int32_t rows_per_workgroup, int32_t variant);
 
 #ifdef __cplusplus

@@ -102,7 +102,10 @@ __device__ __forceinline__ PairInfo pair_info(const DecodeParams& p) {
       if (herald) atomicOr(p.err, BC_ERRBIT_STATE);
     } else {
       pi.nchunks = (pi.L + p.rows_per_wg - 1) / p.rows_per_wg;
-      pi.update = append_ok || pi.evict_due;
+      // the evaluation cap is tested on what this step's attention sees, whether or not the
+      // append went through
+      pi.update = append_ok || pi.evict_due ||
+                  (p.budget && pi.nb + pi.w_att >= p.budget[pi.s]);
       if (pi.chunk < pi.nchunks) {
         pi.row0 = pi.chunk * p.rows_per_wg;
         pi.row_end = min(pi.L, pi.row0 + p.rows_per_wg);
