@@ -155,10 +155,15 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
 
   // Body of one key tile.  Scores stay unscaled; the softmax scale enters through one fused
   // multiply-add per key: p = 2^(s*qs - m), qs > 0.
-  auto tile_body = [&](const char* tk, const char* tv, const TileDesc& td, auto masked_tag) {
-    constexpr bool MASKED = decltype(masked_tag)::value;
+  const bool full_rows = r0 + kPfBM - 1 <= r1;
+  auto tile_body = [&](const char* tk, const char* tv, const TileDesc& td) {
+    // a full tile of the prompt or beacon run under a full query tile needs no per-key tests;
+    // the flag is uniform over the workgroup, so the tests are skipped by cheap scalar branches
+    const bool MASKED = td.predicate || td.nvalid < kPfBN || !full_rows;
     bool vis[8];
-    if constexpr (MASKED) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) vis[e] = true;
+    if (MASKED) {
       const int lim = row_ok ? td.nvalid - 8 * kb : 0;      // entries e < lim exist
 #pragma unroll
       for (int e = 0; e < 8; ++e) vis[e] = e < lim;
@@ -203,7 +208,10 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         sv[e] = Sx[e >> 2][e & 3];
-        if constexpr (MASKED) sv[e] = vis[e] ? sv[e] : kNegBig;
+      }
+      if (MASKED) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sv[e] = vis[e] ? sv[e] : kNegBig;
       }
       float tmax = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])),
                          fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
@@ -217,7 +225,10 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         pe[e] = fast_exp2(fmaf(sv[e], p.qscale, -m_new));
-        if constexpr (MASKED) pe[e] = vis[e] ? pe[e] : 0.f;
+      }
+      if (MASKED) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pe[e] = vis[e] ? pe[e] : 0.f;
       }
       const float psum = ((pe[0] + pe[1]) + (pe[2] + pe[3])) + ((pe[4] + pe[5]) + (pe[6] + pe[7]));
       uint32_t hi[4], lo[4];
@@ -274,7 +285,7 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
     const char* tv = tk + kPfTile;
     stage = stage + 1 == kPfStages ? 0 : stage + 1;
     const TileDesc td = tile_desc(kt);
-    tile_body(tk, tv, td, std::true_type{});
+    tile_body(tk, tv, td);
   }
   __syncthreads();          // the tile stages are free: the epilogue reuses LDS
 
