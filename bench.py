@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the decode hot path on one MI355X.
 
-Workload (benchmark configs[1]): batch 64, 12 query / 2 KV heads, head_dim 128, bf16,
+Workload: batch 64, 12 query / 2 KV heads, head_dim 128, bf16,
 prompt 256, 4096 generated tokens, c = 16.  One *step* is one pass of the hot path over one
 batch for one attention layer: append the token's K/V, decode attention over
 [prompt | beacons | window], beacon append + eviction on the sequences that are due.
@@ -11,7 +11,7 @@ The model is represented by `--layers` independent cache instances visited round
 The timed region is the last `--steps` layer-steps of the rollout, the warm-up the ones
 before it; by default the two cover the whole 4096-token rollout.
 
-Prints ONE JSON line (see README): value = algorithmic KV bytes read by decode
+Prints ONE JSON line: value = algorithmic KV bytes read by decode
 attention per second over the whole timed region (all kernels and launch gaps included).
 """
 import argparse
@@ -252,7 +252,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (--gpus 1); multi-GPU sharding is a design "
-              "note in DESIGN.md, not an implemented path", file=sys.stderr)
+              "note in the design document, not an implemented path", file=sys.stderr)
         sys.exit(2)
 
     import torch
