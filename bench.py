@@ -222,6 +222,73 @@ def bench_prefill_bwd(args):
                                    "frac": round(tflops / 2500.0, 4), "traffic": None}}))
 
 
+def bench_distill(args):
+    """Distillation loss at the paper's shape: T=4096 tokens x 151,936 logits (bf16), top-100
+    teacher.  Forward and backward are timed separately; both are single streaming passes."""
+    import ctypes as C
+    import torch
+    from paper_2510_13797_amd import bc
+    bc.load()
+    dev = torch.device("cuda:0")
+    T, V, k = 4096, 151936, 100
+    gen = torch.Generator(device=dev).manual_seed(1234)
+    z = (2.0 * torch.randn((T, V), generator=gen, device=dev)).to(torch.bfloat16)
+    tl = torch.empty((T, k), dtype=torch.float32, device=dev)
+    idx = torch.empty((T, k), dtype=torch.int32, device=dev)
+    for t0 in range(0, T, 512):
+        top = torch.topk(z[t0:t0 + 512].float() + torch.randn((512, V), generator=gen, device=dev), k, dim=1)
+        tl[t0:t0 + 512] = top.values
+        idx[t0:t0 + 512] = top.indices.to(torch.int32)
+    loss = torch.empty(T, dtype=torch.float32, device=dev)
+    lse = torch.empty(T, dtype=torch.float32, device=dev)
+    mean = torch.empty(1, dtype=torch.float32, device=dev)
+    dz = torch.empty_like(z)
+    ptr = lambda t: C.c_void_p(t.data_ptr())
+    stream = torch.cuda.current_stream()
+    sp = C.c_void_p(stream.cuda_stream)
+
+    def fwd():
+        st = bc.bc_topk_kl_loss(T, V, k, ptr(z), bc.BC_BF16, ptr(tl), ptr(idx), ptr(loss), ptr(lse), ptr(mean), sp)
+        assert st == 0, st
+
+    def bwd():
+        st = bc.bc_topk_kl_loss_bwd(T, V, k, ptr(z), bc.BC_BF16, ptr(tl), ptr(idx), ptr(lse), 1.0 / T, ptr(dz), sp)
+        assert st == 0, st
+
+    W_ = args.warmup if args.warmup >= 0 else 3
+    K_ = args.steps if args.steps >= 0 else 20
+
+    def timed(fn):
+        for _ in range(W_):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(K_):
+            fn()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / K_
+
+    ms_f, ms_b = timed(fwd), timed(bwd)
+    assert torch.isfinite(mean).all() and torch.isfinite(dz[:8].float()).all()
+    bytes_f = T * V * 2 + T * k * 10              # logits once; teacher logits + ids; gathered logits
+    bytes_b = 2 * T * V * 2 + T * k * 8
+    gbs_f, gbs_b = bytes_f / (ms_f * 1e-3) / 1e9, bytes_b / (ms_b * 1e-3) / 1e9
+    ms = ms_f + ms_b
+    print(json.dumps({"metric": "distill_loss_tokens_per_s", "value": round(T / (ms * 1e-3), 1), "unit": "tokens/s",
+                      "n_gpus": 1, "steps": K_, "warmup": W_, "ms_per_step": round(ms, 4),
+                      "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+                      "data": "synthetic",
+                      "config": {"workload": "top-100 KL distillation loss, forward + backward: T=4096 tokens, "
+                                             "V=151936 logits (bf16)",
+                                 "ms_forward": round(ms_f, 4), "ms_backward": round(ms_b, 4),
+                                 "forward_GBps": round(gbs_f, 1), "backward_GBps": round(gbs_b, 1)},
+                      "roofline": {"bound": "hbm", "kernel": "bc::topk_kl_bwd_kernel<bf16_t, true>",
+                                   "achieved": round(gbs_b, 1), "peak": 8000.0, "unit": "GB/s",
+                                   "frac": round(gbs_b / 8000.0, 4), "traffic": None}}))
+
+
 def bench_copy(args):
     """Plain device copy of known size: calibrates the FETCH_SIZE / WRITE_SIZE counters."""
     import torch
@@ -240,7 +307,7 @@ def bench_copy(args):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--workload", default="decode", choices=["decode", "prefill", "prefill_bwd", "copy"])
+    ap.add_argument("--workload", default="decode", choices=["decode", "prefill", "prefill_bwd", "distill", "copy"])
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=-1)
     ap.add_argument("--warmup", type=int, default=-1)
@@ -265,6 +332,8 @@ def main():
         return bench_prefill(args)
     if args.workload == "prefill_bwd":
         return bench_prefill_bwd(args)
+    if args.workload == "distill":
+        return bench_distill(args)
     if args.workload == "copy":
         return bench_copy(args)
     if args.rows_per_wg:

@@ -202,6 +202,33 @@ int32_t bc_prefill_attn_bwd(const bc_shape *shape, const void *q, const void *k,
                             int32_t max_rows, int64_t total_rows, float *dq, float *dk, float *dv,
                             void *workspace, size_t workspace_bytes, void *stream);
 
+/* Token-level distillation loss of the training recipe (Eq. 1, Sec. 3.2) with the teacher given
+ * by its stored top-k logits per token (App. A; k = 100 there).  The teacher distribution is the
+ * softmax over its k stored logits; the student's log-probabilities are its full-vocabulary
+ * log-softmax at the same token ids:  loss[t] = sum_i p_T(i) * (log p_T(i) - log p_S(idx[t,i])).
+ * student_logits: device [T, V] row-major, logits_dtype BC_BF16 or BC_F32, finite values;
+ * teacher_logits: device [T, k] fp32; teacher_idx: device [T, k] int32, distinct ids in [0, V)
+ * per row (an id outside the range makes loss[t] NaN; nothing is read out of bounds).
+ * loss_per_token: device [T] fp32.  lse (nullable): device [T] fp32, natural-log partition
+ * function of the student row, the input of the backward call.  loss_mean (nullable): device
+ * [1] fp32, the mean of loss_per_token (trajectories of equal weight per token), summed in a
+ * fixed order.  1 <= k <= min(V, 1024).  Rows are read with 16-byte loads when V * element size
+ * is a multiple of 16 and the pointer is aligned, element by element otherwise. */
+int32_t bc_topk_kl_loss(int64_t T, int32_t V, int32_t k, const void *student_logits,
+                        int32_t logits_dtype, const float *teacher_logits,
+                        const int32_t *teacher_idx, float *loss_per_token, float *lse,
+                        float *loss_mean, void *stream);
+
+/* Gradient of grad_scale * sum_t loss[t] with respect to the student's logits (the teacher is
+ * fixed, Sec. 3.2): dlogits[t, v] = grad_scale * (softmax(student)[t, v] - p_T at v, if v is one
+ * of the teacher's ids).  lse: as written by bc_topk_kl_loss.  dlogits: device [T, V] of the
+ * logits' dtype, every element written; must not alias student_logits.  For the mean loss pass
+ * grad_scale = 1 / T. */
+int32_t bc_topk_kl_loss_bwd(int64_t T, int32_t V, int32_t k, const void *student_logits,
+                            int32_t logits_dtype, const float *teacher_logits,
+                            const int32_t *teacher_idx, const float *lse, float grad_scale,
+                            void *dlogits, void *stream);
+
 /* Copy nb[B], w[B] and err[1] to HOST arrays (any may be NULL) and wait for the stream. */
 int32_t bc_tables_to_host(const bc_shape *shape, const bc_cache *cache, int32_t *nb_host,
                           int32_t *w_host, int32_t *err_host, void *stream);

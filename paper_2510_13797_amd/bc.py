@@ -19,6 +19,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libbc.so")
 
 BC_OK = 0
+BC_ERR_ARG, BC_ERR_SHAPE, BC_ERR_CAPACITY, BC_ERR_STATE, BC_ERR_WORKSPACE, BC_ERR_HIP = -1, -2, -3, -4, -5, -6
 BC_F32, BC_BF16 = 0, 1
 BC_ERRBIT_STATE, BC_ERRBIT_CAPACITY = 1, 2
 BC_ROW_TOKEN, BC_ROW_BEACON = 0, 1
@@ -27,8 +28,8 @@ EXPORTS = [
     "bc_status_str", "bc_version", "bc_cache_init", "bc_append_kv",
     "bc_decode_workspace_bytes", "bc_workspace_init", "bc_decode_attn",
     "bc_compress_evict", "bc_decode_step", "bc_decode_step_budget", "bc_set_ratio",
-    "bc_prefill_attn", "bc_prefill_bwd_workspace_bytes", "bc_prefill_attn_bwd", "bc_tables_to_host",
-    "bc_set_decode_tuning",
+    "bc_prefill_attn", "bc_prefill_bwd_workspace_bytes", "bc_prefill_attn_bwd",
+    "bc_topk_kl_loss", "bc_topk_kl_loss_bwd", "bc_tables_to_host", "bc_set_decode_tuning",
 ]
 
 
@@ -91,6 +92,10 @@ def load():
     lib.bc_prefill_bwd_workspace_bytes.argtypes = [sp, i64]
     lib.bc_prefill_attn_bwd.restype = i32
     lib.bc_prefill_attn_bwd.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i64, vp, vp, vp, vp, sz, vp]
+    lib.bc_topk_kl_loss.restype = i32
+    lib.bc_topk_kl_loss.argtypes = [i64, i32, i32, vp, i32, vp, vp, vp, vp, vp, vp]
+    lib.bc_topk_kl_loss_bwd.restype = i32
+    lib.bc_topk_kl_loss_bwd.argtypes = [i64, i32, i32, vp, i32, vp, vp, vp, C.c_float, vp, vp]
     lib.bc_tables_to_host.restype = i32
     lib.bc_tables_to_host.argtypes = [sp, cp, vp, vp, vp, vp]
     lib.bc_set_decode_tuning.restype = None
@@ -166,6 +171,18 @@ def bc_prefill_attn_bwd(shape, q, k, v, out, lse, dout, row_offsets, P, c, max_r
                         dv, ws, ws_bytes, stream):
     return load().bc_prefill_attn_bwd(C.byref(shape), q, k, v, out, lse, dout, row_offsets, P, c,
                                       max_rows, total_rows, dq, dk, dv, ws, ws_bytes, stream)
+
+
+def bc_topk_kl_loss(T, V, k, student_logits, logits_dtype, teacher_logits, teacher_idx, loss_per_token,
+                    lse, loss_mean, stream):
+    return load().bc_topk_kl_loss(T, V, k, student_logits, logits_dtype, teacher_logits, teacher_idx,
+                                  loss_per_token, lse, loss_mean, stream)
+
+
+def bc_topk_kl_loss_bwd(T, V, k, student_logits, logits_dtype, teacher_logits, teacher_idx, lse,
+                        grad_scale, dlogits, stream):
+    return load().bc_topk_kl_loss_bwd(T, V, k, student_logits, logits_dtype, teacher_logits,
+                                      teacher_idx, lse, grad_scale, dlogits, stream)
 
 
 def bc_tables_to_host(shape, cache, nb_host, w_host, err_host, stream):
@@ -399,3 +416,44 @@ def prefill_attn_bwd(q, k, v, out, lse, dout, row_offsets, P, c, Hq, Hkv, d, sca
                                _ptr(ws), ws_bytes, _stream_ptr()))
     torch.cuda.current_stream().synchronize()
     return dq, dk, dv
+
+
+def _logits_code(t):
+    import torch
+    if t.dtype == torch.bfloat16:
+        return BC_BF16
+    if t.dtype == torch.float32:
+        return BC_F32
+    raise BcError("logits must be bf16 or fp32 device tensors")
+
+
+def topk_kl_loss(student_logits, teacher_logits, teacher_idx):
+    """bc_topk_kl_loss on device tensors: student_logits [T, V] bf16/fp32, teacher_logits [T, k]
+    fp32, teacher_idx [T, k] int32.  Returns (loss_per_token [T], lse [T], loss_mean [1]) fp32."""
+    import torch
+    load()
+    T, V = student_logits.shape
+    k = teacher_logits.shape[1]
+    dev = student_logits.device
+    loss = torch.full((T,), float("nan"), dtype=torch.float32, device=dev)
+    lse = torch.full((T,), float("nan"), dtype=torch.float32, device=dev)
+    mean = torch.full((1,), float("nan"), dtype=torch.float32, device=dev)
+    _check(bc_topk_kl_loss(T, V, k, _ptr(student_logits), _logits_code(student_logits),
+                           _ptr(teacher_logits), _ptr(teacher_idx), _ptr(loss), _ptr(lse), _ptr(mean),
+                           _stream_ptr()))
+    torch.cuda.current_stream().synchronize()
+    return loss, lse, mean
+
+
+def topk_kl_loss_bwd(student_logits, teacher_logits, teacher_idx, lse, grad_scale):
+    """bc_topk_kl_loss_bwd on device tensors; returns dlogits [T, V] in the logits' dtype."""
+    import torch
+    load()
+    T, V = student_logits.shape
+    k = teacher_logits.shape[1]
+    dz = torch.full_like(student_logits, float("nan"))
+    _check(bc_topk_kl_loss_bwd(T, V, k, _ptr(student_logits), _logits_code(student_logits),
+                               _ptr(teacher_logits), _ptr(teacher_idx), _ptr(lse), float(grad_scale),
+                               _ptr(dz), _stream_ptr()))
+    torch.cuda.current_stream().synchronize()
+    return dz

@@ -235,3 +235,45 @@ def prefill_train(B: int = 16, tokens: int = 8192, P: int = 256, c: int = 16,
     response tokens (8192, 256, 16 -> 496 beacons, 8688 rows)."""
     return PrefillWorkload("prefill_train", 5, B, 12, 2, 128, "bf16", _const(B, P),
                            _const(B, tokens - P), _const(B, c), seed=seed)
+
+
+_STREAM_DISTILL = 7
+
+
+@dataclass
+class DistillWorkload:
+    """Inputs of the distillation loss (Eq. 1; App. A): student logits over a vocabulary of V
+    entries for T tokens, and the teacher's k largest logits per token with their ids.  Synthetic:
+    student logits N(0, 2^2); the teacher is the student plus N(0, 1) noise (a trained student
+    is close to its teacher), and its k largest entries are kept.  Rows are generated one token
+    at a time, so any subset of tokens can be drawn without the rest."""
+    name: str
+    T: int
+    V: int
+    k: int
+    dtype: str
+    seed: int = BASE_SEED
+
+    def token(self, t: int):
+        """(student logits [V] fp32 exact in dtype, teacher logits [k] fp32, teacher ids [k] int32)."""
+        r = np.random.default_rng([self.seed, _STREAM_DISTILL, self.V, t])
+        z = 2.0 * r.standard_normal(self.V, dtype=np.float32)
+        teacher = z + r.standard_normal(self.V, dtype=np.float32)
+        if self.k < self.V:
+            idx = np.argpartition(-teacher, self.k - 1)[: self.k]
+        else:
+            idx = np.arange(self.V)
+        idx = idx[np.argsort(-teacher[idx], kind="stable")].astype(np.int32)
+        return round_to_dtype(z, self.dtype), teacher[idx].astype(np.float32), idx
+
+    def tokens(self, ts):
+        rows = [self.token(int(t)) for t in ts]
+        return (np.stack([x[0] for x in rows]), np.stack([x[1] for x in rows]),
+                np.stack([x[2] for x in rows]))
+
+
+def distill(T: int = 4096, V: int = 151936, k: int = 100, dtype: str = "bf16",
+            seed: int = BASE_SEED) -> DistillWorkload:
+    """Loss inputs at the paper's shape: vocabulary of the Qwen2.5 family (151,936 logits per
+    token), top-100 teacher logits (App. A); T tokens of a micro-batch."""
+    return DistillWorkload("distill", T, V, k, dtype, seed)

@@ -61,3 +61,14 @@ def test_peaked_keys_every_64th_written_row():
             if written % 64 == 63:
                 assert np.abs(kb[0]).max() > 8.0
             written += 1
+
+
+def test_distill_workload_rows_are_reproducible_and_well_formed():
+    wl = W.DistillWorkload("t", 9, 512, 20, "bf16")
+    z, tl, idx = wl.tokens([3, 7])
+    z2, tl2, idx2 = wl.token(7)
+    assert np.array_equal(z[1], z2) and np.array_equal(tl[1], tl2) and np.array_equal(idx[1], idx2)
+    assert np.array_equal(W.round_to_dtype(z, "bf16"), z)          # exact in the logits' dtype
+    assert len(set(idx[0].tolist())) == 20 and idx.min() >= 0 and idx.max() < 512
+    assert np.all(np.diff(tl, axis=1) <= 0)                        # the k largest, in descending order
+    assert W.distill().V == 151936 and W.distill().k == 100
