@@ -108,3 +108,42 @@ def test_mask_without_the_diagonal_is_caught(monkeypatch):
     monkeypatch.setattr(A, "visible_row", lambda r, P, c: good(r, P, c)[:-1] if r > 0 else good(r, P, c))
     assert _caught([TP.test_vectorised_row_equals_predicate_and_mask,
                     TP.test_prefill_row_equals_decode_over_evicted_cache]) == 2
+
+
+# -- distillation loss ---------------------------------------------------------------------
+from oracle import distill as D          # noqa: E402
+import test_oracle_distill as TD         # noqa: E402
+
+DISTILL_PINS = [TD.test_lse_matches_library_and_kl_is_nonnegative,
+                TD.test_loss_matches_torch_kl_div_on_the_same_definition,
+                TD.test_zero_when_student_equals_teacher_on_full_vocabulary,
+                TD.test_two_token_closed_form]
+
+
+def test_distill_pins_pass_unmutated():
+    assert _caught(DISTILL_PINS) == 0
+
+
+def test_reversed_kl_is_caught(monkeypatch):
+    good = D.topk_kl_loss
+
+    def reversed_kl(z, tl, idx):                       # KL(student || teacher) on the stored ids
+        loss, lse = good(z, tl, idx)
+        z, tl = np.asarray(z, float), np.asarray(tl, float)
+        out = np.empty_like(loss)
+        for t in range(len(loss)):
+            lps = z[t, idx[t]] - lse[t]
+            lpt = tl[t] - np.log(np.exp(tl[t]).sum())
+            out[t] = (np.exp(lps) * (lps - lpt)).sum()
+        return out, lse
+    monkeypatch.setattr(D, "topk_kl_loss", reversed_kl)
+    assert _caught(DISTILL_PINS) >= 2
+
+
+def test_unnormalised_teacher_and_missing_teacher_term_are_caught(monkeypatch):
+    good = D.topk_kl_loss_grad
+    monkeypatch.setattr(D, "topk_kl_loss_grad",
+                        lambda z, tl, idx, gs: good(z, np.asarray(tl) * 0.0, idx, gs))   # teacher logits ignored
+    assert _caught(DISTILL_PINS) >= 1
+    monkeypatch.setattr(D, "topk_kl_loss_grad", lambda z, tl, idx, gs: good(z, tl, idx, 1.0))   # scale dropped
+    assert _caught(DISTILL_PINS) >= 1
