@@ -314,6 +314,9 @@ def main():
     ap.add_argument("--layers", type=int, default=16, help="cache instances visited round-robin")
     ap.add_argument("--c", type=int, default=16, help="compression ratio (0: uncompressed control)")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
+    ap.add_argument("--beacon-attn", action="store_true",
+                    help="also run the beacon token's own attention (bc_beacon_step) at every window end "
+                         "instead of handing the beacon K/V to the token step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rows-per-wg", type=int, default=0)
     args = ap.parse_args()
@@ -377,11 +380,21 @@ def main():
     pool = [dict(k=rnd(wl.B, wl.Hkv, wl.d), v=rnd(wl.B, wl.Hkv, wl.d), q=rnd(wl.B, wl.Hq, wl.d),
                  bk=rnd(wl.B, wl.Hkv, wl.d), bv=rnd(wl.B, wl.Hkv, wl.d)) for _ in range(n_pool)]
 
+    faithful = args.beacon_attn and c > 0
+
     def layer_step(i):
         """i-th layer-step of the rollout (counted from the warm-up start)."""
         rt = layers[i % NL]
         x = pool[i % n_pool]
-        rt.decode_step(x["k"], x["v"], x["q"], x["bk"] if c > 0 else None, x["bv"] if c > 0 else None)
+        if not faithful:
+            rt.decode_step(x["k"], x["v"], x["q"], x["bk"] if c > 0 else None, x["bv"] if c > 0 else None)
+            return
+        # the window's last token is followed by the beacon token's own pass through all layers
+        rt.decode_step(x["k"], x["v"], x["q"], None, None)
+        if (t0 + i // NL + 1) % c == 0 and i % NL == NL - 1:
+            for li in range(NL):
+                y = pool[(i + 1 + li) % n_pool]
+                layers[li].beacon_step(y["bk"], y["bv"], y["q"])
 
     stream = torch.cuda.Stream()
     graph = None
@@ -437,6 +450,12 @@ def main():
     tok_first = t0 + W // NL + 1
     step_bytes = [kv_bytes_per_step(wl, t) for t in range(tok_first, t_end + 1)]
     total_bytes = sum(step_bytes) * NL
+    launches = K
+    if faithful:     # the beacon steps read the full window plus the beacon itself
+        row = wl.B * wl.Hkv * wl.d * 2 * 2
+        beacon_tokens = [t for t in range(tok_first, t_end + 1) if t % c == 0]
+        total_bytes += sum(kv_bytes_per_step(wl, t) + row for t in beacon_tokens) * NL
+        launches += len(beacon_tokens) * NL
     value = total_bytes / elapsed / 1e9
 
     # --- dominant kernel: the fused step kernel (append + attention + eviction in one launch),
@@ -478,9 +497,9 @@ def main():
     if use_graph:
         # The timed region is K back-to-back launches of this one kernel and nothing else, so the
         # region's own event pair gives the average launch duration without per-pair event cost.
-        avg_launch_us = gpu_ms * 1e3 / K
+        avg_launch_us = gpu_ms * 1e3 / launches
         achieved = total_bytes / (gpu_ms / 1e3) / 1e9
-        method = "HIP events over the timed region / %d launches (graph replay, one kernel per step)" % K
+        method = "HIP events over the timed region / %d launches (graph replay, one kernel per step)" % launches
 
     rec = {
         "metric": "decode_attn_kv_GBps", "value": round(value, 2), "unit": "GB/s",
@@ -492,7 +511,7 @@ def main():
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "config": {"workload": "batch64 rollout: B=64, Hq=12, Hkv=2, d=128, bf16, P=256, G=4096, c=%s; "
                                "tokens %d..%d of the rollout" % (c if c > 0 else "inf", tok_first, t_end),
-                   "layers_round_robin": NL, "hip_graph": bool(use_graph),
+                   "layers_round_robin": NL, "hip_graph": bool(use_graph), "beacon_token_attention": bool(faithful),
                    "step": "bc_decode_step for one layer: append_kv + decode_attn + compress_evict, one launch",
                    "kv_bytes_per_step_mean": int(np.mean(step_bytes))},
         "roofline": {"bound": "hbm", "kernel": "bc::decode_lds_kernel (bc_decode_step: append + attention + eviction)",
@@ -501,7 +520,7 @@ def main():
                      "traffic_detail": stored_traffic(),
                      "avg_launch_us": round(avg_launch_us, 3), "method": method,
                      "avg_launch_us_event_pairs_eager": round(samp_ms * 1e3 / max(n_samp, 1), 3),
-                     "bytes_per_launch_mean": int(total_bytes / K)},
+                     "bytes_per_launch_mean": int(total_bytes / launches)},
     }
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(wl)

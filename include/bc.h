@@ -154,6 +154,19 @@ int32_t bc_decode_step(const bc_shape *shape, const bc_cache *cache, const void 
                        const void *beacon_v, const uint8_t *active, void *workspace,
                        size_t workspace_bytes, void *stream);
 
+/* The beacon's own step in one launch (Alg. 1: encode the beacon, then drop the window; Sec. 3.1):
+ * the same as bc_append_kv(kind = BC_ROW_BEACON) + bc_decode_attn + bc_compress_evict(NULL, NULL)
+ * on the sequences whose window is full.  k, v: the beacon token's K/V rows [B, Hkv, d]; q: its
+ * query [B, Hq, d]; out [B, Hq, d]: its attention over prompt, earlier beacons, the full window
+ * and itself.  Afterwards the beacon sits behind the earlier beacons, nb is one larger and w = 0.
+ * Takes part: active sequences with c > 0 and w == c.  Other sequences are left alone and their
+ * rows of `out` are unspecified (pass an `active` mask of the due sequences to have every written
+ * row defined).  A due sequence without room for one more entry (L == cap) gets the capacity bit
+ * and is left alone. */
+int32_t bc_beacon_step(const bc_shape *shape, const bc_cache *cache, const void *k, const void *v,
+                       const void *q, float *out, const uint8_t *active, void *workspace,
+                       size_t workspace_bytes, void *stream);
+
 /* bc_decode_step under the evaluation rule of the paper (Sec. 4, Evaluation: the cache size is
  * capped - 1,000 entries there - and generation is interrupted when the cap is reached).
  * budget: device [B] int32, cap on the generation entries nb + w (prompt rows not counted);

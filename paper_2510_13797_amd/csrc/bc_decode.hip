@@ -45,6 +45,7 @@ struct DecodeParams {
   int32_t* tickets;    // [B], zero between launches
   const int32_t* budget;   // [B] cap on nb + w (nullable), with
   uint8_t* live;           // [B] cleared when the cap is reached
+  int32_t beacon_row;  // the fused row is the beacon closing a full window (bk = new_k, bv = new_v)
   int32_t debug_stage; // experiments only: leave the kernel early (0 = run everything)
   int32_t Hq, Hkv, g;  // g = real group size
   int32_t Gp;          // padded group size of the partial layout
@@ -83,10 +84,22 @@ __device__ __forceinline__ PairInfo pair_info(const DecodeParams& p) {
   pi.live = false;
   pi.update = false; pi.evict_due = false; pi.new_row = -1;
   pi.L = 0; pi.nchunks = 0; pi.chunk = blockIdx.x; pi.row0 = 0; pi.row_end = 0; pi.w_att = w;
-  if (act) {
+  // beacon step: only sequences whose window is full take part; one that has no room for the
+  // beacon at the tail is reported and left alone
+  bool take = act != 0;
+  if (take && p.beacon_row) {
+    take = pi.c > 0 && w == pi.c;
+    if (take && pi.P + pi.nb + w >= pi.cap) {
+      if (herald) atomicOr(p.err, BC_ERRBIT_CAPACITY);
+      take = false;
+    }
+  }
+  if (take) {
     const int L_old = pi.P + pi.nb + w;
     bool append_ok = false;
-    if (p.new_k) {
+    if (p.beacon_row) {
+      append_ok = true;
+    } else if (p.new_k) {
       if (pi.c > 0 && w >= pi.c) { if (herald) atomicOr(p.err, BC_ERRBIT_STATE); }
       else if (L_old >= pi.cap)  { if (herald) atomicOr(p.err, BC_ERRBIT_CAPACITY); }
       else append_ok = true;
@@ -94,7 +107,9 @@ __device__ __forceinline__ PairInfo pair_info(const DecodeParams& p) {
     pi.L = L_old + (append_ok ? 1 : 0);
     pi.w_att = w + (append_ok ? 1 : 0);
     if (append_ok) pi.new_row = L_old;
-    if (p.bk && pi.c > 0) {
+    if (p.beacon_row) {
+      pi.evict_due = true;          // the row just attended to moves behind the earlier beacons
+    } else if (p.bk && pi.c > 0) {
       if (pi.w_att == pi.c + 1) { if (herald) atomicOr(p.err, BC_ERRBIT_STATE); }
       else if (pi.w_att == pi.c) pi.evict_due = true;
     }
@@ -264,7 +279,7 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
         char* tile = lane < 16 ? wk : wv;
         const int u = lane & 15;
         *reinterpret_cast<uint4*>(tile + ra * 256 + ((u ^ lds_swz(ra)) << 4)) = newrow;
-        if (!(pi.evict_due && pi.w_att == 1)) {
+        if (!(pi.evict_due && (pi.w_att == 1 || p.beacon_row))) {
           char* slab = const_cast<char*>(lane < 16 ? kbase : vbase);
           *reinterpret_cast<uint4*>(slab + (int64_t)pi.new_row * 256 + (u << 4)) = newrow;
         }
@@ -656,7 +671,7 @@ static int32_t launch_attention(const bc_shape* shape, const bc_cache* cache, co
                                 const void* q, float* out, const uint8_t* active, void* workspace,
                                 const void* k, const void* v, const void* bk, const void* bv,
                                 hipStream_t hs, const int32_t* budget = nullptr,
-                                uint8_t* live = nullptr) {
+                                uint8_t* live = nullptr, bool beacon_row = false) {
   DecodeParams p;
   p.k_slab = static_cast<const char*>(cache->k_slab);
   p.v_slab = static_cast<const char*>(cache->v_slab);
@@ -674,6 +689,7 @@ static int32_t launch_attention(const bc_shape* shape, const bc_cache* cache, co
   p.new_k = static_cast<const char*>(k); p.new_v = static_cast<const char*>(v);
   p.bk = static_cast<const char*>(bk); p.bv = static_cast<const char*>(bv);
   p.budget = budget; p.live = live;
+  p.beacon_row = beacon_row ? 1 : 0;
   p.Hq = shape->Hq; p.Hkv = shape->Hkv; p.g = shape->Hq / shape->Hkv;
   p.Gp = pl.Gp;
   p.D = shape->d;
@@ -774,6 +790,24 @@ extern "C" int32_t bc_decode_step(const bc_shape* shape, const bc_cache* cache, 
   if (st != BC_OK) return st;
   if (beacon_k) st = bc_compress_evict(shape, cache, beacon_k, beacon_v, active, 1, stream);
   return st;
+}
+
+extern "C" int32_t bc_beacon_step(const bc_shape* shape, const bc_cache* cache, const void* k,
+                                  const void* v, const void* q, float* out, const uint8_t* active,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
+  DecodePlan pl;
+  int32_t st = check_attention_args(shape, cache, q, out, workspace, workspace_bytes, &pl);
+  if (st != BC_OK) return st;
+  if (!k || !v || !aligned16(k) || !aligned16(v)) return BC_ERR_ARG;
+  if (pl.lds)     // one launch: beacon row at the tail, its attention, compaction
+    return launch_attention(shape, cache, pl, q, out, active, workspace, k, v, k, v,
+                            as_stream(stream), nullptr, nullptr, true);
+  st = bc_append_kv(shape, cache, k, v, active, BC_ROW_BEACON, stream);
+  if (st != BC_OK) return st;
+  st = launch_attention(shape, cache, pl, q, out, active, workspace, nullptr, nullptr, nullptr,
+                        nullptr, as_stream(stream));
+  if (st != BC_OK) return st;
+  return bc_compress_evict(shape, cache, nullptr, nullptr, active, 1, stream);
 }
 
 extern "C" int32_t bc_decode_step_budget(const bc_shape* shape, const bc_cache* cache, const void* k,

@@ -66,7 +66,7 @@ def check_attention(o, q, oc, wl, seqs=None, t=None):
 
 
 def rollout(wl, rt, oc, steps, attn_steps, slab_steps, table_every=1, tail_form=False,
-            use_step_call=False, seq_sample=None):
+            use_step_call=False, seq_sample=None, beacon_call=False):
     """Alg. 1 for `steps` decode steps; sequences whose generation is over stay resident."""
     attn_steps, slab_steps = set(attn_steps), set(slab_steps)
     worst = 0.0
@@ -77,7 +77,22 @@ def rollout(wl, rt, oc, steps, attn_steps, slab_steps, table_every=1, tail_form=
         need_attn = t in attn_steps
         q = wl.step_q(t) if (need_attn or use_step_call) else None
         bk, bv = wl.beacon_kv(t)
-        if use_step_call:
+        if beacon_call:
+            # token step without eviction, then the beacon's own step (bc_beacon_step): beacon row
+            # at the tail, its attention, compaction - one launch each on the bf16 d=128 path
+            o = rt.decode_step(k, v, q, None, None, active=act)
+            oc.append(k, v, active=act)
+            if need_attn:
+                seqs = [s for s in (range(wl.B) if seq_sample is None else seq_sample) if active[s]]
+                worst = max(worst, check_attention(o.cpu().numpy(), q, oc, wl, seqs, t))
+            qb = wl.beacon_q(t)
+            ob = rt.beacon_step(bk, bv, qb, active=act)
+            oc.append(bk, bv, active=act, beacon=True)
+            due = [s for s in range(wl.B) if active[s] and oc.c[s] > 0 and oc.w[s] == oc.c[s] + 1]
+            if need_attn and due:
+                worst = max(worst, check_attention(ob.cpu().numpy(), qb, oc, wl, due, t))
+            oc.compress_evict(active=act)
+        elif use_step_call:
             o = rt.decode_step(k, v, q, bk, bv, active=act)
             oc.append(k, v, active=act)
             if need_attn:
@@ -147,6 +162,43 @@ def test_fused_step_bf16_every_step(dev, c, P):
     rt, oc = make(wl, dev)
     steps = range(1, 151)
     rollout(wl, rt, oc, 150, steps, steps, use_step_call=True)
+
+
+@pytest.mark.parametrize("name,dtype,d", [("bstep", "bf16", 128), ("bstep32", "f32", 64)])
+def test_beacon_step_rollout(dev, name, dtype, d):
+    # the beacon's own step: single launch on the bf16 d=128 path, three launches otherwise
+    c = np.array([1, 2, 4, 8, 16, 32, 0, 3], np.int32)
+    wl = W.Workload(name, 85, 8, 12, 2, d, dtype,
+                    np.array([0, 1, 31, 32, 33, 64, 7, 100], np.int32),
+                    np.array([120, 120, 120, 77, 120, 120, 120, 50], np.int32), c)
+    cap = wl.capacity()
+    cap[4] = 33 + 16           # sequence 4: room for one full window but not for its beacon
+    rt, oc = make(wl, dev, cap)
+    steps = range(1, 121)
+    rollout(wl, rt, oc, 120, steps, (1, 2, 3, 16, 17, 50, 120), beacon_call=True)
+    assert oc.err & ERR_CAPACITY
+
+
+def test_beacon_step_leaves_other_sequences_alone(dev):
+    wl = W.Workload("bstep2", 86, 4, 12, 2, 128, "bf16", np.full(4, 40, np.int32),
+                    np.full(4, 64, np.int32), np.array([4, 4, 0, 8], np.int32))
+    rt, oc = make(wl, dev)
+    for t in range(1, 5):                       # after 4 tokens: sequences 0, 1 are due (c = 4)
+        k, v = wl.step_kv(t)
+        rt.decode_step(k, v, wl.step_q(t))
+        oc.append(k, v)
+    bk, bv = wl.beacon_kv(4)
+    qb = wl.beacon_q(4)
+    rt.out.fill_(-7.0)
+    o = rt.beacon_step(bk, bv, qb, active=np.array([1, 0, 1, 1], np.uint8)).cpu().numpy()
+    mask = np.array([1, 0, 1, 1], np.uint8)
+    oc.append(bk, bv, active=mask, beacon=True)
+    check_attention(o, qb, oc, wl, [0])
+    oc.compress_evict(active=mask)
+    assert np.all(o[1] == -7.0) and np.all(o[2] == -7.0) and np.all(o[3] == -7.0)
+    nb, w = check_tables(rt, oc)
+    assert list(nb) == [1, 0, 0, 0] and list(w) == [0, 4, 4, 4]
+    check_slabs(rt, oc)
 
 
 def test_fused_step_ragged_ratios_and_errors(dev):

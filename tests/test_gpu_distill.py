@@ -48,7 +48,7 @@ def _check(wl, ts, dev, gs=None):
     return loss, dz
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("V,k", [(1000, 100), (1001, 100), (4104, 1), (64, 64), (8, 3), (5000, 700)])
 def test_small_vocabularies(dev, dtype, V, k):
     # 1000: whole 16-byte units; 1001: element-wise path; k = 1, k = V, k > 256 (several per thread)
@@ -62,7 +62,7 @@ def test_paper_vocabulary_all_rows(dev):
 
 
 def test_paper_vocabulary_fp32(dev):
-    wl = W.distill(T=6, dtype="fp32")
+    wl = W.distill(T=6, dtype="f32")
     _check(wl, range(6), dev)
 
 
