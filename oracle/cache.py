@@ -148,6 +148,26 @@ class BatchCache:
             if live[s] and len(self.beacons[s]) + len(self.window[s]) >= budget[s]:
                 live[s] = 0
 
+    def admit(self, admit, prompts_k, prompts_v, new_c=None, live=None):
+        """A new sequence takes over a slot whose generation is over (the evaluation rule of
+        Sec. 4 ends generations at different times; the slot's capacity stays).  Equivalent to
+        Alg. 1's initialisation for that slot alone: prompt entries, no beacons, empty window.
+        A prompt longer than the slot is a capacity error and leaves the slot as it was."""
+        for s in range(self.B):
+            if not admit[s]:
+                continue
+            if len(prompts_k[s]) > self.cap[s]:
+                self.err |= ERR_CAPACITY
+                continue
+            self.P[s] = len(prompts_k[s])
+            self.prompt[s] = [(prompts_k[s][j], prompts_v[s][j]) for j in range(self.P[s])]
+            self.beacons[s] = []
+            self.window[s] = []
+            if new_c is not None:
+                self.c[s] = int(new_c[s])
+            if live is not None:
+                live[s] = 1
+
     # -- views --------------------------------------------------------------
     def resident(self, s):
         """(K, V) [L, Hkv, d] of sequence s in cache order."""

@@ -3,7 +3,7 @@
 import numpy as np
 
 from oracle import residency as R
-from oracle.cache import BatchCache, ERR_STATE
+from oracle.cache import BatchCache, ERR_CAPACITY, ERR_STATE
 
 
 def _rows(rng, n, Hkv=1, d=2):
@@ -81,3 +81,33 @@ def test_ratio_change_refused_when_window_does_not_fit():
     cache.err = 0
     cache.set_ratio([0, 0], active=[1, 0])      # switching compression off is always allowed
     assert cache.err == 0 and cache.c == [0, 6]
+
+
+def test_admitted_slot_behaves_like_a_fresh_cache():
+    # a slot taken over by a new sequence must evolve exactly like a cache created for that
+    # sequence (Alg. 1 from its initialisation), whatever the slot held before
+    rng = np.random.default_rng(9)
+    Hkv, d = 2, 4
+    mk = lambda n: rng.standard_normal((n, Hkv, d))
+    pk, pv = [mk(5), mk(3)], [mk(5), mk(3)]
+    old = BatchCache(pk, pv, [2, 3], [40, 40])
+    for t in range(1, 8):
+        old.append(mk(2), mk(2))
+        old.compress_evict(mk(2), mk(2))
+    nk, nv = mk(7), mk(7)
+    live = [0, 1]
+    old.admit([1, 0], [nk, None], [nv, None], new_c=[4, 0], live=live)
+    assert live == [1, 1] and old.P[0] == 7 and old.c == [4, 3] and old.nb[0] == 0 and old.w[0] == 0
+    fresh = BatchCache([nk], [nv], [4], [40])
+    for t in range(1, 14):
+        k, v, bk, bv = mk(2), mk(2), mk(2), mk(2)
+        old.append(k, v); fresh.append(k[:1], v[:1])
+        old.compress_evict(bk, bv); fresh.compress_evict(bk[:1], bv[:1])
+        Ko, Vo = old.resident(0); Kf, Vf = fresh.resident(0)
+        assert np.array_equal(Ko, Kf) and np.array_equal(Vo, Vf)
+        assert old.L(0) == R.len_after_step(7, 4, t)
+    assert old.err == 0
+    # too long a prompt: capacity error, slot untouched
+    before = old.resident(1)[0].copy()
+    old.admit([0, 1], [None, mk(41)], [None, mk(41)])
+    assert old.err == ERR_CAPACITY and np.array_equal(old.resident(1)[0], before)
