@@ -78,7 +78,7 @@ typedef struct {
   void *k_slab, *v_slab; /* sum_s cap[s]*Hkv*d elements each                      */
   const int64_t *base;   /* [B] first entry of sequence s (in entries of Hkv*d)   */
   const int32_t *cap;    /* [B] rows per KV head                                  */
-  const int32_t *P;      /* [B] prompt length                                     */
+  int32_t *P;            /* [B] prompt length         (rewritten by bc_cache_admit) */
   int32_t *c;            /* [B] compression ratio; <= 0: never compress (bc_set_ratio) */
   int32_t *nb;           /* [B] beacons so far           (updated by the library) */
   int32_t *w;            /* [B] rows after the beacons   (updated by the library) */
@@ -98,6 +98,21 @@ int32_t bc_version(void);
 int32_t bc_cache_init(const bc_shape *shape, const bc_cache *cache, const void *k_prompt,
                       const void *v_prompt, const int64_t *prompt_offsets,
                       int64_t total_rows, void *stream);
+
+/* Admission of new sequences into the slots of finished ones (the evaluation rule of Sec. 4 ends
+ * generations at different times; a slot's slab can then serve the next request).  For every s
+ * with admit[s] != 0, slot s starts over as Alg. 1 initialises a cache: the rows
+ * [prompt_offsets[s], prompt_offsets[s+1]) of k_prompt / v_prompt become its prompt,
+ * P[s] = that span, nb = w = 0, c[s] = new_c[s] when new_c is given, live[s] = 1 when live is
+ * given.  base[s] and cap[s] stay: a prompt longer than cap[s] sets the capacity bit and leaves
+ * the slot (and live[s]) as it was.  Slots with admit[s] == 0 are not touched and their spans are
+ * ignored (normally empty).  prompt_offsets: device [B+1] int64; total_rows: host copy of
+ * prompt_offsets[B]; new_c: device [B] int32 or NULL; admit: device [B] bytes; live: device [B]
+ * bytes or NULL (the mask of bc_decode_step_budget).  There is no block table: compaction keeps
+ * every sequence contiguous and bounded by P + G/c + c + 1 rows, so a slot is one fixed slab. */
+int32_t bc_cache_admit(const bc_shape *shape, const bc_cache *cache, const void *k_prompt,
+                       const void *v_prompt, const int64_t *prompt_offsets, int64_t total_rows,
+                       const int32_t *new_c, const uint8_t *admit, uint8_t *live, void *stream);
 
 /* Append one row per active sequence (Alg. 1: "KV is updated internally" for a token;
  * "encode b" for a beacon).  k, v: [B, Hkv, d].

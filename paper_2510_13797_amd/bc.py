@@ -25,7 +25,7 @@ BC_ERRBIT_STATE, BC_ERRBIT_CAPACITY = 1, 2
 BC_ROW_TOKEN, BC_ROW_BEACON = 0, 1
 
 EXPORTS = [
-    "bc_status_str", "bc_version", "bc_cache_init", "bc_append_kv",
+    "bc_status_str", "bc_version", "bc_cache_init", "bc_cache_admit", "bc_append_kv",
     "bc_decode_workspace_bytes", "bc_workspace_init", "bc_decode_attn",
     "bc_compress_evict", "bc_decode_step", "bc_beacon_step", "bc_decode_step_budget", "bc_set_ratio",
     "bc_prefill_attn", "bc_prefill_bwd_workspace_bytes", "bc_prefill_attn_bwd",
@@ -70,6 +70,8 @@ def load():
     lib.bc_version.restype = i32
     lib.bc_cache_init.restype = i32
     lib.bc_cache_init.argtypes = [sp, cp, vp, vp, vp, i64, vp]
+    lib.bc_cache_admit.restype = i32
+    lib.bc_cache_admit.argtypes = [sp, cp, vp, vp, vp, i64, vp, vp, vp, vp]
     lib.bc_append_kv.restype = i32
     lib.bc_append_kv.argtypes = [sp, cp, vp, vp, vp, i32, vp]
     lib.bc_decode_workspace_bytes.restype = sz
@@ -122,6 +124,11 @@ def bc_version():
 def bc_cache_init(shape, cache, k_prompt, v_prompt, prompt_offsets, total_rows, stream):
     return load().bc_cache_init(C.byref(shape), C.byref(cache), k_prompt, v_prompt, prompt_offsets,
                                 total_rows, stream)
+
+
+def bc_cache_admit(shape, cache, k_prompt, v_prompt, prompt_offsets, total_rows, new_c, admit, live, stream):
+    return load().bc_cache_admit(C.byref(shape), C.byref(cache), k_prompt, v_prompt, prompt_offsets,
+                                 total_rows, new_c, admit, live, stream)
 
 
 def bc_append_kv(shape, cache, k, v, active, kind, stream):
@@ -298,6 +305,31 @@ class Runtime:
         _check(bc_cache_init(self.shape, self.cache, _ptr(kp), _ptr(vp), _ptr(offd), total,
                              _stream_ptr()))
         torch.cuda.current_stream().synchronize()     # inputs may be freed after this
+
+    def cache_admit(self, admit, prompts_k, prompts_v, new_c=None, live=None):
+        """admit: [B] 0/1; prompts_k/v: per slot [P, Hkv, d] arrays (ignored where admit is 0);
+        new_c: [B] or None; live: uint8 device tensor [B] or None."""
+        torch = self.torch
+        admit = np.asarray(admit, dtype=np.uint8)
+        spans = [len(prompts_k[s]) if admit[s] else 0 for s in range(self.B)]
+        off = np.zeros(self.B + 1, dtype=np.int64)
+        off[1:] = np.cumsum(spans)
+        total = int(off[-1])
+        rows = [s for s in range(self.B) if admit[s] and spans[s]]
+        if total:
+            kp = self.dev(np.concatenate([np.asarray(prompts_k[s], np.float32) for s in rows], axis=0))
+            vp = self.dev(np.concatenate([np.asarray(prompts_v[s], np.float32) for s in rows], axis=0))
+        else:
+            kp = vp = None
+        offd = torch.from_numpy(off).to(self.device)
+        ad = torch.from_numpy(admit).to(self.device)
+        ncd = None if new_c is None else torch.from_numpy(np.asarray(new_c, dtype=np.int32)).to(self.device)
+        _check(bc_cache_admit(self.shape, self.cache, _ptr(kp), _ptr(vp), _ptr(offd), total, _ptr(ncd),
+                              _ptr(ad), _ptr(live), _stream_ptr()))
+        torch.cuda.current_stream().synchronize()
+        for s in range(self.B):           # host mirror of P, used by resident()
+            if admit[s] and spans[s] <= int(self.cap_host[s]):
+                self.P_host[s] = spans[s]
 
     def append_kv(self, k, v, active=None, kind=BC_ROW_TOKEN):
         k, v, a = self.dev(k), self.dev(v), self.mask(active)

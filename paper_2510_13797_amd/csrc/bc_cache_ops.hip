@@ -38,9 +38,12 @@ __device__ __forceinline__ int64_t row_offset(const CacheView& cv, int s, int kv
 // ---------------------------------------------------------------------------
 // Prompt fill: one 16-byte unit per thread; sequence found by binary search.
 // ---------------------------------------------------------------------------
+// admit == NULL: fill every sequence whose span equals P[s]; otherwise fill the slots selected by
+// admit[] (their P[s] is being rewritten by the table kernel of the same call).
 __global__ void cache_init_kernel(CacheView cv, const char* __restrict__ kp,
                                   const char* __restrict__ vp,
-                                  const int64_t* __restrict__ off, int B, int64_t total_rows) {
+                                  const int64_t* __restrict__ off, int B, int64_t total_rows,
+                                  const uint8_t* __restrict__ admit) {
   const int units_per_row = cv.row_bytes >> 4;
   const int64_t units_per_tok = (int64_t)units_per_row * cv.Hkv;
   const int64_t n = total_rows * units_per_tok;
@@ -58,7 +61,8 @@ __global__ void cache_init_kernel(CacheView cv, const char* __restrict__ kp,
     const int j = (int)(tok - off[s]);
     const int cap = cv.cap[s];
     const int64_t span = off[s + 1] - off[s];
-    if (span != cv.P[s] || span > cap) continue;     // flagged by the table kernel
+    if (span > cap) continue;                          // flagged by the table kernel
+    if (admit ? !admit[s] : span != cv.P[s]) continue;
     const int64_t dst = row_offset(cv, s, kvh, cap, j) + ((int64_t)u << 4);
     *reinterpret_cast<uint4*>(cv.k_slab + dst) = reinterpret_cast<const uint4*>(kp)[i];
     *reinterpret_cast<uint4*>(cv.v_slab + dst) = reinterpret_cast<const uint4*>(vp)[i];
@@ -73,6 +77,21 @@ __global__ void cache_init_tables_kernel(CacheView cv, const int64_t* __restrict
   else if (span > cv.cap[s]) atomicOr(cv.err, BC_ERRBIT_CAPACITY);
   cv.nb[s] = 0;
   cv.w[s] = 0;
+}
+
+// Slots taken over by new sequences: prompt length, ratio, counters, live flag.
+__global__ void admit_tables_kernel(CacheView cv, int32_t* P, const int64_t* __restrict__ off,
+                                    const int32_t* __restrict__ new_c,
+                                    const uint8_t* __restrict__ admit, uint8_t* live, int B) {
+  const int s = blockIdx.x * blockDim.x + threadIdx.x;
+  if (s >= B || !admit[s]) return;
+  const int64_t span = off[s + 1] - off[s];
+  if (span < 0 || span > cv.cap[s]) { atomicOr(cv.err, BC_ERRBIT_CAPACITY); return; }
+  P[s] = (int32_t)span;
+  if (new_c) cv.c[s] = new_c[s];
+  cv.nb[s] = 0;
+  cv.w[s] = 0;
+  if (live) live[s] = 1;
 }
 
 // ---------------------------------------------------------------------------
@@ -232,8 +251,35 @@ extern "C" int32_t bc_cache_init(const bc_shape* shape, const bc_cache* cache, c
     const int grid = (int)(blocks < 65536 ? blocks : 65536);
     cache_init_kernel<<<grid, 256, 0, s>>>(cv, static_cast<const char*>(k_prompt),
                                            static_cast<const char*>(v_prompt), prompt_offsets,
-                                           shape->B, total_rows);
+                                           shape->B, total_rows, nullptr);
   }
+  return launch_status();
+}
+
+extern "C" int32_t bc_cache_admit(const bc_shape* shape, const bc_cache* cache, const void* k_prompt,
+                                  const void* v_prompt, const int64_t* prompt_offsets,
+                                  int64_t total_rows, const int32_t* new_c, const uint8_t* admit,
+                                  uint8_t* live, void* stream) {
+  int32_t st = check_shape(shape);
+  if (st != BC_OK) return st;
+  st = check_cache(cache);
+  if (st != BC_OK) return st;
+  if (!prompt_offsets || !admit || total_rows < 0) return BC_ERR_ARG;
+  if (total_rows > 0 && (!k_prompt || !v_prompt || !aligned16(k_prompt) || !aligned16(v_prompt)))
+    return BC_ERR_ARG;
+  CacheView cv = make_view(shape, cache);
+  hipStream_t s = as_stream(stream);
+  // the fill does not read the tables the other kernel writes, so their order is free
+  if (total_rows > 0) {
+    const int64_t units = total_rows * shape->Hkv * (cv.row_bytes >> 4);
+    const int64_t blocks = (units + 255) / 256;
+    const int grid = (int)(blocks < 65536 ? blocks : 65536);
+    cache_init_kernel<<<grid, 256, 0, s>>>(cv, static_cast<const char*>(k_prompt),
+                                           static_cast<const char*>(v_prompt), prompt_offsets,
+                                           shape->B, total_rows, admit);
+  }
+  admit_tables_kernel<<<(shape->B + 255) / 256, 256, 0, s>>>(cv, cache->P, prompt_offsets, new_c,
+                                                             admit, live, shape->B);
   return launch_status();
 }
 

@@ -399,6 +399,58 @@ def test_budget_rule_interrupts_generation_on_device(dev, dtype, d):
         assert last[s] == OR.first_step_reaching(int(budget[s]), int(c[s])), (s, last[s])
 
 
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64)])
+def test_admission_into_finished_slots(dev, dtype, d):
+    # continuous batching: the budget rule ends generations at different steps; every 10 steps
+    # the finished slots take new sequences (new prompt length and ratio) and carry on
+    import torch
+    B = 6
+    c = np.array([1, 2, 4, 16, 0, 3], np.int32)
+    Hq, Hkv = (12, 2) if d == 128 else (4, 1)
+    wl = W.Workload("admit", 93, B, Hq, Hkv, d, dtype, np.array([3, 0, 17, 32, 5, 64], np.int32),
+                    np.full(B, 400, np.int32), c)
+    cap = np.full(B, 120, np.int32)
+    rt, oc = make(wl, dev, cap)
+    budget = np.array([10, 12, 7, 20, 9, 15], np.int32)
+    bud_d = torch.from_numpy(budget).to(dev)
+    live_d = torch.ones(B, dtype=torch.uint8, device=dev)
+    live = [1] * B
+    rng = np.random.default_rng(17)
+    admitted = 0
+    for t in range(1, 161):
+        k, v = wl.step_kv(t)
+        q = wl.step_q(t)
+        bk, bv = wl.beacon_kv(t)
+        o = rt.decode_step_budget(k, v, q, bk, bv, bud_d, live_d).cpu().numpy()
+        was = list(live)
+        oc.append(k, v, active=was)
+        act = [s for s in range(B) if was[s]]
+        if act:
+            check_attention(o, q, oc, wl, act, t)
+        oc.apply_budget(budget, live)
+        oc.compress_evict(bk, bv, active=was)
+        if t % 10 == 0:
+            adm = np.array([0 if x else 1 for x in live], np.uint8)
+            if t == 40:
+                adm[:] = 0
+                adm[[s for s in range(B) if not live[s]][:1]] = 1     # one slot with too long a prompt
+            newP = [int(rng.integers(1, 90)) for _ in range(B)]
+            if t == 40:
+                newP = [121] * B
+            pk = [W.round_to_dtype(rng.standard_normal((newP[s], Hkv, d)), dtype) for s in range(B)]
+            pv = [W.round_to_dtype(rng.standard_normal((newP[s], Hkv, d)), dtype) for s in range(B)]
+            new_c = rng.choice([0, 1, 2, 3, 5, 8], size=B).astype(np.int32)
+            rt.cache_admit(adm, pk, pv, new_c, live_d)
+            oc.admit(adm, pk, pv, new_c, live)
+            admitted += int(adm.sum())
+        assert live_d.cpu().tolist() == live, t
+        check_tables(rt, oc, t)
+        assert rt.c.cpu().tolist() == oc.c and rt.P.cpu().tolist() == oc.P, t
+        if t % 10 == 0 or t == 160:
+            check_slabs(rt, oc, None, t)
+    assert admitted >= 12 and oc.err == ERR_CAPACITY
+
+
 def test_ratio_change_mid_generation(dev):
     B = 4
     wl = W.Workload("ratio", 92, B, 12, 2, 128, "bf16", np.array([8, 0, 40, 3], np.int32),
