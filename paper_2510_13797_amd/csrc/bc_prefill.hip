@@ -56,6 +56,8 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {      // RNE, a
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(pf_f32x2_t{a, b}, bf16x2_t));
 }
 
+constexpr float kPfLazy = 5.0f;
+
 template <int HPW>     // query heads per wave (the group's heads are split over two wave sets)
 __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams p) {
   __shared__ __attribute__((aligned(1024))) char lds[kPfLds];
@@ -217,9 +219,14 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
                          fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
       tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
       tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-      const float m_new = fmaxf(m_run[h], tmax * p.qscale);     // kNegBig * qs stays hugely negative
+      // Lazy reference: the running reference m only moves when the tile's maximum exceeds it by
+      // more than kPfLazy (log2 units); until then weights are at most 2^kPfLazy, which fp32 sums
+      // and the two-part bf16 weights carry without loss, and the accumulators need no rescale.
+      const float m_cand = tmax * p.qscale;                     // kNegBig * qs stays hugely negative
+      const bool grow = m_cand > m_run[h] + kPfLazy;
+      const float m_new = grow ? m_cand : m_run[h];
       alpha[h] = fast_exp2(m_run[h] - m_new);
-      any_rescale = any_rescale || (m_new != m_run[h]);
+      any_rescale = any_rescale || grow;
       m_run[h] = m_new;
       float pe[8];
 #pragma unroll
