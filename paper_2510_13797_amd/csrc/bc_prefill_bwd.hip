@@ -52,6 +52,8 @@ struct BwdParams {
   float* dk;
   float* dv;
   float* stat;          // [Hq][total_rows][2]: lse*log2(e), Delta
+  float* part;          // [hsplit][2][total_rows][Hkv][128]: dk, dv partials of the dense key blocks
+  int32_t hsplit;       // head splits of a dense key block (1: none), heads per split = ceil(g / hsplit)
   int64_t total_rows;
   int32_t Hq, Hkv, g;
   float scale;
@@ -325,8 +327,22 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dkv_kernel(BwdPa
   const int nbeac = c > 0 ? (int)__umulhi((uint32_t)nresp, magic) : 0;   // complete windows
   const int NPB = (Pk + kBwBM - 1) / kBwBM, NBB = (nbeac + kBwBM - 1) / kBwBM;
   const int NLB = (nresp + kBwBM - 1) / kBwBM;
-  const int blk = blockIdx.y;
-  if (blk >= NPB + NBB + NLB) return;
+  // The dense blocks (prompt keys, beacons) stream every later row of every head; each is cut
+  // into `hsplit` workgroups by query heads, whose partial sums a second kernel adds in a fixed
+  // order.  The short response blocks take all heads and store their result directly.
+  const int nd = NPB + NBB;
+  int blk, h_begin = 0, h_end = p.g, split = -1;
+  if ((int)blockIdx.y < nd * p.hsplit) {
+    blk = blockIdx.y / p.hsplit;
+    if (p.hsplit > 1) {
+      split = blockIdx.y - blk * p.hsplit;
+      const int hps = (p.g + p.hsplit - 1) / p.hsplit;
+      h_begin = split * hps; h_end = min(p.g, h_begin + hps);
+    }
+  } else {
+    blk = nd + ((int)blockIdx.y - nd * p.hsplit);
+  }
+  if (blk >= nd + NLB) return;
   const int kind = blk < NPB ? 0 : blk < NPB + NBB ? 1 : 2;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -370,11 +386,12 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dkv_kernel(BwdPa
   }
 
   const int ntile = (re - rs) / kBwBN + 1;     // row tiles per head
-  const int NT = ntile * p.g;                  // streamed tiles: head-major
+  const int NT = ntile * (h_end - h_begin);     // streamed tiles: head-major
   const int64_t q_row_bytes = (int64_t)p.Hq * 256;
   const int ld_rr = 4 * wave + (lane >> 4);
   auto issue_tile = [&](int it, int stage) {
-    const int h = it / ntile, rt = it - h * ntile;
+    const int hl = it / ntile, rt = it - hl * ntile;
+    const int h = h_begin + hl;
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
       const int tr = ld_rr + 16 * half;                       // entry of the tile
@@ -475,9 +492,46 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dkv_kernel(BwdPa
     const int ok = __shfl((int)key_ok, t, 64);
     return ok ? base + ((off0 + jk) * p.Hkv + kvh) * 128 : nullptr;
   };
-  bw_store_tile(my, dK, p.scale, lane, [&](int t) { return dst_of(p.dk, t); });
-  bw_store_tile(my, dV, 1.0f, lane, [&](int t) { return dst_of(p.dv, t); });
+  float* dk_base = p.dk;
+  float* dv_base = p.dv;
+  if (split >= 0) {
+    const int64_t plane = p.total_rows * p.Hkv * 128;
+    dk_base = p.part + (int64_t)(2 * split) * plane;
+    dv_base = dk_base + plane;
+  }
+  bw_store_tile(my, dK, p.scale, lane, [&](int t) { return dst_of(dk_base, t); });
+  bw_store_tile(my, dV, 1.0f, lane, [&](int t) { return dst_of(dv_base, t); });
 }
+
+// Sum of the head-split partials of the dense keys (prompt rows and beacons), in split order.
+// One thread per 16 bytes of one (row, KV head); rows that are not dense were written directly.
+__global__ __launch_bounds__(256) void prefill_bwd_reduce_kernel(BwdParams p, int B) {
+  const int64_t units = p.total_rows * p.Hkv * 32;
+  const int64_t plane = p.total_rows * p.Hkv * 128;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < units;
+       i += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t row = i / (p.Hkv * 32);
+    int lo = 0, hi = B;                        // largest b with row_off[b] <= row
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (p.row_off[mid] <= row) lo = mid; else hi = mid;
+    }
+    const int j = (int)(row - p.row_off[lo]);
+    const int P0 = p.P[lo], c = p.c[lo];
+    const bool dense = c <= 0 || j < P0 || (j - P0) % (c + 1) == c;
+    if (!dense) continue;
+    f32x4_t sk = f32x4_t{0.f, 0.f, 0.f, 0.f}, sv = sk;
+    for (int sp = 0; sp < p.hsplit; ++sp) {
+      sk += *reinterpret_cast<const f32x4_t*>(p.part + (int64_t)(2 * sp) * plane + i * 4);
+      sv += *reinterpret_cast<const f32x4_t*>(p.part + (int64_t)(2 * sp + 1) * plane + i * 4);
+    }
+    *reinterpret_cast<f32x4_t*>(p.dk + i * 4) = sk;
+    *reinterpret_cast<f32x4_t*>(p.dv + i * 4) = sv;
+  }
+}
+
+// head splits of the dense key blocks: two when the group has several heads
+static int bwd_head_splits(int g) { return g >= 2 ? 2 : 1; }
 
 }  // namespace bc
 
@@ -485,7 +539,11 @@ using namespace bc;
 
 extern "C" size_t bc_prefill_bwd_workspace_bytes(const bc_shape* shape, int64_t total_rows) {
   if (check_shape(shape) != BC_OK || total_rows < 1) return 0;
-  return (size_t)total_rows * shape->Hq * 2 * sizeof(float);
+  const int g = shape->Hq / shape->Hkv;
+  const int hs = bwd_head_splits(g);
+  size_t bytes = (size_t)total_rows * shape->Hq * 2 * sizeof(float);
+  if (hs > 1) bytes += (size_t)hs * 2 * total_rows * shape->Hkv * 128 * sizeof(float);
+  return bytes;
 }
 
 extern "C" int32_t bc_prefill_attn_bwd(const bc_shape* shape, const void* q, const void* k,
@@ -514,6 +572,8 @@ extern "C" int32_t bc_prefill_attn_bwd(const bc_shape* shape, const void* q, con
   p.row_off = row_offsets; p.P = P; p.c = c;
   p.dq = dq; p.dk = dk; p.dv = dv;
   p.stat = static_cast<float*>(workspace);
+  p.part = p.stat + (size_t)total_rows * shape->Hq * 2;
+  p.hsplit = bwd_head_splits(shape->Hq / shape->Hkv);
   p.total_rows = total_rows;
   p.Hq = shape->Hq; p.Hkv = shape->Hkv; p.g = shape->Hq / shape->Hkv;
   p.scale = shape->scale;
@@ -523,6 +583,11 @@ extern "C" int32_t bc_prefill_attn_bwd(const bc_shape* shape, const void* q, con
   const int nhg = (p.g + kDqHeads - 1) / kDqHeads;
   prefill_bwd_dq_kernel<<<dim3(shape->B * shape->Hkv * nhg, tiles), kBwWaves * 64, 0, hs>>>(p);
   // key blocks: at most `tiles` dense-causal blocks + the gathered beacons + `tiles` response blocks
-  prefill_bwd_dkv_kernel<<<dim3(shape->B * shape->Hkv, 3 * tiles + 2), kBwWaves * 64, 0, hs>>>(p);
+  prefill_bwd_dkv_kernel<<<dim3(shape->B * shape->Hkv, (2 * tiles + 2) * p.hsplit + tiles),
+                           kBwWaves * 64, 0, hs>>>(p);
+  if (p.hsplit > 1) {
+    const int64_t blocks = (total_rows * shape->Hkv * 32 + 255) / 256;
+    prefill_bwd_reduce_kernel<<<(int)(blocks < 65536 ? blocks : 65536), 256, 0, hs>>>(p, shape->B);
+  }
   return launch_status();
 }
