@@ -46,6 +46,8 @@ struct DecodeParams {
   const int32_t* budget;   // [B] cap on nb + w (nullable), with
   uint8_t* live;           // [B] cleared when the cap is reached
   int32_t beacon_row;  // the fused row is the beacon closing a full window (bk = new_k, bv = new_v)
+  int32_t lpt;         // workgroups take the sequences in order of decreasing length (B <= kLptMaxB)
+  int32_t B;
   int32_t debug_stage; // experiments only: leave the kernel early (0 = run everything)
   int32_t Hq, Hkv, g;  // g = real group size
   int32_t Gp;          // padded group size of the partial layout
@@ -68,18 +70,90 @@ struct PairInfo {
 // Common prologue: which rows does this workgroup own?  Uniform across the workgroup.  All
 // table loads are issued together.  With a fused append the state rules of bc_append_kv are
 // applied here, identically in every workgroup of the sequence.
-__device__ __forceinline__ PairInfo pair_info(const DecodeParams& p) {
+constexpr int kLptMaxB = 256;        // the pick costs about 2 B^2 lane operations per workgroup
+constexpr int kLptMinPairs = 256;   // compute units of the chip: below this every workgroup starts at once
+
+// Longest sequence first: with more workgroups than the chip holds at once and ragged lengths,
+// the dispatch order decides the tail.  Workgroup number i (in dispatch order) takes the
+// sequence with the i-th largest resident length.  Every workgroup reads all tables once (no
+// second, dependent read for the chosen sequence), ranks the B lengths itself (keys made unique
+// by the index, so the ranks are a permutation) and picks its sequence: about 2 microseconds at
+// B = 256, growing with B^2, hence the limit on B.
+// scratch: kLptScratchBytes of LDS, free again after the caller's next barrier.
+constexpr int kLptScratchBytes = 10 * kLptMaxB * 4;
+struct LptPick { int s, act, P, nb, w, cap, c; int64_t base; };
+
+__device__ __forceinline__ LptPick lpt_sequence(const DecodeParams& p, int target_rank, char* scratch) {
+  int* s_key = reinterpret_cast<int*>(scratch);          // [Bp] sort keys
+  int* s_rank = s_key + kLptMaxB;                        // [B] number of larger keys
+  int* s_tab = s_rank + kLptMaxB;                        // [6][kLptMaxB]: act, P, nb, w, cap, c
+  int64_t* s_base = reinterpret_cast<int64_t*>(s_tab + 6 * kLptMaxB);
+  __shared__ int s_pick;
+  const int Bp = (p.B + 3) & ~3;
+  for (int t = threadIdx.x; t < Bp; t += blockDim.x) {
+    int key = -1;                                     // padding and inactive sequences rank last
+    if (t < p.B) {
+      const int act = p.active ? p.active[t] : 1;
+      const int P = p.P[t], nb = p.nb[t], w = p.w[t];
+      s_tab[t] = act; s_tab[kLptMaxB + t] = P; s_tab[2 * kLptMaxB + t] = nb;
+      s_tab[3 * kLptMaxB + t] = w; s_tab[4 * kLptMaxB + t] = p.cap[t];
+      s_tab[5 * kLptMaxB + t] = p.c ? p.c[t] : 0;
+      s_base[t] = p.base[t];
+      const int len = act ? P + nb + w + 1 : 0;
+      key = (len << 10) | (1023 - t);                 // lengths stay below 2^20, t below 2^10
+      s_rank[t] = 0;
+    }
+    s_key[t] = key;
+  }
+  __syncthreads();
+  // every thread counts the larger keys in its share of the list for one sequence
+  const int parts = max(1, (int)blockDim.x / p.B);
+  const int span = (((Bp + parts - 1) / parts) + 3) & ~3;
+  for (int i = threadIdx.x; i < parts * p.B; i += blockDim.x) {
+    const int part = i / p.B, t = i - part * p.B;
+    const int mine = s_key[t];
+    const int u0 = part * span, u1 = min(Bp, u0 + span);
+    int cnt = 0;
+#pragma unroll 4
+    for (int u = u0; u < u1; u += 4) {
+      const int4 o = *reinterpret_cast<const int4*>(s_key + u);
+      cnt += (o.x > mine) + (o.y > mine) + (o.z > mine) + (o.w > mine);
+    }
+    if (parts == 1) s_rank[t] = cnt; else atomicAdd(&s_rank[t], cnt);
+  }
+  __syncthreads();
+  for (int t = threadIdx.x; t < p.B; t += blockDim.x)
+    if (s_rank[t] == target_rank) s_pick = t;
+  __syncthreads();
+  LptPick r;
+  r.s = s_pick;
+  r.act = s_tab[r.s]; r.P = s_tab[kLptMaxB + r.s]; r.nb = s_tab[2 * kLptMaxB + r.s];
+  r.w = s_tab[3 * kLptMaxB + r.s]; r.cap = s_tab[4 * kLptMaxB + r.s];
+  r.c = s_tab[5 * kLptMaxB + r.s]; r.base = s_base[r.s];
+  return r;
+}
+
+__device__ __forceinline__ PairInfo pair_info(const DecodeParams& p, char* scratch = nullptr) {
   PairInfo pi;
-  const int pair = blockIdx.y;
-  pi.s = pair / p.Hkv;
-  pi.kvh = pair - pi.s * p.Hkv;
-  const int act = p.active ? p.active[pi.s] : 1;
-  pi.P = p.P[pi.s];
-  pi.nb = p.nb[pi.s];
-  const int w = p.w[pi.s];
-  pi.cap = p.cap[pi.s];
-  pi.base = p.base[pi.s];
-  pi.c = p.c ? p.c[pi.s] : 0;
+  int act, w;
+  if (p.lpt && scratch) {
+    const int rank = blockIdx.y / p.Hkv;
+    const LptPick k = lpt_sequence(p, rank, scratch);
+    pi.s = k.s; pi.kvh = blockIdx.y - rank * p.Hkv;
+    act = k.act; pi.P = k.P; pi.nb = k.nb; w = k.w; pi.cap = k.cap; pi.c = k.c; pi.base = k.base;
+    __syncthreads();                   // the scratch area is free from here on
+  } else {
+    const int pair = blockIdx.y;
+    pi.s = pair / p.Hkv;
+    pi.kvh = pair - pi.s * p.Hkv;
+    act = p.active ? p.active[pi.s] : 1;
+    pi.P = p.P[pi.s];
+    pi.nb = p.nb[pi.s];
+    w = p.w[pi.s];
+    pi.cap = p.cap[pi.s];
+    pi.base = p.base[pi.s];
+    pi.c = p.c ? p.c[pi.s] : 0;
+  }
   const bool herald = blockIdx.x == 0 && pi.kvh == 0 && threadIdx.x == 0;   // reports errors
   pi.live = false;
   pi.update = false; pi.evict_due = false; pi.new_row = -1;
@@ -128,7 +202,7 @@ __device__ __forceinline__ PairInfo pair_info(const DecodeParams& p) {
       }
     }
   }
-  if (p.part_n && blockIdx.x == 0 && threadIdx.x == 0) p.part_n[pair] = pi.nchunks;
+  if (p.part_n && blockIdx.x == 0 && threadIdx.x == 0) p.part_n[pi.s * p.Hkv + pi.kvh] = pi.nchunks;
   return pi;
 }
 
@@ -139,7 +213,7 @@ __device__ __forceinline__ void merge_waves_and_store(const DecodeParams& p, con
                                                       const float* s_m, const float* s_l,
                                                       const float* s_acc, int gstride) {
   const int nout = p.g * D;
-  const int pair = blockIdx.y;
+  const int pair = pi.s * p.Hkv + pi.kvh;
   float* po = p.part_o + ((int64_t)pair * p.max_chunks + pi.chunk) * (p.Gp * D);
   float* pml = p.part_ml + ((int64_t)pair * p.max_chunks + pi.chunk) * (2 * p.Gp);
   float* outp = p.out + (int64_t)(pi.s * p.Hq + pi.kvh * p.g) * D;
@@ -171,6 +245,7 @@ constexpr int kLdsWaves = 8;           // waves per workgroup
 constexpr int kTileRows = 32;          // rows per wave tile
 constexpr int kTileBytes = kTileRows * 256;   // one K (or V) tile: 8 KB
 constexpr int kLdsBytes = kLdsWaves * 2 * kTileBytes;   // 128 KB
+static_assert(kLptScratchBytes <= kLdsBytes, "the pick's scratch lives in the tile area");
 
 typedef __attribute__((address_space(3))) void lds_void_t;
 typedef __attribute__((address_space(1))) const void global_void_t;
@@ -185,7 +260,7 @@ __device__ __forceinline__ uint32_t bf16_rne_bits(float x) {     // finite x onl
 __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams p) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   if (p.debug_stage == 1) return;
-  const PairInfo pi = pair_info(p);
+  const PairInfo pi = pair_info(p, lds);
   if (!pi.live) return;
   if (p.debug_stage == 2) { if (pi.L == 12345678) p.out[0] = 1.f; return; }
 
@@ -690,6 +765,14 @@ static int32_t launch_attention(const bc_shape* shape, const bc_cache* cache, co
   p.bk = static_cast<const char*>(bk); p.bv = static_cast<const char*>(bv);
   p.budget = budget; p.live = live;
   p.beacon_row = beacon_row ? 1 : 0;
+  p.B = shape->B;
+  // Ragged batches that need more than one round of workgroups: longest sequence first.  Only
+  // for launches that leave the tables alone: a fused step updates nb and w of a sequence when
+  // its last workgroup ends, so later workgroups would rank different lengths and the picks
+  // would no longer form a permutation.
+  p.lpt = (pl.lds && pl.max_chunks == 1 && !k && !bk && !budget && shape->B <= kLptMaxB &&
+           shape->B * shape->Hkv > kLptMinPairs && cache->max_cap < (1 << 20) && g_variant != 3)
+              ? 1 : 0;
   p.Hq = shape->Hq; p.Hkv = shape->Hkv; p.g = shape->Hq / shape->Hkv;
   p.Gp = pl.Gp;
   p.D = shape->d;

@@ -201,6 +201,51 @@ def test_beacon_step_leaves_other_sequences_alone(dev):
     check_slabs(rt, oc)
 
 
+def test_longest_first_dispatch_large_ragged_batch(dev):
+    # more (sequence, KV head) pairs than compute units: in bc_decode_attn workgroups pick their
+    # sequence by rank of the resident length (fused steps keep the plain order, their tables
+    # change during the launch).  Against the oracle with and without an inactive stripe, and
+    # bit-equality with the plain dispatch order (tuning variant 3).
+    bc = _bc()
+    B = 160
+    rng = np.random.default_rng(23)
+    P = rng.integers(1, 700, size=B).astype(np.int32)
+    P[:4] = [1, 699, 350, 350]
+    c = rng.choice([0, 2, 4, 16], size=B).astype(np.int32)
+    wl = W.Workload("lpt", 87, B, 12, 2, 128, "bf16", P, np.full(B, 40, np.int32), c)
+    rt, oc = make(wl, dev)
+    active = np.ones(B, np.uint8)
+    active[5::7] = 0
+    for t in range(1, 25):
+        k, v = wl.step_kv(t)
+        q = wl.step_q(t)
+        bk, bv = wl.beacon_kv(t)
+        act = active if t % 3 == 0 else None
+        o = rt.decode_step(k, v, q, bk, bv, active=act).cpu().numpy()
+        oc.append(k, v, active=act)
+        seqs = [s for s in range(B) if act is None or act[s]]
+        if t in (1, 2, 3, 16, 17, 24):
+            check_attention(o, q, oc, wl, seqs, t)
+        oc.compress_evict(bk, bv, active=act)
+        check_tables(rt, oc, t)
+    check_slabs(rt, oc, None, 24)
+    q = wl.step_q(99)
+    for act in (None, active):
+        rt.out.fill_(-3.0)
+        a = rt.decode_attn(q, active=act).cpu().numpy().copy()
+        bc.bc_set_decode_tuning(0, 3)
+        try:
+            rt.out.fill_(-3.0)
+            b = rt.decode_attn(q, active=act).cpu().numpy().copy()
+        finally:
+            bc.bc_set_decode_tuning(0, 0)
+        assert np.array_equal(a, b)
+        seqs = [s for s in range(B) if act is None or act[s]]
+        check_attention(a, q, oc, wl, seqs, 99)
+        if act is not None:
+            assert np.all(a[5::7] == -3.0)
+
+
 def test_fused_step_ragged_ratios_and_errors(dev):
     c = np.array([1, 2, 4, 8, 16, 32, 0, 3], np.int32)
     wl = W.Workload("fusedr", 80, 8, 12, 2, 128, "bf16",
