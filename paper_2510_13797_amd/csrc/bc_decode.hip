@@ -63,6 +63,7 @@ struct PairInfo {
   int64_t base;               // first entry of the sequence in the slabs
   int new_row;                // slot of the row appended by this launch, or -1
   bool evict_due;             // this launch ends with beacon append + eviction
+  bool store_new_row;         // the appended row outlives this launch: write it to the slab
   bool update;                // tables change at the end of this launch
   bool live;
 };
@@ -125,11 +126,16 @@ __device__ __forceinline__ LptPick lpt_sequence(const DecodeParams& p, int targe
   for (int t = threadIdx.x; t < p.B; t += blockDim.x)
     if (s_rank[t] == target_rank) s_pick = t;
   __syncthreads();
+  // values read from LDS count as per-lane to the compiler: hand them back as wave-uniform
+  // scalars so that the address arithmetic that follows stays on the scalar unit
+  auto uni = [](int x) { return __builtin_amdgcn_readfirstlane(x); };
   LptPick r;
-  r.s = s_pick;
-  r.act = s_tab[r.s]; r.P = s_tab[kLptMaxB + r.s]; r.nb = s_tab[2 * kLptMaxB + r.s];
-  r.w = s_tab[3 * kLptMaxB + r.s]; r.cap = s_tab[4 * kLptMaxB + r.s];
-  r.c = s_tab[5 * kLptMaxB + r.s]; r.base = s_base[r.s];
+  r.s = uni(s_pick);
+  r.act = uni(s_tab[r.s]); r.P = uni(s_tab[kLptMaxB + r.s]); r.nb = uni(s_tab[2 * kLptMaxB + r.s]);
+  r.w = uni(s_tab[3 * kLptMaxB + r.s]); r.cap = uni(s_tab[4 * kLptMaxB + r.s]);
+  r.c = uni(s_tab[5 * kLptMaxB + r.s]);
+  const int64_t b = s_base[r.s];
+  r.base = ((int64_t)uni((int)(b >> 32)) << 32) | (uint32_t)uni((int)(b & 0xffffffff));
   return r;
 }
 
@@ -156,7 +162,7 @@ __device__ __forceinline__ PairInfo pair_info(const DecodeParams& p, char* scrat
   }
   const bool herald = blockIdx.x == 0 && pi.kvh == 0 && threadIdx.x == 0;   // reports errors
   pi.live = false;
-  pi.update = false; pi.evict_due = false; pi.new_row = -1;
+  pi.update = false; pi.evict_due = false; pi.new_row = -1; pi.store_new_row = false;
   pi.L = 0; pi.nchunks = 0; pi.chunk = blockIdx.x; pi.row0 = 0; pi.row_end = 0; pi.w_att = w;
   // beacon step: only sequences whose window is full take part; one that has no room for the
   // beacon at the tail is reported and left alone
@@ -187,6 +193,9 @@ __device__ __forceinline__ PairInfo pair_info(const DecodeParams& p, char* scrat
       if (pi.w_att == pi.c + 1) { if (herald) atomicOr(p.err, BC_ERRBIT_STATE); }
       else if (pi.w_att == pi.c) pi.evict_due = true;
     }
+    // a row that this step's eviction drops at once (c = 1, or the beacon itself, which goes
+    // straight to its slot behind the earlier beacons) is never written at the tail
+    pi.store_new_row = append_ok && !(pi.evict_due && (pi.w_att == 1 || p.beacon_row));
     if (pi.L <= 0) {
       if (herald) atomicOr(p.err, BC_ERRBIT_STATE);
     } else {
@@ -354,7 +363,7 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
         char* tile = lane < 16 ? wk : wv;
         const int u = lane & 15;
         *reinterpret_cast<uint4*>(tile + ra * 256 + ((u ^ lds_swz(ra)) << 4)) = newrow;
-        if (!(pi.evict_due && (pi.w_att == 1 || p.beacon_row))) {
+        if (pi.store_new_row) {
           char* slab = const_cast<char*>(lane < 16 ? kbase : vbase);
           *reinterpret_cast<uint4*>(slab + (int64_t)pi.new_row * 256 + (u << 4)) = newrow;
         }
