@@ -266,12 +266,13 @@ __device__ __forceinline__ uint32_t bf16_rne_bits(float x) {     // finite x onl
   return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
+template <bool PROBES>   // PROBES: honour the early exits of the timing probes (tuning variants 11..15)
 __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams p) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
-  if (p.debug_stage == 1) return;
+  if (PROBES && p.debug_stage == 1) return;
   const PairInfo pi = pair_info(p, lds);
   if (!pi.live) return;
-  if (p.debug_stage == 2) { if (pi.L == 12345678) p.out[0] = 1.f; return; }
+  if (PROBES && p.debug_stage == 2) { if (pi.L == 12345678) p.out[0] = 1.f; return; }
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, kb = lane >> 4;       // MFMA column / k-block of this lane
@@ -353,7 +354,7 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
       }
       if (tile + kLdsWaves < ntiles) { BC_LOAD_TILE_REGS(trow0 + kLdsWaves * kTileRows) }
     }
-    if (p.debug_stage == 3) continue;
+    if (PROBES && p.debug_stage == 3) continue;
 
     if (pi.new_row >= trow0 && pi.new_row < trow0 + kTileRows) {
       // the appended row is not in the slab yet: place it in the tile, store it for later
@@ -443,7 +444,7 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
     }
   }
 
-  if (p.debug_stage == 3 || p.debug_stage == 4) { if (m_run == 123.f) p.out[0] = l_run + O[0][0]; return; }
+  if (PROBES && (p.debug_stage == 3 || p.debug_stage == 4)) { if (m_run == 123.f) p.out[0] = l_run + O[0][0]; return; }
 #undef BC_LOAD_TILE_REGS
   // denominators: sum the four k-blocks of each head
   l_run += __shfl_xor(l_run, 16, 64);
@@ -474,7 +475,7 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
   merge_waves_and_store<kLdsWaves, 128>(p, pi, s_m, s_l, s_acc, 8);
 
   // ---- the last workgroup of the sequence writes the beacon row and updates the tables
-  if (!pi.update || p.debug_stage == 5) return;
+  if (!pi.update || (PROBES && p.debug_stage == 5)) return;
   if (tid == 0) {
     asm volatile("s_waitcnt vmcnt(0)" : "+v"(ticket) : : "memory");   // the ticket has arrived
     *s_last = (ticket == p.Hkv * pi.nchunks - 1) ? 1 : 0;
@@ -737,7 +738,9 @@ static int32_t enable_big_lds() {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return BC_ERR_HIP;
   if (done[dev]) return BC_OK;
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(decode_lds_kernel),
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(decode_lds_kernel<false>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) != hipSuccess ||
+      hipFuncSetAttribute(reinterpret_cast<const void*>(decode_lds_kernel<true>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) != hipSuccess)
     return BC_ERR_HIP;
   done[dev] = true;
@@ -795,7 +798,8 @@ static int32_t launch_attention(const bc_shape* shape, const bc_cache* cache, co
   if (pl.lds) {
     const int32_t st = enable_big_lds();
     if (st != BC_OK) return st;
-    decode_lds_kernel<<<grid, kLdsWaves * 64, kLdsBytes, hs>>>(p);
+    if (p.debug_stage) decode_lds_kernel<true><<<grid, kLdsWaves * 64, kLdsBytes, hs>>>(p);
+    else decode_lds_kernel<false><<<grid, kLdsWaves * 64, kLdsBytes, hs>>>(p);
   } else if (shape->kv_dtype == BC_BF16) {
     if (shape->d == 128) launch_valu<bf16_t, 128>(p, pl.Gp, grid, hs);
     else launch_valu<bf16_t, 64>(p, pl.Gp, grid, hs);
