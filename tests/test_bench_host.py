@@ -1,0 +1,38 @@
+"""Host-side logic of bench.py (no GPU): the one-GPU rule and the algorithmic byte / flop counts
+the reported figures are built from, against the oracle's closed forms."""
+import os
+import subprocess
+import sys
+
+import numpy as np
+
+sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+import bench  # noqa: E402
+from oracle import attention as OA  # noqa: E402
+from oracle import residency as OR  # noqa: E402
+from paper_2510_13797_amd import workloads as W  # noqa: E402
+
+
+def test_more_than_one_gpu_is_refused_with_a_message():
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_kv_bytes_per_step_is_the_resident_length_at_attention():
+    wl = W.batch64(c=16)
+    for t in (1, 15, 16, 17, 4095, 4096):
+        L = OR.len_at_attention(256, 16, t)
+        assert bench.kv_bytes_per_step(wl, t) == 64 * L * 2 * 128 * 2 * 2
+    wl0 = W.batch64(c=0)
+    assert bench.kv_bytes_per_step(wl0, 100) == 64 * (256 + 100) * 2 * 128 * 2 * 2
+
+
+def test_visible_pairs_equals_the_sum_of_the_oracle_row_counts():
+    for S, P, c in ((200, 17, 4), (97, 0, 16), (64, 64, 3), (50, 10, 0)):
+        assert bench.visible_pairs(S, P, c) == sum(OA.count_visible(r, P, c) for r in range(S))
+    pw = W.prefill_train()
+    pairs = bench.visible_pairs(int(pw.S[0]), 256, 16)
+    assert abs(4.0 * 128 * pairs * 12 * 16 / 1e9 - 428.0) < 0.5      # GFLOP of the forward at config 5
