@@ -241,8 +241,11 @@ __device__ __forceinline__ void merge_waves_and_store(const DecodeParams& p, con
     if (pi.nchunks == 1) {
       __builtin_nontemporal_store(o / lsum, outp + i);   // streamed out: nothing left dirty in L2
     } else {
-      po[i] = o;
-      if (x == 0) { pml[h] = mx; pml[p.Gp + h] = lsum; }
+      __builtin_nontemporal_store(o, po + i);
+      if (x == 0) {
+        __builtin_nontemporal_store(mx, pml + h);
+        __builtin_nontemporal_store(lsum, pml + p.Gp + h);
+      }
     }
   }
 }
