@@ -52,7 +52,8 @@ struct DecodeParams {
   int32_t Hq, Hkv, g;  // g = real group size
   int32_t Gp;          // padded group size of the partial layout
   int32_t D;
-  int32_t rows_per_wg; // R
+  int32_t rows_per_wg; // R: rows per workgroup when a chunk size is forced; otherwise (0) the
+                       // resident rows of a sequence are spread evenly over its chunks
   int32_t max_chunks;
   float qscale;        // softmax scale * log2(e)
 };
@@ -71,6 +72,8 @@ struct PairInfo {
 // Common prologue: which rows does this workgroup own?  Uniform across the workgroup.  All
 // table loads are issued together.  With a fused append the state rules of bc_append_kv are
 // applied here, identically in every workgroup of the sequence.
+constexpr int kMinChunkRows = 128;   // a chunk smaller than this is not worth a workgroup
+constexpr int kMinSplitRows = 1024;  // sequences shorter than this are not split at all
 constexpr int kLptMaxB = 256;        // the pick costs about 2 B^2 lane operations per workgroup
 constexpr int kLptMinPairs = 256;   // compute units of the chip: below this every workgroup starts at once
 
@@ -199,14 +202,22 @@ __device__ __forceinline__ PairInfo pair_info(const DecodeParams& p, char* scrat
     if (pi.L <= 0) {
       if (herald) atomicOr(p.err, BC_ERRBIT_STATE);
     } else {
-      pi.nchunks = (pi.L + p.rows_per_wg - 1) / p.rows_per_wg;
+      // rows per chunk: the forced size, or the sequence's rows spread evenly over as many of
+      // the max_chunks workgroups as have at least kMinChunkRows rows to read
+      int rpc = p.rows_per_wg;
+      if (rpc <= 0) {
+        // (a short sequence stays whole: its partial would cost more than the split saves)
+        const int nc = pi.L < kMinSplitRows ? 1 : min(p.max_chunks, pi.L / kMinChunkRows);
+        rpc = (((pi.L + nc - 1) / nc) + 31) & ~31;
+      }
+      pi.nchunks = (pi.L + rpc - 1) / rpc;
       // the evaluation cap is tested on what this step's attention sees, whether or not the
       // append went through
       pi.update = append_ok || pi.evict_due ||
                   (p.budget && pi.nb + pi.w_att >= p.budget[pi.s]);
       if (pi.chunk < pi.nchunks) {
-        pi.row0 = pi.chunk * p.rows_per_wg;
-        pi.row_end = min(pi.L, pi.row0 + p.rows_per_wg);
+        pi.row0 = pi.chunk * rpc;
+        pi.row_end = min(pi.L, pi.row0 + rpc);
         pi.live = true;
       }
     }
@@ -657,15 +668,36 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeParams p) {
   const float* aml = p.part_ml + (int64_t)pair * p.max_chunks * (2 * p.Gp);
   float* outp = p.out + (int64_t)(s * p.Hq + kvh * p.g) * D;
   const int nout = p.g * D;
+  // chunks are folded in order, sixteen at a time: the loads of a batch are independent and in
+  // flight together (the partials come from memory, not from this compute unit's caches)
+  constexpr int kBatch = 16;
   for (int i = threadIdx.x; i < nout; i += blockDim.x) {
     const int h = i / D;
-    float mx = kNegBig;
-    for (int ch = 0; ch < nchunks; ++ch) mx = fmaxf(mx, aml[ch * 2 * p.Gp + h]);
-    float lsum = 0.f, o = 0.f;
-    for (int ch = 0; ch < nchunks; ++ch) {
-      const float a = fast_exp2(aml[ch * 2 * p.Gp + h] - mx);
-      lsum += aml[ch * 2 * p.Gp + p.Gp + h] * a;
-      o += ao[(int64_t)ch * (p.Gp * D) + i] * a;
+    float mx = kNegBig, lsum = 0.f, o = 0.f;
+    for (int ch0 = 0; ch0 < nchunks; ch0 += kBatch) {
+      float mv[kBatch], lv[kBatch], ov[kBatch];
+#pragma unroll
+      for (int k = 0; k < kBatch; ++k) {
+        const int ch = min(ch0 + k, nchunks - 1);
+        mv[k] = aml[ch * 2 * p.Gp + h];
+        lv[k] = aml[ch * 2 * p.Gp + p.Gp + h];
+        ov[k] = ao[(int64_t)ch * (p.Gp * D) + i];
+      }
+      float bm = kNegBig;
+#pragma unroll
+      for (int k = 0; k < kBatch; ++k) {
+        if (ch0 + k >= nchunks) mv[k] = kNegBig;
+        bm = fmaxf(bm, mv[k]);
+      }
+      const float mn = fmaxf(mx, bm);
+      const float keep = fast_exp2(mx - mn);
+      lsum *= keep; o *= keep; mx = mn;
+#pragma unroll
+      for (int k = 0; k < kBatch; ++k) {
+        const float a = (ch0 + k < nchunks) ? fast_exp2(mv[k] - mx) : 0.f;
+        lsum += lv[k] * a;
+        o += ov[k] * a;
+      }
     }
     outp[i] = o / lsum;
   }
@@ -687,6 +719,8 @@ struct DecodePlan {
 static int padded_group(int g) { return g <= 1 ? 1 : g <= 2 ? 2 : g <= 4 ? 4 : g <= 6 ? 6 : 8; }
 static size_t align256(size_t x) { return (x + 255) / 256 * 256; }
 
+constexpr int kPlanForSizing = -1;    // rows_override value: size the workspace for any plan
+
 static DecodePlan make_plan(const bc_shape* sh, int max_cap, int rows_override, int variant) {
   DecodePlan pl;
   pl.lds = sh->kv_dtype == BC_BF16 && sh->d == 128 && variant != 1;
@@ -699,23 +733,31 @@ static DecodePlan make_plan(const bc_shape* sh, int max_cap, int rows_override, 
     const int lpr = sh->d / epl, rpi = 64 / lpr;
     pl.rows_per_pass = kValuWaves * rpi * 8;
   }
-  int R;
+  const long npairs = (long)sh->B * sh->Hkv;
   if (rows_override > 0) {
-    R = rows_override;
+    // forced chunk size (experiments, tests): fixed rows per workgroup
+    int R = ((rows_override + pl.rows_per_pass - 1) / pl.rows_per_pass) * pl.rows_per_pass;
+    while ((max_cap + R - 1) / R > 64) R += pl.rows_per_pass;   // bound the partials per pair
+    pl.R = R;
+    pl.max_chunks = (max_cap + R - 1) / R;
   } else {
     // One workgroup per (sequence, KV head) pair when there are enough pairs: a long-running
-    // workgroup streams its rows at full rate and needs no merge launch.  With few pairs,
-    // split so that about 128 workgroups exist.
-    const long pairs = (long)sh->B * sh->Hkv;
-    long want = (128 + pairs - 1) / pairs;
-    if (want < 1) want = 1;
-    R = (int)((max_cap + want - 1) / want);
-    if (R < 4 * pl.rows_per_pass) R = 4 * pl.rows_per_pass;
+    // workgroup streams its rows at full rate and needs no merge launch.  With few pairs the
+    // rows of a sequence are spread over enough workgroups to fill the chip (256 compute units),
+    // at least kMinChunkRows rows each, at most 64 chunks - but only when the longest stream
+    // gets shorter by more than the merge launch costs (about 6 us, some 480 rows of one stream).
+    long chunks = 1;
+    if (npairs < 128) {
+      chunks = (256 + npairs - 1) / npairs;
+      const long by_rows = max_cap / kMinChunkRows;
+      if (chunks > by_rows) chunks = by_rows;
+      if (chunks > 64) chunks = 64;
+      if (chunks < 1 || max_cap - max_cap / chunks < 480) chunks = 1;
+    }
+    pl.R = 0;                                        // spread evenly, decided per sequence
+    pl.max_chunks = (int)chunks;
   }
-  R = ((R + pl.rows_per_pass - 1) / pl.rows_per_pass) * pl.rows_per_pass;
-  while ((max_cap + R - 1) / R > 64) R += pl.rows_per_pass;   // bound the partials per pair
-  pl.R = R;
-  pl.max_chunks = (max_cap + R - 1) / R;
+  if (rows_override == kPlanForSizing) pl.max_chunks = 64;   // the most any plan can use
   const size_t pairs = (size_t)sh->B * sh->Hkv;
   pl.tickets_bytes = align256((size_t)sh->B * 4);
   pl.part_n_bytes = align256(pairs * 4);
@@ -844,8 +886,9 @@ extern "C" void bc_set_decode_tuning(int32_t rows_per_workgroup, int32_t variant
 
 extern "C" size_t bc_decode_workspace_bytes(const bc_shape* shape, int32_t max_cap) {
   if (check_shape(shape) != BC_OK || max_cap < 1) return 0;
-  // sized for the smallest chunk any tuning can select, for either kernel
-  const DecodePlan a = make_plan(shape, max_cap, 1, 0), b = make_plan(shape, max_cap, 1, 1);
+  // sized for the largest number of chunks any plan or tuning can select, for either kernel
+  const DecodePlan a = make_plan(shape, max_cap, kPlanForSizing, 0),
+                   b = make_plan(shape, max_cap, kPlanForSizing, 1);
   return a.total() > b.total() ? a.total() : b.total();
 }
 

@@ -201,6 +201,25 @@ def test_beacon_step_leaves_other_sequences_alone(dev):
     check_slabs(rt, oc)
 
 
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64)])
+def test_small_batch_rows_spread_over_workgroups(dev, dtype, d):
+    # few (sequence, KV head) pairs and long sequences: the rows of a sequence are spread evenly
+    # over several workgroups whose partials a second launch merges; a short sequence in the same
+    # batch stays whole.  Fused steps (append + attention + eviction) against the oracle.
+    B = 3
+    Hq, Hkv = (12, 2) if d == 128 else (4, 1)
+    wl = W.Workload("spread", 88, B, Hq, Hkv, d, dtype, np.array([1100, 2500, 300], np.int32),
+                    np.full(B, 40, np.int32), np.array([0, 16, 4], np.int32))
+    rt, oc = make(wl, dev)
+    steps = range(1, 41)
+    rollout(wl, rt, oc, 40, steps, (1, 16, 17, 40), use_step_call=True)
+    q = wl.step_q(77)
+    a = rt.decode_attn(q).cpu().numpy().copy()
+    check_attention(a, q, oc, wl, None, 77)
+    b = rt.decode_attn(q).cpu().numpy().copy()
+    assert np.array_equal(a, b)                    # reproducible: fixed merge order, no atomics
+
+
 def test_longest_first_dispatch_large_ragged_batch(dev):
     # more (sequence, KV head) pairs than compute units: in bc_decode_attn workgroups pick their
     # sequence by rank of the resident length (fused steps keep the plain order, their tables
