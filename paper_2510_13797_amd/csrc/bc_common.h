@@ -69,6 +69,25 @@ __device__ __forceinline__ float group_allreduce_sum(float x) {
   return x;
 }
 
+// All-reduce over the four 16-lane rows of a wave (lane l with l ^ 16 and l ^ 32) by the two
+// row-swap instructions of gfx950 instead of two LDS-routed shuffles.  permlane16_swap(x, x)
+// returns {rows 0,0,2,2 ; rows 1,1,3,3} of x, permlane32_swap(y, y) {lower half twice ; upper
+// half twice}, so combining the two results of each gives every lane the value over all rows.
+__device__ __forceinline__ float rows_allreduce_max(float x) {
+  const uint32_t u = __float_as_uint(x);
+  const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const uint32_t v = __float_as_uint(fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1])));
+  const auto b = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ __forceinline__ float rows_allreduce_sum(float x) {
+  const uint32_t u = __float_as_uint(x);
+  const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const uint32_t v = __float_as_uint(__uint_as_float(a[0]) + __uint_as_float(a[1]));
+  const auto b = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+  return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
 inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }

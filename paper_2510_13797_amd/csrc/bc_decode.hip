@@ -411,8 +411,7 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
       sv[e] = valid ? S[e >> 2][e & 3] * p.qscale : kNegBig;
       tmax = fmaxf(tmax, sv[e]);
     }
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+    tmax = rows_allreduce_max(tmax);
     const float m_new = fmaxf(m_run, tmax);
     const float alpha = fast_exp2(m_run - m_new);
     m_run = m_new;
@@ -461,8 +460,7 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
   if (PROBES && (p.debug_stage == 3 || p.debug_stage == 4)) { if (m_run == 123.f) p.out[0] = l_run + O[0][0]; return; }
 #undef BC_LOAD_TILE_REGS
   // denominators: sum the four k-blocks of each head
-  l_run += __shfl_xor(l_run, 16, 64);
-  l_run += __shfl_xor(l_run, 32, 64);
+  l_run = rows_allreduce_sum(l_run);
 
   // ---- merge the waves through LDS (the tile regions are free once everyone is here)
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // this wave's slab store has landed

@@ -217,8 +217,7 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
       }
       float tmax = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])),
                          fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+      tmax = rows_allreduce_max(tmax);
       // Lazy reference: the running reference m only moves when the tile's maximum exceeds it by
       // more than kPfLazy (log2 units); until then weights are at most 2^kPfLazy, which fp32 sums
       // and the two-part bf16 weights carry without loss, and the accumulators need no rescale.
@@ -302,8 +301,7 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
   for (int h = 0; h < HPW; ++h) {
     const int head = hh * HPW + h;
     float l = l_run[h];
-    l += __shfl_xor(l, 16, 64);
-    l += __shfl_xor(l, 32, 64);
+    l = rows_allreduce_sum(l);
     const float inv = 1.0f / l;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {

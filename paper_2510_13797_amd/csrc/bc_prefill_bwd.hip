@@ -211,8 +211,7 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dq_kernel(BwdPar
       qb[h][i] = __builtin_bit_cast(bf16x8_t, x);
       dob[h][i] = __builtin_bit_cast(bf16x8_t, y);
     }
-    part += __shfl_xor(part, 16, 64);
-    part += __shfl_xor(part, 32, 64);
+    part = rows_allreduce_sum(part);
     delta[h] = part;
     lse2[h] = head_ok ? p.lse[rh] * kLog2e : 0.f;
     if (head_ok && row_ok && kb == 0) {
