@@ -1,11 +1,13 @@
 // bc_decode_attn: single-token grouped-query attention over the ragged compressed cache
 // (Sec. 2 and Sec. 3.1 of the paper: standard attention over whatever is resident).
 //
-// Split-K flash decoding.  Work item = (sequence, KV head) pair x chunk of R rows; grid =
-// (max chunks, pairs); workgroups whose chunk lies beyond L exit at once.  A pair that fits
-// one chunk is finished by its workgroup; otherwise every chunk writes an (m, l, o) partial
-// and a second, tiny kernel merges the partials of each pair in chunk order.  No atomics and
-// no fences: results are bit-reproducible.
+// Split-K flash decoding.  Work item = (sequence, KV head) pair x chunk of rows; grid =
+// (max chunks, pairs).  With 128 pairs or more a pair is one chunk and its workgroup finishes
+// it.  With fewer pairs the resident rows of a sequence are spread evenly over up to 64
+// workgroups (sequences under 1024 rows stay whole); every chunk writes an (m, l, o) partial
+// and a second, small kernel folds the partials of each pair in chunk order.  No float atomics
+// and no fences: results are bit-reproducible.  Large ragged batches (more pairs than compute
+// units) dispatch the longest sequences first in bc_decode_attn.
 //
 // Two main kernels:
 //  * decode_lds_kernel (bf16, d = 128): every wave streams 32-row K and V tiles from HBM
