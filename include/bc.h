@@ -1,6 +1,7 @@
 /*
  * bc.h - C ABI of the MI355X (gfx950) decode / compress / masked-prefill path of
- * Breadcrumbs Reasoning (arXiv 2510.13797).
+ * Breadcrumbs Reasoning (arXiv 2510.13797), with the gradients of the masked attention and
+ * the distillation loss of its training recipe.
  *
  * Problem statement (paper, Alg. 1 and Sec. 3.1): while a model generates, every c
  * generated tokens a beacon token is encoded; the beacon's K/V entry is kept and the
