@@ -164,6 +164,17 @@ def test_fused_step_bf16_every_step(dev, c, P):
     rollout(wl, rt, oc, 150, steps, steps, use_step_call=True)
 
 
+@pytest.mark.parametrize("Hq,Hkv,dtype,d", [(1, 1, "bf16", 128), (4, 2, "bf16", 128), (3, 1, "bf16", 128),
+                                             (10, 2, "bf16", 128), (7, 1, "bf16", 128), (16, 2, "bf16", 128),
+                                             (8, 1, "f32", 64), (6, 2, "bf16", 64), (5, 1, "f32", 128)])
+def test_group_sizes_one_to_eight(dev, Hq, Hkv, dtype, d):
+    # every group size g = Hq / Hkv from 1 to 8, on the MFMA kernel and on the plain-ALU kernel
+    wl = W.Workload("groups", 89, 5, Hq, Hkv, d, dtype, np.array([0, 3, 31, 64, 100], np.int32),
+                    np.full(5, 70, np.int32), np.array([16, 4, 0, 1, 7], np.int32))
+    rt, oc = make(wl, dev)
+    rollout(wl, rt, oc, 70, (1, 2, 7, 8, 16, 17, 33, 70), (16, 70), use_step_call=True)
+
+
 @pytest.mark.parametrize("name,dtype,d", [("bstep", "bf16", 128), ("bstep32", "f32", 64)])
 def test_beacon_step_rollout(dev, name, dtype, d):
     # the beacon's own step: single launch on the bf16 d=128 path, three launches otherwise
