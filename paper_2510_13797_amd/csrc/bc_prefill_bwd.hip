@@ -186,6 +186,7 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dq_kernel(BwdPar
   // this lane's query row; Q^T and dO^T as B operands; log-sum-exp and Delta of the row
   const int r = r0 + 16 * wave + n;
   const bool row_ok = r <= r1;
+  const bool full_rows = r0 + kBwBM - 1 <= r1;
   const int rq = row_ok ? r : r1;
   bf16x8_t qb[kDqHeads][4], dob[kDqHeads][4];
   float lse2[kDqHeads], delta[kDqHeads];
@@ -239,8 +240,13 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dq_kernel(BwdPar
     stage = stage + 1 == kBwStages ? 0 : stage + 1;
     const TileDesc td = tile_desc(kt);
 
+    // a full tile of the prompt or beacon run under a full query tile needs no per-key tests
+    // (uniform over the workgroup: skipped by a scalar branch)
+    const bool MASKED = td.predicate || td.nvalid < kBwBN || !full_rows;
     bool vis[8];
-    {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) vis[e] = true;
+    if (MASKED) {
       const int lim = row_ok ? td.nvalid - 8 * kb : 0;
 #pragma unroll
       for (int e = 0; e < 8; ++e) vis[e] = e < lim;
@@ -276,8 +282,12 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dq_kernel(BwdPar
       float ds[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        const float a = vis[e] ? fast_exp2(fmaf(Sx[e >> 2][e & 3], p.qscale, -lse2[h])) : 0.f;
+        const float a = fast_exp2(fmaf(Sx[e >> 2][e & 3], p.qscale, -lse2[h]));
         ds[e] = a * (dPx[e >> 2][e & 3] - delta[h]);
+      }
+      if (MASKED) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ds[e] = vis[e] ? ds[e] : 0.f;
       }
       bw_split(ds, dshi[h], dslo[h]);
     }
@@ -372,6 +382,12 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dkv_kernel(BwdPa
     const int wl = (int)__umulhi((uint32_t)(jl - Pk), magic);
     rs = j0; re = min(S - 1, Pk + (wl + 1) * cp1 - 1);      // through the closing beacon
   }
+  // first row tile of a dense block from which every streamed row sees every key of the block
+  // (never, for a block with missing keys or of response tokens)
+  int dense_from_rt = 0x7fffffff;
+  if (kind == 0 && blk * kBwBM + kBwBM <= Pk) dense_from_rt = kBwBM / kBwBN;
+  if (kind == 1 && (blk - NPB) * kBwBM + kBwBM <= nbeac)
+    dense_from_rt = ((kBwBM - 1) * cp1 + kBwBN) / kBwBN;
   if (!key_ok) jkey = rs;                      // loads stay in range; contributions are masked
   const int win_j = (c > 0 && jkey >= Pk) ? (int)__umulhi((uint32_t)(jkey - Pk), magic) : -1;
 
@@ -438,7 +454,12 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dkv_kernel(BwdPa
       const f32x4_t x = *reinterpret_cast<const f32x4_t*>(tstat + 16 * kb + 4 * e4);
       st[4 * e4] = x[0]; st[4 * e4 + 1] = x[1]; st[4 * e4 + 2] = x[2]; st[4 * e4 + 3] = x[3];
     }
+    // dense blocks: once the streamed rows lie behind every key of the block, nothing is hidden
+    const bool MASKED = rt < dense_from_rt || rs + rt * kBwBN + kBwBN - 1 > re;
     bool vis[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) vis[e] = true;
+    if (MASKED) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const int r = row0 + e;
@@ -449,6 +470,7 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dkv_kernel(BwdPa
         ok = wr == win_j;
       }
       vis[e] = ok;
+    }
     }
 
     f32x4_t Sx[2], dPx[2];
@@ -465,7 +487,8 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dkv_kernel(BwdPa
     float a[8], ds[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      a[e] = vis[e] ? fast_exp2(fmaf(Sx[e >> 2][e & 3], p.qscale, -st[2 * e])) : 0.f;
+      a[e] = fast_exp2(fmaf(Sx[e >> 2][e & 3], p.qscale, -st[2 * e]));
+      if (MASKED) a[e] = vis[e] ? a[e] : 0.f;
       ds[e] = a[e] * (dPx[e >> 2][e & 3] - st[2 * e + 1]);
     }
     bf16x8_t ahi, alo, dshi, dslo;
