@@ -12,8 +12,8 @@
 // touch the prompt use run C alone with the same predicate (which is then plain causal).
 //
 // One workgroup = 64 query rows x half of the query heads of one KV head, 4 waves of 16 rows
-// each; two workgroups share a CU, so one group's matrix phase overlaps the other's vector
-// (softmax) phase.  K/V tiles of 32 keys are gathered from HBM into LDS by
+// each; two workgroups share a CU (matrix and vector instructions of one SIMD overlap only
+// partly on this chip, so the tile body is bound by the sum of the two).  K/V tiles of 32 keys are gathered from HBM into LDS by
 // 16-byte LDS-DMA loads (3-stage ring, one barrier per tile, each row 256 contiguous bytes), shared by the 4
 // waves and fed to 16x16x32 bf16 MFMA: S^T = K.Q^T, O^T += V^T.P^T with P split into two
 // bf16 parts so that the softmax weights keep about 16 bits.  Softmax runs online in

@@ -5,7 +5,7 @@
 //   Delta_r = sum_x dO[r,x]*O[r,x]        dV = A^T.dO        dA = dO.V^T
 //   dS = A*(dA - Delta)                   dQ = scale*dS.K    dK = scale*dS^T.Q
 // A is recomputed from the saved log-sum-exp.  Two kernels, both on the compacted structure of
-// the mask, no atomics (every output element has exactly one owner, results are reproducible):
+// the mask, no atomics (results are reproducible), plus a small fixed-order reduction:
 //
 //  dq kernel   one workgroup = 64 query rows x 2 query heads, walking the same key list as the
 //              forward kernel (prompt run, gathered beacon run, masked band).  Also writes
@@ -15,6 +15,9 @@
 //                gathered beacons -> the same, from the first beacon's row on (dense)
 //                response tokens  -> only the rows up to the end of their window (masked band)
 //              so the dense part of the work is spent on the ~P + S/(c+1) keys every row sees.
+//              A dense block is long (every later row x every head); it is cut in two by query
+//              heads, the halves write partial dK/dV to the workspace and a third kernel adds
+//              them in a fixed order.  Response blocks store their result directly.
 //
 // All contractions are 16x16x32 bf16 MFMA; A and dS are split into two bf16 parts before they
 // enter a product (their rounding would otherwise dominate the error); tiles of 32 rows are
