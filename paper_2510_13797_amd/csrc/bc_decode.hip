@@ -719,7 +719,7 @@ struct DecodePlan {
 static int padded_group(int g) { return g <= 1 ? 1 : g <= 2 ? 2 : g <= 4 ? 4 : g <= 6 ? 6 : 8; }
 static size_t align256(size_t x) { return (x + 255) / 256 * 256; }
 
-constexpr int kPlanForSizing = -1;    // rows_override value: size the workspace for any plan
+constexpr int kPlanForSizing = -1;    // rows_override value: size the workspace (see below)
 
 static DecodePlan make_plan(const bc_shape* sh, int max_cap, int rows_override, int variant) {
   DecodePlan pl;
@@ -757,7 +757,9 @@ static DecodePlan make_plan(const bc_shape* sh, int max_cap, int rows_override, 
     pl.R = 0;                                        // spread evenly, decided per sequence
     pl.max_chunks = (int)chunks;
   }
-  if (rows_override == kPlanForSizing) pl.max_chunks = 64;   // the most any plan can use
+  // Workspace sizing: the most chunks the automatic plan can choose (64 with few pairs, one
+  // otherwise); a forced chunk size on a large batch may use up to four.
+  if (rows_override == kPlanForSizing) pl.max_chunks = npairs < 128 ? 64 : 4;
   const size_t pairs = (size_t)sh->B * sh->Hkv;
   pl.tickets_bytes = align256((size_t)sh->B * 4);
   pl.part_n_bytes = align256(pairs * 4);
@@ -886,7 +888,7 @@ extern "C" void bc_set_decode_tuning(int32_t rows_per_workgroup, int32_t variant
 
 extern "C" size_t bc_decode_workspace_bytes(const bc_shape* shape, int32_t max_cap) {
   if (check_shape(shape) != BC_OK || max_cap < 1) return 0;
-  // sized for the largest number of chunks any plan or tuning can select, for either kernel
+  // sized for the largest number of chunks the automatic plan can select, for either kernel
   const DecodePlan a = make_plan(shape, max_cap, kPlanForSizing, 0),
                    b = make_plan(shape, max_cap, kPlanForSizing, 1);
   return a.total() > b.total() ? a.total() : b.total();
