@@ -147,12 +147,16 @@ def bench_prefill(args):
     pairs = sum(visible_pairs(int(pw.S[b]), int(pw.P[b]), int(pw.c[b])) for b in range(pw.B))
     flops = 4.0 * pw.d * pairs * pw.Hq               # q.k and p.v, 2 flop per multiply-add
     tflops = flops / (ms * 1e-3) / 1e12
+    hbm_bytes = R * (pw.Hq * pw.d * 2 + 2 * pw.Hkv * pw.d * 2 + pw.Hq * pw.d * 4 + pw.Hq * 4)
     rec = {"metric": "prefill_attn_TFLOPs", "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1,
            "steps": K_, "warmup": W_, "ms_per_step": round(ms, 4), "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
            "config": {"workload": "beacon-masked prefill forward: B=16, Hq=12, Hkv=2, d=128, bf16, "
                                   "8192 tokens (P=256) + 496 beacons = 8688 rows, c=16",
-                      "algorithmic_GFLOP": round(flops / 1e9, 1)},
+                      "algorithmic_GFLOP": round(flops / 1e9, 1),
+                      # q, k, v read once (bf16), out (fp32) and lse written once
+                      "algorithmic_MB": round(hbm_bytes / 1e6, 1),
+                      "algorithmic_GBps": round(hbm_bytes / (ms * 1e-3) / 1e9, 1)},
            "roofline": {"bound": "mfma", "kernel": "bc::prefill_kernel<3>", "achieved": round(tflops, 2),
                         "peak": 2500.0, "unit": "TFLOP/s", "frac": round(tflops / 2500.0, 4),
                         "traffic": None}}
