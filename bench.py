@@ -87,6 +87,48 @@ def cpu_baseline(wl, budget_s=12.0):
                       "fp64 NumPy oracle, %.1f s" % (steps, L, wl.B, wl.Hq, wall)}
 
 
+def uncompressed_control(dev, NL=4, reps=10):
+    """The same shapes without compression (c = infinity) at the end of the rollout: every sequence
+    holds P + G = 4352 entries.  Decode attention alone (the tables do not change), NL cache
+    instances round-robin (2.3 GB > Infinity Cache), graph replay, HIP events."""
+    import torch
+    from paper_2510_13797_amd import bc, workloads
+    wl = workloads.batch64(c=0)
+    G = int(wl.G[0])
+    layers = []
+    for _ in range(NL):
+        rt = bc.Runtime(wl.B, wl.Hq, wl.Hkv, wl.d, wl.dtype, wl.scale, wl.P, wl.c, wl.capacity(), dev)
+        rt.k_slab.normal_()
+        rt.v_slab.normal_()
+        rt.set_tables(np.zeros(wl.B, np.int32), np.full(wl.B, G, np.int32))
+        layers.append(rt)
+    q = torch.randn(wl.B, wl.Hq, wl.d, device=dev).to(torch.bfloat16)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        for rt in layers:
+            rt.decode_attn(q)
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            for rt in layers:
+                rt.decode_attn(q)
+        graph.replay()
+        stream.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            graph.replay()
+        e1.record(stream)
+        stream.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / (reps * NL)
+    L = int(wl.P[0]) + G
+    nbytes = wl.B * L * wl.Hkv * wl.d * 2 * 2
+    assert torch.isfinite(layers[0].out).all()
+    return {"workload": "same shapes, c=inf, end of rollout: L=%d entries per sequence" % L,
+            "kv_bytes_per_step": nbytes, "us_per_step": round(us, 2),
+            "GBps": round(nbytes / us / 1e3, 1), "pct_of_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBPS * 100, 1)}
+
+
 def visible_pairs(S, P, c):
     """Number of (query row, visible key) pairs of one trajectory: sum over rows of |vis(r)|."""
     r = np.arange(S, dtype=np.int64)
@@ -322,6 +364,7 @@ def main():
                     help="also run the beacon token's own attention (bc_beacon_step) at every window end "
                          "instead of handing the beacon K/V to the token step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-control", action="store_true", help="skip the uncompressed (c=inf) control measurement")
     ap.add_argument("--rows-per-wg", type=int, default=0)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -526,6 +569,10 @@ def main():
                      "avg_launch_us_event_pairs_eager": round(samp_ms * 1e3 / max(n_samp, 1), 3),
                      "bytes_per_launch_mean": int(total_bytes / launches)},
     }
+    if c > 0 and not args.no_control:
+        del layers, pool
+        torch.cuda.empty_cache()
+        rec["uncompressed_control"] = uncompressed_control(dev)
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(rec))
