@@ -315,9 +315,9 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
         const int t = 2 * pass + (lane >> 5), unit = lane & 31;
         const f32x4_t val = *reinterpret_cast<const f32x4_t*>(my + t * 128 + ((unit ^ t) << 2));
         const int rr = r0 + 16 * tg + t;
-        if (rr <= r1)
-          *reinterpret_cast<f32x4_t*>(
-              p.out + ((off0 + rr) * p.Hq + kvh * p.g + head) * 128 + unit * 4) = val;
+        if (rr <= r1)     // written once, not read again by this launch: streaming store
+          __builtin_nontemporal_store(val, reinterpret_cast<f32x4_t*>(
+              p.out + ((off0 + rr) * p.Hq + kvh * p.g + head) * 128 + unit * 4));
       }
       if (p.lse && kb == 0 && row_ok)
         p.lse[(off0 + r) * p.Hq + kvh * p.g + head] = (m_run[h] + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;

@@ -115,7 +115,7 @@ __device__ __forceinline__ void bw_store_tile(float* my, const f32x4_t (&acc)[8]
     const int t = 2 * pass + (lane >> 5), unit = lane & 31;
     const f32x4_t val = *reinterpret_cast<const f32x4_t*>(my + t * 128 + ((unit ^ t) << 2));
     float* dst = dst_row(t);
-    if (dst) *reinterpret_cast<f32x4_t*>(dst + unit * 4) = val;
+    if (dst) __builtin_nontemporal_store(val, reinterpret_cast<f32x4_t*>(dst + unit * 4));   // written once
   }
 }
 
