@@ -268,7 +268,8 @@ int32_t bc_tables_to_host(const bc_shape *shape, const bc_cache *cache, int32_t 
 /* Tuning override for experiments: rows of one (sequence, KV head) stream handled by one
  * workgroup of bc_decode_attn (0 = automatic), and kernel variant: 0 = automatic, 1 = always the
  * plain-ALU kernel, 2 = the LDS/MFMA kernel or BC_ERR_SHAPE, 3 = automatic but without the
- * longest-sequence-first dispatch of large ragged batches; 11..15 = timing probes that leave
+ * longest-sequence-first dispatch of large ragged batches, 4 = automatic but with the default
+ * cache policy for the K/V loads of large launches; 11..15 = timing probes that leave
  * the LDS/MFMA kernel after a given stage (outputs are then meaningless). */
 void bc_set_decode_tuning(int32_t rows_per_workgroup, int32_t variant);
 

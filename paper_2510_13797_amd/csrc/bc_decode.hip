@@ -281,19 +281,29 @@ typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
 // (the `nt` bit of the load instructions), which measured 5 % faster per step than the default
 // policy at config 2.  kStreamPolicy is that bit in the LDS-DMA load's cache-policy operand.
 constexpr int kStreamPolicy = 2;
+constexpr int kStreamMinWorkgroups = 48;
 
+template <bool STREAM> __device__ __forceinline__ uint4 load16(const char* p);
+template <> __device__ __forceinline__ uint4 load16<false>(const char* p) {
+  return *reinterpret_cast<const uint4*>(p);
+}
 __device__ __forceinline__ uint4 load16_stream(const char* p) {
   typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
   const u32x4_t r = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
   return make_uint4(r.x, r.y, r.z, r.w);
 }
 
+template <> __device__ __forceinline__ uint4 load16<true>(const char* p) { return load16_stream(p); }
+
 __device__ __forceinline__ uint32_t bf16_rne_bits(float x) {     // finite x only
   const uint32_t u = __float_as_uint(x);
   return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
-template <bool PROBES>   // PROBES: honour the early exits of the timing probes (tuning variants 11..15)
+// PROBES: honour the early exits of the timing probes (tuning variants 11..15).
+// STREAM: load K/V with the non-temporal policy (large launches; small ones are latency-bound
+// and about a microsecond faster with the default policy).
+template <bool PROBES, bool STREAM>
 __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams p) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   if (PROBES && p.debug_stage == 1) return;
@@ -348,8 +358,8 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
   _Pragma("unroll") for (int j = 0; j < 8; ++j) {                             \
     const int grow_ = min((TROW0) + 4 * j + r4, last_slab_row);               \
     const int64_t goff_ = (int64_t)grow_ * 256 + (pos << 4);                  \
-    kreg[j] = load16_stream(kbase + goff_);                                   \
-    vreg[j] = load16_stream(vbase + goff_);                                   \
+    kreg[j] = load16<STREAM>(kbase + goff_);                                  \
+    vreg[j] = load16<STREAM>(vbase + goff_);                                  \
   }
   if (wave < ntiles) {
     // ---- HBM -> LDS: 8 + 8 instructions, each 4 whole rows (1 KB), 16-byte units XOR-swizzled
@@ -360,9 +370,9 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
       const int grow = min(trow0 + row, last_slab_row);     // stay inside the slab rows
       const int64_t goff = (int64_t)grow * 256 + ((pos ^ lds_swz(row)) << 4);
       __builtin_amdgcn_global_load_lds((global_void_t*)(kbase + goff),
-                                       (lds_void_t*)(wk + j * 1024), 16, 0, kStreamPolicy);
+                                       (lds_void_t*)(wk + j * 1024), 16, 0, STREAM ? kStreamPolicy : 0);
       __builtin_amdgcn_global_load_lds((global_void_t*)(vbase + goff),
-                                       (lds_void_t*)(wv + j * 1024), 16, 0, kStreamPolicy);
+                                       (lds_void_t*)(wv + j * 1024), 16, 0, STREAM ? kStreamPolicy : 0);
     }
     if (wave + kLdsWaves < ntiles) { BC_LOAD_TILE_REGS(trow0 + kLdsWaves * kTileRows) }
   }
@@ -690,9 +700,9 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeParams p) {
 #pragma unroll
       for (int k = 0; k < kBatch; ++k) {
         const int ch = min(ch0 + k, nchunks - 1);
-        mv[k] = aml[ch * 2 * p.Gp + h];
-        lv[k] = aml[ch * 2 * p.Gp + p.Gp + h];
-        ov[k] = ao[(int64_t)ch * (p.Gp * D) + i];
+        mv[k] = __builtin_nontemporal_load(aml + ch * 2 * p.Gp + h);
+        lv[k] = __builtin_nontemporal_load(aml + ch * 2 * p.Gp + p.Gp + h);
+        ov[k] = __builtin_nontemporal_load(ao + (int64_t)ch * (p.Gp * D) + i);
       }
       float bm = kNegBig;
 #pragma unroll
@@ -796,10 +806,15 @@ static int32_t enable_big_lds() {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return BC_ERR_HIP;
   if (done[dev]) return BC_OK;
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(decode_lds_kernel<false>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) != hipSuccess ||
-      hipFuncSetAttribute(reinterpret_cast<const void*>(decode_lds_kernel<true>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) != hipSuccess)
+  const void* kernels[4] = {reinterpret_cast<const void*>(decode_lds_kernel<false, false>),
+                            reinterpret_cast<const void*>(decode_lds_kernel<false, true>),
+                            reinterpret_cast<const void*>(decode_lds_kernel<true, false>),
+                            reinterpret_cast<const void*>(decode_lds_kernel<true, true>)};
+  bool ok = true;
+  for (const void* kfn : kernels)
+    ok = ok && hipFuncSetAttribute(kfn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) ==
+                   hipSuccess;
+  if (!ok)
     return BC_ERR_HIP;
   done[dev] = true;
   return BC_OK;
@@ -856,8 +871,11 @@ static int32_t launch_attention(const bc_shape* shape, const bc_cache* cache, co
   if (pl.lds) {
     const int32_t st = enable_big_lds();
     if (st != BC_OK) return st;
-    if (p.debug_stage) decode_lds_kernel<true><<<grid, kLdsWaves * 64, kLdsBytes, hs>>>(p);
-    else decode_lds_kernel<false><<<grid, kLdsWaves * 64, kLdsBytes, hs>>>(p);
+    // launches that cannot saturate the memory system are latency-bound: default cache policy
+    const bool stream = (long)pairs * pl.max_chunks >= kStreamMinWorkgroups && g_variant != 4;
+    auto kfn = p.debug_stage ? (stream ? decode_lds_kernel<true, true> : decode_lds_kernel<true, false>)
+                             : (stream ? decode_lds_kernel<false, true> : decode_lds_kernel<false, false>);
+    kfn<<<grid, kLdsWaves * 64, kLdsBytes, hs>>>(p);
   } else if (shape->kv_dtype == BC_BF16) {
     if (shape->d == 128) launch_valu<bf16_t, 128>(p, pl.Gp, grid, hs);
     else launch_valu<bf16_t, 64>(p, pl.Gp, grid, hs);
