@@ -56,6 +56,16 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {      // RNE, a
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(pf_f32x2_t{a, b}, bf16x2_t));
 }
 
+// x - (one half of the bf16 pair hp), exactly, in one instruction: the bf16 dot product with a
+// selector pair that holds -1 in that half and 0 in the other, accumulated onto x.  The selector
+// must sit in a register: as an immediate the assembler encodes it as a 32-bit constant, which
+// the instruction does not read as a pair.
+__device__ __forceinline__ float minus_half(float x, uint32_t hp, uint32_t selector) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, hp),
+                                         __builtin_bit_cast(bf16x2_t, selector), x, false);
+}
+constexpr uint32_t kSelLow = 0x0000bf80u, kSelHigh = 0xbf800000u;   // (-1, 0) and (0, -1) as bf16 pairs
+
 constexpr float kPfLazy = 5.0f;
 
 template <int HPW>     // query heads per wave (the group's heads are split over two wave sets)
@@ -88,6 +98,8 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, kb = lane >> 4;
   const int tg = wave;
+  uint32_t sel_low = kSelLow, sel_high = kSelHigh;
+  asm volatile("" : "+s"(sel_low), "+s"(sel_high));       // keep them in scalar registers
   const int64_t kv_row_bytes = (int64_t)p.Hkv * 256;
   const char* kbase = p.k + (off0 * p.Hkv + kvh) * 256;
   const char* vbase = p.v + (off0 * p.Hkv + kvh) * 256;
@@ -147,10 +159,11 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
   const int win_r = (c > 0 && r >= P) ? (int)__umulhi((uint32_t)(r - P), magic) : -1;
 
   f32x4_t O[HPW][8];
-  float m_run[HPW], l_run[HPW];
+  float m_run[HPW], l_run[HPW], grow_at[HPW];
+  const float inv_qscale = 1.0f / p.qscale;
 #pragma unroll
   for (int h = 0; h < HPW; ++h) {
-    m_run[h] = kNegBig; l_run[h] = 0.f;
+    m_run[h] = kNegBig; l_run[h] = 0.f; grow_at[h] = (kNegBig + kPfLazy) * inv_qscale;
 #pragma unroll
     for (int j = 0; j < 8; ++j) O[h][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
   }
@@ -194,8 +207,6 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
         ka[t][i] = *reinterpret_cast<const bf16x8_t*>(tk + row * 256 + (((4 * i + kb) ^ lds_swz(row)) << 4));
     }
     bf16x8_t phi[HPW], plo[HPW];
-    float alpha[HPW];
-    bool any_rescale = false;
 #pragma unroll
     for (int h = 0; h < HPW; ++h) {
       f32x4_t Sx[2];
@@ -215,18 +226,24 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
 #pragma unroll
         for (int e = 0; e < 8; ++e) sv[e] = vis[e] ? sv[e] : kNegBig;
       }
-      float tmax = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])),
-                         fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
+      float tmax = fmaxf(fmaxf(fmaxf(fmaxf(sv[0], sv[1]), sv[2]), fmaxf(fmaxf(sv[3], sv[4]), sv[5])),
+                         fmaxf(sv[6], sv[7]));
       tmax = rows_allreduce_max(tmax);
       // Lazy reference: the running reference m only moves when the tile's maximum exceeds it by
       // more than kPfLazy (log2 units); until then weights are at most 2^kPfLazy, which fp32 sums
       // and the two-part bf16 weights carry without loss, and the accumulators need no rescale.
-      const float m_cand = tmax * p.qscale;                     // kNegBig * qs stays hugely negative
-      const bool grow = m_cand > m_run[h] + kPfLazy;
-      const float m_new = grow ? m_cand : m_run[h];
-      alpha[h] = fast_exp2(m_run[h] - m_new);
-      any_rescale = any_rescale || grow;
-      m_run[h] = m_new;
+      // The test runs on the unscaled maximum against grow_at = (m + kPfLazy) / qs.
+      if (__any(tmax > grow_at[h])) {
+        const float m_cand = tmax * p.qscale;                   // kNegBig * qs stays hugely negative
+        const float m_new = m_cand > m_run[h] + kPfLazy ? m_cand : m_run[h];
+        const float alpha = fast_exp2(m_run[h] - m_new);
+        m_run[h] = m_new;
+        grow_at[h] = (m_new + kPfLazy) * inv_qscale;
+        l_run[h] *= alpha;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) O[h][j] *= alpha;
+      }
+      const float m_new = m_run[h];
       float pe[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
@@ -242,20 +259,12 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
       for (int e = 0; e < 8; e += 2) {
         const uint32_t hp = pack_bf16(pe[e], pe[e + 1]);
         hi[e >> 1] = hp;
-        lo[e >> 1] = pack_bf16(pe[e] - __uint_as_float(hp << 16),
-                               pe[e + 1] - __uint_as_float(hp & 0xffff0000u));
+        lo[e >> 1] = pack_bf16(minus_half(pe[e], hp, sel_low), minus_half(pe[e + 1], hp, sel_high));
       }
-      l_run[h] = fmaf(l_run[h], alpha[h], psum);
+      l_run[h] += psum;
       phi[h] = __builtin_bit_cast(bf16x8_t, make_uint4(hi[0], hi[1], hi[2], hi[3]));
       plo[h] = __builtin_bit_cast(bf16x8_t, make_uint4(lo[0], lo[1], lo[2], lo[3]));
     }
-    if (__any(any_rescale)) {
-#pragma unroll
-      for (int h = 0; h < HPW; ++h)
-#pragma unroll
-        for (int j = 0; j < 8; ++j) O[h][j] *= alpha[h];
-    }
-
     // O^T += V^T . P^T ; V^T through the transposing LDS read
     {
       const int rl = lane & 15;
