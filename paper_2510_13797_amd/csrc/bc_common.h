@@ -33,6 +33,22 @@ __device__ __forceinline__ int lds_swz(int row) {
   return ((row & 3) << 1) | (((row >> 3) & 1) << 3) | ((row >> 4) & 1);
 }
 
+// x minus one half of the bf16 pair hp, exactly, in one instruction: the bf16 dot product with a
+// selector pair that holds -1 in that half and 0 in the other, accumulated onto x.  Used to split
+// an fp32 value into two bf16 parts (hp holds the rounded high parts of two values).  The
+// selectors must sit in registers: as an immediate the assembler encodes the pair as a 32-bit
+// constant, which the instruction does not read as a pair.
+struct HalfSelectors { uint32_t low, high; };
+__device__ __forceinline__ HalfSelectors half_selectors() {
+  uint32_t low = 0x0000bf80u, high = 0xbf800000u;          // (-1, 0) and (0, -1) as bf16 pairs
+  asm volatile("" : "+s"(low), "+s"(high));                // opaque: stay in scalar registers
+  return HalfSelectors{low, high};
+}
+__device__ __forceinline__ float minus_half(float x, uint32_t hp, uint32_t selector) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, hp),
+                                         __builtin_bit_cast(bf16x2_t, selector), x, false);
+}
+
 // 16 bytes of a row -> floats
 __device__ __forceinline__ void unpack16(const uint4& r, float (&f)[4], float) {
   f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y);

@@ -56,16 +56,6 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {      // RNE, a
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(pf_f32x2_t{a, b}, bf16x2_t));
 }
 
-// x - (one half of the bf16 pair hp), exactly, in one instruction: the bf16 dot product with a
-// selector pair that holds -1 in that half and 0 in the other, accumulated onto x.  The selector
-// must sit in a register: as an immediate the assembler encodes it as a 32-bit constant, which
-// the instruction does not read as a pair.
-__device__ __forceinline__ float minus_half(float x, uint32_t hp, uint32_t selector) {
-  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, hp),
-                                         __builtin_bit_cast(bf16x2_t, selector), x, false);
-}
-constexpr uint32_t kSelLow = 0x0000bf80u, kSelHigh = 0xbf800000u;   // (-1, 0) and (0, -1) as bf16 pairs
-
 constexpr float kPfLazy = 5.0f;
 
 template <int HPW>     // query heads per wave (the group's heads are split over two wave sets)
@@ -98,8 +88,7 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, kb = lane >> 4;
   const int tg = wave;
-  uint32_t sel_low = kSelLow, sel_high = kSelHigh;
-  asm volatile("" : "+s"(sel_low), "+s"(sel_high));       // keep them in scalar registers
+  const HalfSelectors sel = half_selectors();
   const int64_t kv_row_bytes = (int64_t)p.Hkv * 256;
   const char* kbase = p.k + (off0 * p.Hkv + kvh) * 256;
   const char* vbase = p.v + (off0 * p.Hkv + kvh) * 256;
@@ -259,7 +248,7 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
       for (int e = 0; e < 8; e += 2) {
         const uint32_t hp = pack_bf16(pe[e], pe[e + 1]);
         hi[e >> 1] = hp;
-        lo[e >> 1] = pack_bf16(minus_half(pe[e], hp, sel_low), minus_half(pe[e + 1], hp, sel_high));
+        lo[e >> 1] = pack_bf16(minus_half(pe[e], hp, sel.low), minus_half(pe[e + 1], hp, sel.high));
       }
       l_run[h] += psum;
       phi[h] = __builtin_bit_cast(bf16x8_t, make_uint4(hi[0], hi[1], hi[2], hi[3]));

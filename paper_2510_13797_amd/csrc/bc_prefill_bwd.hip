@@ -68,13 +68,14 @@ __device__ __forceinline__ uint32_t bw_pack(float a, float b) {       // two flo
 }
 
 // 8 floats (consecutive k indices) -> hi and lo bf16x8 operands with hi + lo ~ x to 16 bits
-__device__ __forceinline__ void bw_split(const float (&x)[8], bf16x8_t& hi, bf16x8_t& lo) {
+__device__ __forceinline__ void bw_split(const float (&x)[8], bf16x8_t& hi, bf16x8_t& lo,
+                                         const HalfSelectors& sel) {
   uint32_t h[4], l[4];
 #pragma unroll
   for (int e = 0; e < 8; e += 2) {
     const uint32_t hp = bw_pack(x[e], x[e + 1]);
     h[e >> 1] = hp;
-    l[e >> 1] = bw_pack(x[e] - __uint_as_float(hp << 16), x[e + 1] - __uint_as_float(hp & 0xffff0000u));
+    l[e >> 1] = bw_pack(minus_half(x[e], hp, sel.low), minus_half(x[e + 1], hp, sel.high));
   }
   hi = __builtin_bit_cast(bf16x8_t, make_uint4(h[0], h[1], h[2], h[3]));
   lo = __builtin_bit_cast(bf16x8_t, make_uint4(l[0], l[1], l[2], l[3]));
@@ -150,6 +151,7 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dq_kernel(BwdPar
   const int NT = TA + TB + (nC + kBwBN - 1) / kBwBN;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const HalfSelectors sel = half_selectors();
   const int n = lane & 15, kb = lane >> 4;
   const int64_t kv_row_bytes = (int64_t)p.Hkv * 256;
   const char* kbase = p.k + (off0 * p.Hkv + kvh) * 256;
@@ -292,7 +294,7 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dq_kernel(BwdPar
 #pragma unroll
         for (int e = 0; e < 8; ++e) ds[e] = vis[e] ? ds[e] : 0.f;
       }
-      bw_split(ds, dshi[h], dslo[h]);
+      bw_split(ds, dshi[h], dslo[h], sel);
     }
     // dQ^T += K^T . dS^T
 #pragma unroll
@@ -358,6 +360,7 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dkv_kernel(BwdPa
   const int kind = blk < NPB ? 0 : blk < NPB + NBB ? 1 : 2;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const HalfSelectors sel = half_selectors();
   const int n = lane & 15, kb = lane >> 4;
 
   // this lane's key (column n of the wave's 16 keys) and the row range the block streams
@@ -495,8 +498,8 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dkv_kernel(BwdPa
       ds[e] = a[e] * (dPx[e >> 2][e & 3] - st[2 * e + 1]);
     }
     bf16x8_t ahi, alo, dshi, dslo;
-    bw_split(a, ahi, alo);
-    bw_split(ds, dshi, dslo);
+    bw_split(a, ahi, alo, sel);
+    bw_split(ds, dshi, dslo, sel);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const bf16x8_t dot = bw_cols_operand(tdo, j, lane);      // dO^T
