@@ -410,9 +410,12 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dkv_kernel(BwdPa
   const int NT = ntile * (h_end - h_begin);     // streamed tiles: head-major
   const int64_t q_row_bytes = (int64_t)p.Hq * 256;
   const int ld_rr = 4 * wave + (lane >> 4);
-  auto issue_tile = [&](int it, int stage) {
-    const int hl = it / ntile, rt = it - hl * ntile;
-    const int h = h_begin + hl;
+  // tiles are issued in order, so the (head, row tile) pair of the next tile to issue is kept
+  // in two counters instead of being recovered by a division
+  int issue_h = h_begin, issue_rt = 0;
+  auto issue_tile = [&](int stage) {
+    const int h = issue_h, rt = issue_rt;
+    if (++issue_rt == ntile) { issue_rt = 0; ++issue_h; }
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
       const int tr = ld_rr + 16 * half;                       // entry of the tile
@@ -432,25 +435,26 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dkv_kernel(BwdPa
     }
   };
   (void)q_row_bytes;
-  issue_tile(0, 0);
-  if (NT > 1) issue_tile(1, 1);
+  issue_tile(0);
+  if (NT > 1) issue_tile(1);
 
   f32x4_t dK[8], dV[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) { dK[j] = f32x4_t{0.f, 0.f, 0.f, 0.f}; dV[j] = f32x4_t{0.f, 0.f, 0.f, 0.f}; }
 
-  int stage = 0;
+  int stage = 0, cur_rt = 0;
   for (int it = 0; it < NT; ++it) {
     if (it + 1 >= NT) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     else if (wave == 0) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");     // one more load per tile
     else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
     __syncthreads();
-    if (it + 2 < NT) issue_tile(it + 2, stage >= 1 ? stage - 1 : kBwStages - 1);
+    if (it + 2 < NT) issue_tile(stage >= 1 ? stage - 1 : kBwStages - 1);
     const char* tq = lds + stage * (2 * kBwTile);
     const char* tdo = tq + kBwTile;
     const float* tstat = reinterpret_cast<const float*>(lds + kBwLds + stage * 256);
     stage = stage + 1 == kBwStages ? 0 : stage + 1;
-    const int rt = it % ntile;
+    const int rt = cur_rt;
+    if (++cur_rt == ntile) cur_rt = 0;
     const int row0 = rs + rt * kBwBN + 8 * kb;          // this lane's 8 rows: row0 + e
 
     // per-row statistics of this lane's rows (head-major, 8 rows = 64 contiguous bytes)
