@@ -49,6 +49,7 @@ struct PrefillParams {
   float* out;
   float* lse;
   int32_t Hq, Hkv, g;
+  int32_t hsplit;     // the group's heads are split over this many workgroups (HPW heads each)
   float qscale;       // softmax scale * log2(e)
 };
 
@@ -58,13 +59,13 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {      // RNE, a
 
 constexpr float kPfLazy = 5.0f;
 
-template <int HPW>     // query heads per wave (the group's heads are split over two wave sets)
+template <int HPW>     // query heads per wave (the group's heads are split over p.hsplit workgroups)
 __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams p) {
   __shared__ __attribute__((aligned(1024))) char lds[kPfLds];
-  // grid: x = (trajectory, KV head, head half), y = query tile; workgroups are dispatched
+  // grid: x = (trajectory, KV head, head split), y = query tile; workgroups are dispatched
   // x-fastest, so the longest tiles of every trajectory start first
-  const int hh = blockIdx.x & 1, kvh = (blockIdx.x >> 1) % p.Hkv, b = (blockIdx.x >> 1) / p.Hkv;
-  if (hh * HPW >= p.g) return;                      // this half holds no head of the group
+  const int pair = blockIdx.x / p.hsplit, hh = blockIdx.x - pair * p.hsplit;
+  const int kvh = pair % p.Hkv, b = pair / p.Hkv;
   const int64_t off0 = p.row_off[b];
   const int S = (int)(p.row_off[b + 1] - off0);
   const int qt = gridDim.y - 1 - blockIdx.y;        // long tiles first
@@ -346,14 +347,16 @@ extern "C" int32_t bc_prefill_attn(const bc_shape* shape, const void* q, const v
   p.out = out; p.lse = lse;
   p.Hq = shape->Hq; p.Hkv = shape->Hkv; p.g = shape->Hq / shape->Hkv;
   p.qscale = shape->scale * kLog2e;
-  const dim3 grid(2 * shape->Hkv * shape->B, (max_rows + kPfBM - 1) / kPfBM);
+  // at most three heads per workgroup (the accumulators of a fourth do not fit the register
+  // file): one workgroup for a single head, two for groups up to six, three for seven and eight
+  p.hsplit = p.g == 1 ? 1 : (p.g <= 6 ? 2 : 3);
+  const int hpw = (p.g + p.hsplit - 1) / p.hsplit;
+  const dim3 grid(p.hsplit * shape->Hkv * shape->B, (max_rows + kPfBM - 1) / kPfBM);
   hipStream_t hs = as_stream(stream);
-  const int hpw = (p.g + 1) / 2;
   switch (hpw) {
     case 1: prefill_kernel<1><<<grid, kPfWaves * 64, 0, hs>>>(p); break;
     case 2: prefill_kernel<2><<<grid, kPfWaves * 64, 0, hs>>>(p); break;
-    case 3: prefill_kernel<3><<<grid, kPfWaves * 64, 0, hs>>>(p); break;
-    default: prefill_kernel<4><<<grid, kPfWaves * 64, 0, hs>>>(p); break;
+    default: prefill_kernel<3><<<grid, kPfWaves * 64, 0, hs>>>(p); break;
   }
   return launch_status();
 }

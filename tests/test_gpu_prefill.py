@@ -43,7 +43,7 @@ def _check_rows(pw, qkv, off, out, lse, b, rows):
     return err
 
 
-@pytest.mark.parametrize("Hq,Hkv", [(12, 2), (4, 1), (8, 8), (2, 2)])
+@pytest.mark.parametrize("Hq,Hkv", [(12, 2), (4, 1), (8, 8), (2, 2), (7, 1), (8, 1), (5, 1), (3, 1), (4, 2)])
 def test_prefill_small_ragged_all_rows(dev, Hq, Hkv):
     pw = W.PrefillWorkload("pf_small", 50 + Hq, 6, Hq, Hkv, 128, "bf16",
                            np.array([0, 5, 64, 70, 33, 200], np.int32),      # prompt rows
@@ -161,7 +161,7 @@ def _check_bwd(pw, qkv, dos, off, dq, dk, dv, b):
     return errs
 
 
-@pytest.mark.parametrize("Hq,Hkv", [(12, 2), (4, 1), (8, 8), (6, 2)])
+@pytest.mark.parametrize("Hq,Hkv", [(12, 2), (4, 1), (8, 8), (6, 2), (7, 1), (8, 1), (5, 1)])
 def test_prefill_bwd_small_ragged(dev, Hq, Hkv):
     pw = W.PrefillWorkload("pf_bwd", 55 + Hq, 6, Hq, Hkv, 128, "bf16",
                            np.array([0, 5, 64, 70, 33, 200], np.int32),
