@@ -11,7 +11,7 @@
 // instead of the r rows of causal attention, and never materialises a mask.  Tiles that
 // touch the prompt use run C alone with the same predicate (which is then plain causal).
 //
-// One workgroup = 64 query rows x half of the query heads of one KV head, 4 waves of 16 rows
+// One workgroup = 64 query rows x up to three query heads of one KV head, 4 waves of 16 rows
 // each; two workgroups share a CU (matrix and vector instructions of one SIMD overlap only
 // partly on this chip, so the tile body is bound by the sum of the two).  K/V tiles of 32 keys are gathered from HBM into LDS by
 // 16-byte LDS-DMA loads (3-stage ring, one barrier per tile, each row 256 contiguous bytes), shared by the 4
