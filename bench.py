@@ -49,6 +49,20 @@ def stored_traffic():
         return None
 
 
+def stored_value(key):
+    """One `key = value` figure from profiles/prefill_config5_hbm_traffic.txt (measured HBM-side bytes of
+    the prefill and distillation kernels, same method as stored_traffic); None if absent."""
+    try:
+        with open(os.path.join(ROOT, "profiles", "prefill_config5_hbm_traffic.txt")) as f:
+            for line in f:
+                line = line.split("#")[0]
+                if "=" in line and line.split("=")[0].strip() == key:
+                    return int(float(line.split("=")[1]))
+    except (OSError, ValueError):
+        pass
+    return None
+
+
 def kv_bytes_per_step(wl, t):
     """Algorithmic K+V bytes decode attention reads at token-step t: every resident row once."""
     es = 2 if wl.dtype == "bf16" else 4
@@ -201,7 +215,7 @@ def bench_prefill(args):
                       "algorithmic_GBps": round(hbm_bytes / (ms * 1e-3) / 1e9, 1)},
            "roofline": {"bound": "mfma", "kernel": "bc::prefill_kernel<3>", "achieved": round(tflops, 2),
                         "peak": 2500.0, "unit": "TFLOP/s", "frac": round(tflops / 2500.0, 4),
-                        "traffic": None}}
+                        "traffic": stored_value("prefill_fwd_traffic_bytes")}}
     print(json.dumps(rec))
 
 
@@ -265,7 +279,8 @@ def bench_prefill_bwd(args):
                                  "algorithmic_GFLOP": round(flops / 1e9, 1)},
                       "roofline": {"bound": "mfma", "kernel": "bc::prefill_bwd_dq_kernel + bc::prefill_bwd_dkv_kernel",
                                    "achieved": round(tflops, 2), "peak": 2500.0, "unit": "TFLOP/s",
-                                   "frac": round(tflops / 2500.0, 4), "traffic": None}}))
+                                   "frac": round(tflops / 2500.0, 4),
+                                   "traffic": stored_value("prefill_bwd_traffic_bytes")}}))
 
 
 def bench_distill(args):
@@ -332,7 +347,8 @@ def bench_distill(args):
                                  "forward_GBps": round(gbs_f, 1), "backward_GBps": round(gbs_b, 1)},
                       "roofline": {"bound": "hbm", "kernel": "bc::topk_kl_bwd_kernel<bf16_t, true>",
                                    "achieved": round(gbs_b, 1), "peak": 8000.0, "unit": "GB/s",
-                                   "frac": round(gbs_b / 8000.0, 4), "traffic": None}}))
+                                   "frac": round(gbs_b / 8000.0, 4),
+                                   "traffic": stored_value("distill_bwd_traffic_bytes")}}))
 
 
 def bench_copy(args):

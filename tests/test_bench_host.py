@@ -36,3 +36,15 @@ def test_visible_pairs_equals_the_sum_of_the_oracle_row_counts():
     pw = W.prefill_train()
     pairs = bench.visible_pairs(int(pw.S[0]), 256, 16)
     assert abs(4.0 * 128 * pairs * 12 * 16 / 1e9 - 428.0) < 0.5      # GFLOP of the forward at config 5
+
+
+def test_stored_traffic_figures_are_read_from_the_profiles():
+    # measured HBM-side bytes must be at least the algorithmic bytes of the same launch
+    t = bench.stored_traffic()
+    assert t is not None and t["bytes_per_launch"] >= t["algorithmic_bytes_per_launch"]
+    pw = W.prefill_train()
+    rows = int(np.sum(pw.S))
+    fwd_alg = rows * pw.Hq * 128 * 2 + 2 * rows * pw.Hkv * 128 * 2 + rows * pw.Hq * 128 * 4
+    assert bench.stored_value("prefill_fwd_traffic_bytes") >= fwd_alg
+    assert bench.stored_value("distill_bwd_traffic_bytes") >= 2 * 4096 * 151936 * 2
+    assert bench.stored_value("no_such_key") is None
