@@ -130,7 +130,8 @@ int32_t bc_append_kv(const bc_shape *shape, const bc_cache *cache, const void *k
 /* Bytes of workspace bc_decode_attn() and the step calls need for this shape and max_cap
  * (enough for the automatic plan; a chunk size forced by bc_set_decode_tuning() on a batch with
  * 128 or more (sequence, KV head) pairs may split a sequence into at most four chunks, beyond
- * that the calls return BC_ERR_WORKSPACE). */
+ * that the calls return BC_ERR_WORKSPACE).  Besides partial results the workspace holds one
+ * counter and one 48-byte dispatch record per sequence. */
 size_t bc_decode_workspace_bytes(const bc_shape *shape, int32_t max_cap);
 
 /* Zero a freshly allocated workspace (it holds per-sequence counters that the library

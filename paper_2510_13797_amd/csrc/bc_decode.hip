@@ -7,7 +7,8 @@
 // workgroups (sequences under 1024 rows stay whole); every chunk writes an (m, l, o) partial
 // and a second, small kernel folds the partials of each pair in chunk order.  No float atomics
 // and no fences: results are bit-reproducible.  Large ragged batches (more pairs than compute
-// units) dispatch the longest sequences first in bc_decode_attn.
+// units) dispatch the longest sequences first: a small kernel in front of the main one sorts
+// the sequences by resident length.
 //
 // Two main kernels:
 //  * decode_lds_kernel (bf16, d = 128): every wave streams 32-row K and V tiles from HBM
@@ -45,10 +46,11 @@ struct DecodeParams {
   const char* bk;
   const char* bv;
   int32_t* tickets;    // [B], zero between launches
+  struct OrderRec* order;   // [B] dispatch order of this launch (written by decode_order_kernel)
   const int32_t* budget;   // [B] cap on nb + w (nullable), with
   uint8_t* live;           // [B] cleared when the cap is reached
   int32_t beacon_row;  // the fused row is the beacon closing a full window (bk = new_k, bv = new_v)
-  int32_t lpt;         // workgroups take the sequences in order of decreasing length (B <= kLptMaxB)
+  int32_t lpt;         // workgroups take the sequences in order of decreasing length (`order`)
   int32_t B;
   int32_t debug_stage; // experiments only: leave the kernel early (0 = run everything)
   int32_t Hq, Hkv, g;  // g = real group size
@@ -76,83 +78,56 @@ struct PairInfo {
 // applied here, identically in every workgroup of the sequence.
 constexpr int kMinChunkRows = 128;   // a chunk smaller than this is not worth a workgroup
 constexpr int kMinSplitRows = 1024;  // sequences shorter than this are not split at all
-constexpr int kLptMaxB = 256;        // the pick costs about 2 B^2 lane operations per workgroup
-constexpr int kLptMinPairs = 256;   // compute units of the chip: below this every workgroup starts at once
+constexpr int kLptMaxB = 4096;       // sort key: length * 4096 + index
+constexpr int kLptMaxLen = 1 << 19;
+constexpr int kLptMinPairs = 256;    // compute units of the chip: below this every workgroup starts at once
 
 // Longest sequence first: with more workgroups than the chip holds at once and ragged lengths,
-// the dispatch order decides the tail.  Workgroup number i (in dispatch order) takes the
-// sequence with the i-th largest resident length.  Every workgroup reads all tables once (no
-// second, dependent read for the chosen sequence), ranks the B lengths itself (keys made unique
-// by the index, so the ranks are a permutation) and picks its sequence: about 2 microseconds at
-// B = 256, growing with B^2, hence the limit on B.
-// scratch: kLptScratchBytes of LDS, free again after the caller's next barrier.
-constexpr int kLptScratchBytes = 10 * kLptMaxB * 4;
-struct LptPick { int s, act, P, nb, w, cap, c; int64_t base; };
+// the dispatch order decides the tail.  decode_order_kernel, launched in front of the main
+// kernel, ranks the B sequences by resident length (keys made unique by the index, so the ranks
+// are a permutation) and writes for every rank one record with the sequence and a snapshot of
+// its table entries.  Workgroup number i of the main kernel (in dispatch order) serves the
+// sequence of record i and takes the table values from the record: one read instead of the
+// seven table reads, and the values are the ones at the start of the launch even while a fused
+// step is already updating the tables of sequences that have finished.
+struct alignas(16) OrderRec {
+  int32_t s, act, P, nb;
+  int32_t w, cap, c, pad;
+  int64_t base, pad2;
+};
 
-__device__ __forceinline__ LptPick lpt_sequence(const DecodeParams& p, int target_rank, char* scratch) {
-  int* s_key = reinterpret_cast<int*>(scratch);          // [Bp] sort keys
-  int* s_rank = s_key + kLptMaxB;                        // [B] number of larger keys
-  int* s_tab = s_rank + kLptMaxB;                        // [6][kLptMaxB]: act, P, nb, w, cap, c
-  int64_t* s_base = reinterpret_cast<int64_t*>(s_tab + 6 * kLptMaxB);
-  __shared__ int s_pick;
-  const int Bp = (p.B + 3) & ~3;
-  for (int t = threadIdx.x; t < Bp; t += blockDim.x) {
-    int key = -1;                                     // padding and inactive sequences rank last
-    if (t < p.B) {
-      const int act = p.active ? p.active[t] : 1;
-      const int P = p.P[t], nb = p.nb[t], w = p.w[t];
-      s_tab[t] = act; s_tab[kLptMaxB + t] = P; s_tab[2 * kLptMaxB + t] = nb;
-      s_tab[3 * kLptMaxB + t] = w; s_tab[4 * kLptMaxB + t] = p.cap[t];
-      s_tab[5 * kLptMaxB + t] = p.c ? p.c[t] : 0;
-      s_base[t] = p.base[t];
-      const int len = act ? P + nb + w + 1 : 0;
-      key = (len << 10) | (1023 - t);                 // lengths stay below 2^20, t below 2^10
-      s_rank[t] = 0;
-    }
-    s_key[t] = key;
+__global__ __launch_bounds__(256) void decode_order_kernel(DecodeParams p) {
+  __shared__ int s_key[kLptMaxB];
+  for (int t = threadIdx.x; t < p.B; t += blockDim.x) {
+    const int act = p.active ? p.active[t] : 1;
+    const int len = act ? p.P[t] + p.nb[t] + p.w[t] + 1 : 0;   // inactive sequences rank last
+    s_key[t] = (len << 12) | (kLptMaxB - 1 - t);
   }
+  for (int t = p.B + threadIdx.x; t < ((p.B + 3) & ~3); t += blockDim.x) s_key[t] = -1;
   __syncthreads();
-  // every thread counts the larger keys in its share of the list for one sequence
-  const int parts = max(1, (int)blockDim.x / p.B);
-  const int span = (((Bp + parts - 1) / parts) + 3) & ~3;
-  for (int i = threadIdx.x; i < parts * p.B; i += blockDim.x) {
-    const int part = i / p.B, t = i - part * p.B;
-    const int mine = s_key[t];
-    const int u0 = part * span, u1 = min(Bp, u0 + span);
-    int cnt = 0;
-#pragma unroll 4
-    for (int u = u0; u < u1; u += 4) {
-      const int4 o = *reinterpret_cast<const int4*>(s_key + u);
-      cnt += (o.x > mine) + (o.y > mine) + (o.z > mine) + (o.w > mine);
-    }
-    if (parts == 1) s_rank[t] = cnt; else atomicAdd(&s_rank[t], cnt);
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= p.B) return;
+  const int mine = s_key[t];
+  int rank = 0;                                               // number of larger keys
+  for (int u = 0; u < p.B; u += 4) {
+    const int4 o = *reinterpret_cast<const int4*>(s_key + u);
+    rank += (o.x > mine) + (o.y > mine) + (o.z > mine) + (o.w > mine);
   }
-  __syncthreads();
-  for (int t = threadIdx.x; t < p.B; t += blockDim.x)
-    if (s_rank[t] == target_rank) s_pick = t;
-  __syncthreads();
-  // values read from LDS count as per-lane to the compiler: hand them back as wave-uniform
-  // scalars so that the address arithmetic that follows stays on the scalar unit
-  auto uni = [](int x) { return __builtin_amdgcn_readfirstlane(x); };
-  LptPick r;
-  r.s = uni(s_pick);
-  r.act = uni(s_tab[r.s]); r.P = uni(s_tab[kLptMaxB + r.s]); r.nb = uni(s_tab[2 * kLptMaxB + r.s]);
-  r.w = uni(s_tab[3 * kLptMaxB + r.s]); r.cap = uni(s_tab[4 * kLptMaxB + r.s]);
-  r.c = uni(s_tab[5 * kLptMaxB + r.s]);
-  const int64_t b = s_base[r.s];
-  r.base = ((int64_t)uni((int)(b >> 32)) << 32) | (uint32_t)uni((int)(b & 0xffffffff));
-  return r;
+  OrderRec r;
+  r.s = t; r.act = p.active ? p.active[t] : 1; r.P = p.P[t]; r.nb = p.nb[t];
+  r.w = p.w[t]; r.cap = p.cap[t]; r.c = p.c ? p.c[t] : 0; r.pad = 0;
+  r.base = p.base[t]; r.pad2 = 0;
+  p.order[rank] = r;
 }
 
-__device__ __forceinline__ PairInfo pair_info(const DecodeParams& p, char* scratch = nullptr) {
+__device__ __forceinline__ PairInfo pair_info(const DecodeParams& p) {
   PairInfo pi;
   int act, w;
-  if (p.lpt && scratch) {
+  if (p.lpt) {
     const int rank = blockIdx.y / p.Hkv;
-    const LptPick k = lpt_sequence(p, rank, scratch);
-    pi.s = k.s; pi.kvh = blockIdx.y - rank * p.Hkv;
-    act = k.act; pi.P = k.P; pi.nb = k.nb; w = k.w; pi.cap = k.cap; pi.c = k.c; pi.base = k.base;
-    __syncthreads();                   // the scratch area is free from here on
+    const OrderRec& r = p.order[rank];
+    pi.s = r.s; pi.kvh = blockIdx.y - rank * p.Hkv;
+    act = r.act; pi.P = r.P; pi.nb = r.nb; w = r.w; pi.cap = r.cap; pi.c = r.c; pi.base = r.base;
   } else {
     const int pair = blockIdx.y;
     pi.s = pair / p.Hkv;
@@ -270,7 +245,6 @@ constexpr int kLdsWaves = 8;           // waves per workgroup
 constexpr int kTileRows = 32;          // rows per wave tile
 constexpr int kTileBytes = kTileRows * 256;   // one K (or V) tile: 8 KB
 constexpr int kLdsBytes = kLdsWaves * 2 * kTileBytes;   // 128 KB
-static_assert(kLptScratchBytes <= kLdsBytes, "the pick's scratch lives in the tile area");
 
 typedef __attribute__((address_space(3))) void lds_void_t;
 typedef __attribute__((address_space(1))) const void global_void_t;
@@ -307,7 +281,7 @@ template <bool PROBES, bool STREAM>
 __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams p) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   if (PROBES && p.debug_stage == 1) return;
-  const PairInfo pi = pair_info(p, lds);
+  const PairInfo pi = pair_info(p);
   if (!pi.live) return;
   if (PROBES && p.debug_stage == 2) { if (pi.L == 12345678) p.out[0] = 1.f; return; }
 
@@ -733,8 +707,8 @@ struct DecodePlan {
   int rows_per_pass;  // rows one pass of a workgroup covers
   int R;              // rows per workgroup
   int max_chunks;
-  size_t tickets_bytes, part_n_bytes, part_o_bytes, part_ml_bytes;
-  size_t total() const { return tickets_bytes + part_n_bytes + part_o_bytes + part_ml_bytes; }
+  size_t tickets_bytes, order_bytes, part_n_bytes, part_o_bytes, part_ml_bytes;
+  size_t total() const { return tickets_bytes + order_bytes + part_n_bytes + part_o_bytes + part_ml_bytes; }
 };
 
 static int padded_group(int g) { return g <= 1 ? 1 : g <= 2 ? 2 : g <= 4 ? 4 : g <= 6 ? 6 : 8; }
@@ -783,6 +757,7 @@ static DecodePlan make_plan(const bc_shape* sh, int max_cap, int rows_override, 
   if (rows_override == kPlanForSizing) pl.max_chunks = npairs < 128 ? 64 : 4;
   const size_t pairs = (size_t)sh->B * sh->Hkv;
   pl.tickets_bytes = align256((size_t)sh->B * 4);
+  pl.order_bytes = align256((size_t)sh->B * sizeof(OrderRec));
   pl.part_n_bytes = align256(pairs * 4);
   pl.part_o_bytes = align256(pairs * pl.max_chunks * pl.Gp * sh->d * 4);
   pl.part_ml_bytes = align256(pairs * pl.max_chunks * 2 * pl.Gp * 4);
@@ -842,21 +817,21 @@ static int32_t launch_attention(const bc_shape* shape, const bc_cache* cache, co
   p.active = active;
   char* ws = static_cast<char*>(workspace);
   p.tickets = reinterpret_cast<int32_t*>(ws);
-  p.part_n = pl.max_chunks > 1 ? reinterpret_cast<int32_t*>(ws + pl.tickets_bytes) : nullptr;
-  p.part_o = reinterpret_cast<float*>(ws + pl.tickets_bytes + pl.part_n_bytes);
-  p.part_ml = reinterpret_cast<float*>(ws + pl.tickets_bytes + pl.part_n_bytes + pl.part_o_bytes);
+  p.order = reinterpret_cast<OrderRec*>(ws + pl.tickets_bytes);
+  char* parts = ws + pl.tickets_bytes + pl.order_bytes;
+  p.part_n = pl.max_chunks > 1 ? reinterpret_cast<int32_t*>(parts) : nullptr;
+  p.part_o = reinterpret_cast<float*>(parts + pl.part_n_bytes);
+  p.part_ml = reinterpret_cast<float*>(parts + pl.part_n_bytes + pl.part_o_bytes);
   p.c = cache->c; p.nb_rw = cache->nb; p.w_rw = cache->w;
   p.new_k = static_cast<const char*>(k); p.new_v = static_cast<const char*>(v);
   p.bk = static_cast<const char*>(bk); p.bv = static_cast<const char*>(bv);
   p.budget = budget; p.live = live;
   p.beacon_row = beacon_row ? 1 : 0;
   p.B = shape->B;
-  // Ragged batches that need more than one round of workgroups: longest sequence first.  Only
-  // for launches that leave the tables alone: a fused step updates nb and w of a sequence when
-  // its last workgroup ends, so later workgroups would rank different lengths and the picks
-  // would no longer form a permutation.
-  p.lpt = (pl.lds && pl.max_chunks == 1 && !k && !bk && !budget && shape->B <= kLptMaxB &&
-           shape->B * shape->Hkv > kLptMinPairs && cache->max_cap < (1 << 20) && g_variant != 3)
+  // Batches that need more than one round of workgroups: longest sequence first (see
+  // decode_order_kernel).  The fused steps take part as well: the records are a snapshot.
+  p.lpt = (pl.lds && pl.max_chunks == 1 && shape->B <= kLptMaxB &&
+           shape->B * shape->Hkv > kLptMinPairs && cache->max_cap < kLptMaxLen && g_variant != 3)
               ? 1 : 0;
   p.Hq = shape->Hq; p.Hkv = shape->Hkv; p.g = shape->Hq / shape->Hkv;
   p.Gp = pl.Gp;
@@ -875,6 +850,7 @@ static int32_t launch_attention(const bc_shape* shape, const bc_cache* cache, co
     const bool stream = (long)pairs * pl.max_chunks >= kStreamMinWorkgroups && g_variant != 4;
     auto kfn = p.debug_stage ? (stream ? decode_lds_kernel<true, true> : decode_lds_kernel<true, false>)
                              : (stream ? decode_lds_kernel<false, true> : decode_lds_kernel<false, false>);
+    if (p.lpt) decode_order_kernel<<<(shape->B + 255) / 256, 256, 0, hs>>>(p);
     kfn<<<grid, kLdsWaves * 64, kLdsBytes, hs>>>(p);
   } else if (shape->kv_dtype == BC_BF16) {
     if (shape->d == 128) launch_valu<bf16_t, 128>(p, pl.Gp, grid, hs);

@@ -231,18 +231,19 @@ def test_small_batch_rows_spread_over_workgroups(dev, dtype, d):
     assert np.array_equal(a, b)                    # reproducible: fixed merge order, no atomics
 
 
-def test_longest_first_dispatch_large_ragged_batch(dev):
-    # more (sequence, KV head) pairs than compute units: in bc_decode_attn workgroups pick their
-    # sequence by rank of the resident length (fused steps keep the plain order, their tables
-    # change during the launch).  Against the oracle with and without an inactive stripe, and
-    # bit-equality with the plain dispatch order (tuning variant 3).
+@pytest.mark.parametrize("B,Hq,Hkv", [(160, 12, 2), (300, 4, 1)])
+def test_longest_first_dispatch_large_ragged_batch(dev, B, Hq, Hkv):
+    # more (sequence, KV head) pairs than compute units: a sort kernel in front of the main one
+    # ranks the sequences by resident length and workgroup i serves the i-th longest, in
+    # bc_decode_attn and in the fused steps (B = 300: the ranking itself spans two workgroups).
+    # Against the oracle with and without an inactive stripe, and bit-equality with the plain
+    # dispatch order (tuning variant 3).
     bc = _bc()
-    B = 160
     rng = np.random.default_rng(23)
     P = rng.integers(1, 700, size=B).astype(np.int32)
     P[:4] = [1, 699, 350, 350]
     c = rng.choice([0, 2, 4, 16], size=B).astype(np.int32)
-    wl = W.Workload("lpt", 87, B, 12, 2, 128, "bf16", P, np.full(B, 40, np.int32), c)
+    wl = W.Workload("lpt", 87, B, Hq, Hkv, 128, "bf16", P, np.full(B, 40, np.int32), c)
     rt, oc = make(wl, dev)
     active = np.ones(B, np.uint8)
     active[5::7] = 0
@@ -444,11 +445,19 @@ def test_budget_rule_interrupts_generation_on_device(dev, dtype, d):
                     np.array([3, 0, 17, 32, 5, 64], np.int32), np.full(B, 200, np.int32), c)
     rt, oc = make(wl, dev)
     budget = np.array([10, 12, 7, 20, 9, 15], np.int32)
+    budget_rollout(wl, rt, oc, budget, 120, None, dev)
+
+
+def budget_rollout(wl, rt, oc, budget, steps, attention_steps, dev):
+    """Steps under the evaluation cap: outputs, live flags, tables and the step at which every
+    sequence ends against the oracle; attention_steps = None checks every step."""
+    import torch
+    B, c = wl.B, wl.c
     bud_d = torch.from_numpy(budget).to(dev)
     live_d = torch.ones(B, dtype=torch.uint8, device=dev)
     live = [1] * B
     last = [None] * B
-    for t in range(1, 121):
+    for t in range(1, steps + 1):
         k, v = wl.step_kv(t)
         q = wl.step_q(t)
         bk, bv = wl.beacon_kv(t)
@@ -457,7 +466,7 @@ def test_budget_rule_interrupts_generation_on_device(dev, dtype, d):
         was = list(live)
         oc.append(k, v, active=was)
         act = [s for s in range(B) if was[s]]
-        if act:
+        if act and (attention_steps is None or t in attention_steps):
             check_attention(o, q, oc, wl, act, t)
         for s in range(B):
             if not was[s]:
@@ -471,7 +480,21 @@ def test_budget_rule_interrupts_generation_on_device(dev, dtype, d):
                 last[s] = t
     check_slabs(rt, oc)
     for s in range(B):
-        assert last[s] == OR.first_step_reaching(int(budget[s]), int(c[s])), (s, last[s])
+        if last[s] is not None or OR.first_step_reaching(int(budget[s]), int(c[s])) <= steps:
+            assert last[s] == OR.first_step_reaching(int(budget[s]), int(c[s])), (s, last[s])
+
+
+def test_budget_rule_large_batch_longest_first(dev):
+    # more pairs than compute units: the budget step runs behind the sort kernel, whose records
+    # are a snapshot of tables and live flags taken before any workgroup updates them
+    B = 300
+    rng = np.random.default_rng(31)
+    P = rng.integers(1, 400, size=B).astype(np.int32)
+    c = rng.choice([0, 1, 3, 16], size=B).astype(np.int32)
+    wl = W.Workload("budget_lpt", 93, B, 4, 1, 128, "bf16", P, np.full(B, 60, np.int32), c)
+    rt, oc = make(wl, dev)
+    budget = rng.integers(4, 30, size=B).astype(np.int32)
+    budget_rollout(wl, rt, oc, budget, 36, (1, 2, 5, 17, 36), dev)
 
 
 @pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64)])
