@@ -830,7 +830,7 @@ static int32_t launch_attention(const bc_shape* shape, const bc_cache* cache, co
   p.B = shape->B;
   // Batches that need more than one round of workgroups: longest sequence first (see
   // decode_order_kernel).  The fused steps take part as well: the records are a snapshot.
-  p.lpt = (pl.lds && pl.max_chunks == 1 && shape->B <= kLptMaxB &&
+  p.lpt = (pl.max_chunks == 1 && shape->B <= kLptMaxB &&
            shape->B * shape->Hkv > kLptMinPairs && cache->max_cap < kLptMaxLen && g_variant != 3)
               ? 1 : 0;
   p.Hq = shape->Hq; p.Hkv = shape->Hkv; p.g = shape->Hq / shape->Hkv;
@@ -843,6 +843,7 @@ static int32_t launch_attention(const bc_shape* shape, const bc_cache* cache, co
 
   const int pairs = shape->B * shape->Hkv;
   const dim3 grid(pl.max_chunks, pairs);
+  if (p.lpt) decode_order_kernel<<<(shape->B + 255) / 256, 256, 0, hs>>>(p);
   if (pl.lds) {
     const int32_t st = enable_big_lds();
     if (st != BC_OK) return st;
@@ -850,7 +851,6 @@ static int32_t launch_attention(const bc_shape* shape, const bc_cache* cache, co
     const bool stream = (long)pairs * pl.max_chunks >= kStreamMinWorkgroups && g_variant != 4;
     auto kfn = p.debug_stage ? (stream ? decode_lds_kernel<true, true> : decode_lds_kernel<true, false>)
                              : (stream ? decode_lds_kernel<false, true> : decode_lds_kernel<false, false>);
-    if (p.lpt) decode_order_kernel<<<(shape->B + 255) / 256, 256, 0, hs>>>(p);
     kfn<<<grid, kLdsWaves * 64, kLdsBytes, hs>>>(p);
   } else if (shape->kv_dtype == BC_BF16) {
     if (shape->d == 128) launch_valu<bf16_t, 128>(p, pl.Gp, grid, hs);

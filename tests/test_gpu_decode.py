@@ -231,8 +231,9 @@ def test_small_batch_rows_spread_over_workgroups(dev, dtype, d):
     assert np.array_equal(a, b)                    # reproducible: fixed merge order, no atomics
 
 
-@pytest.mark.parametrize("B,Hq,Hkv", [(160, 12, 2), (300, 4, 1)])
-def test_longest_first_dispatch_large_ragged_batch(dev, B, Hq, Hkv):
+@pytest.mark.parametrize("B,Hq,Hkv,dtype,d", [(160, 12, 2, "bf16", 128), (300, 4, 1, "bf16", 128),
+                                             (272, 2, 1, "f32", 64)])
+def test_longest_first_dispatch_large_ragged_batch(dev, B, Hq, Hkv, dtype, d):
     # more (sequence, KV head) pairs than compute units: a sort kernel in front of the main one
     # ranks the sequences by resident length and workgroup i serves the i-th longest, in
     # bc_decode_attn and in the fused steps (B = 300: the ranking itself spans two workgroups).
@@ -243,7 +244,7 @@ def test_longest_first_dispatch_large_ragged_batch(dev, B, Hq, Hkv):
     P = rng.integers(1, 700, size=B).astype(np.int32)
     P[:4] = [1, 699, 350, 350]
     c = rng.choice([0, 2, 4, 16], size=B).astype(np.int32)
-    wl = W.Workload("lpt", 87, B, Hq, Hkv, 128, "bf16", P, np.full(B, 40, np.int32), c)
+    wl = W.Workload("lpt", 87, B, Hq, Hkv, d, dtype, P, np.full(B, 40, np.int32), c)
     rt, oc = make(wl, dev)
     active = np.ones(B, np.uint8)
     active[5::7] = 0
