@@ -574,3 +574,27 @@ def test_ratio_change_mid_generation(dev):
         if t in (9, 17, 30, 31, 32, 70, 90, 120):
             check_slabs(rt, oc)
     assert oc.err == ERR_STATE          # the change at step 31 did not fit some windows
+
+
+@pytest.mark.parametrize("case", range(12))
+def test_randomised_small_rollouts(dev, case):
+    # seeded random shapes, prompt lengths, ratios and generation lengths; the call form (separate
+    # calls, tail form, fused step, fused step + beacon step) rotates with the case number
+    rng = np.random.default_rng([20251013, 77, case])
+    dtype, d = [("bf16", 128), ("f32", 64), ("bf16", 64), ("f32", 128)][case % 4]
+    Hq, Hkv = [(12, 2), (4, 4), (8, 1), (6, 2), (7, 1), (5, 5), (16, 2), (3, 1)][int(rng.integers(0, 8))]
+    B = int(rng.integers(1, 10))
+    P = rng.integers(0, 300, size=B).astype(np.int32)
+    c = rng.choice([0, 1, 2, 3, 5, 8, 16], size=B).astype(np.int32)
+    steps = 45
+    G = rng.integers(1, steps + 1, size=B).astype(np.int32)
+    G[int(rng.integers(0, B))] = steps
+    for s in range(B):
+        if P[s] == 0 and G[s] < 1:
+            G[s] = 1
+    wl = W.Workload("rand%d" % case, 200 + case, B, Hq, Hkv, d, dtype, P, G, c)
+    rt, oc = make(wl, dev)
+    form = case % 4
+    attn = sorted(set(int(x) for x in rng.integers(1, steps + 1, size=8)) | {1, steps})
+    rollout(wl, rt, oc, steps, attn, (steps // 2, steps), tail_form=(form == 1),
+            use_step_call=(form == 2), beacon_call=(form == 3))

@@ -192,3 +192,25 @@ def test_config5_bwd_full_size(dev):
     assert np.isfinite(dq).all() and np.isfinite(dk).all() and np.isfinite(dv).all()
     errs = _check_bwd(pw, qkv, dos, off, dq, dk, dv, 0)
     print("config5 bwd dq/dk/dv", errs)
+
+
+@pytest.mark.parametrize("case", range(8))
+def test_prefill_randomised_forward_and_backward(dev, case):
+    # seeded random trajectory counts, prompt and response lengths, ratios and head layouts;
+    # every row of the forward and every gradient element against the oracle
+    rng = np.random.default_rng([20251013, 78, case])
+    Hq, Hkv = [(12, 2), (4, 4), (8, 1), (6, 2), (7, 1), (5, 5), (16, 2), (3, 1)][case]
+    B = int(rng.integers(1, 6))
+    P = rng.integers(0, 150, size=B).astype(np.int32)
+    R = rng.integers(0, 260, size=B).astype(np.int32)
+    R[(P == 0) & (R == 0)] = 1
+    c = rng.choice([0, 1, 2, 3, 7, 16, 33], size=B).astype(np.int32)
+    pw = W.PrefillWorkload("pf_rand%d" % case, 300 + case, B, Hq, Hkv, 128, "bf16", P, R, c)
+    qkv, off, out, lse = _run(pw, dev)
+    assert np.isfinite(out).all()
+    for b in range(pw.B):
+        _check_rows(pw, qkv, off, out, lse, b, list(range(int(pw.S[b]))))
+    qkv, dos, off, dq, dk, dv = _run_bwd(pw, dev)
+    assert np.isfinite(dq).all() and np.isfinite(dk).all() and np.isfinite(dv).all()
+    for b in range(pw.B):
+        _check_bwd(pw, qkv, dos, off, dq, dk, dv, b)
