@@ -231,6 +231,18 @@ def test_small_batch_rows_spread_over_workgroups(dev, dtype, d):
     assert np.array_equal(a, b)                    # reproducible: fixed merge order, no atomics
 
 
+def test_very_long_context_next_to_a_short_one(dev):
+    # one sequence of 150,000 resident rows (64 chunks of 2,344 rows and the merge launch) beside
+    # one of 40 rows that stays whole; a few fused steps, then attention, against the oracle
+    wl = W.Workload("long", 89, 2, 12, 2, 128, "bf16", np.array([150000, 40], np.int32),
+                    np.full(2, 6, np.int32), np.array([4, 2], np.int32))
+    rt, oc = make(wl, dev)
+    rollout(wl, rt, oc, 6, (1, 4, 5, 6), (6,), use_step_call=True)
+    q = wl.step_q(9)
+    a = rt.decode_attn(q).cpu().numpy().copy()
+    check_attention(a, q, oc, wl, None, 9)
+
+
 @pytest.mark.parametrize("B,Hq,Hkv,dtype,d", [(160, 12, 2, "bf16", 128), (300, 4, 1, "bf16", 128),
                                              (272, 2, 1, "f32", 64)])
 def test_longest_first_dispatch_large_ragged_batch(dev, B, Hq, Hkv, dtype, d):
