@@ -214,3 +214,18 @@ def test_prefill_randomised_forward_and_backward(dev, case):
     assert np.isfinite(dq).all() and np.isfinite(dk).all() and np.isfinite(dv).all()
     for b in range(pw.B):
         _check_bwd(pw, qkv, dos, off, dq, dk, dv, b)
+
+
+def test_prefill_long_trajectory(dev):
+    # a 32k-token response (the longest generation the paper's setups allow) in one trajectory:
+    # 2,048 beacons, 64 gathered beacon tiles per late query tile; sampled rows against the oracle
+    pw = W.PrefillWorkload("pf_long", 64, 1, 12, 2, 128, "bf16", np.array([512], np.int32),
+                           np.array([32768], np.int32), np.array([16], np.int32))
+    S = int(pw.S[0])
+    assert S == 512 + 32768 + 2048
+    qkv, off, out, lse = _run(pw, dev)
+    assert np.isfinite(out).all()
+    rng = np.random.default_rng(4)
+    rows = sorted(set([0, 511, 512, 528, 529, S - 1, S - 2, S - 17, S - 18])
+                  | set(int(x) for x in rng.integers(0, S, size=160)))
+    _check_rows(pw, qkv, off, out, lse, 0, rows)
