@@ -415,11 +415,13 @@ def main():
     W = args.warmup if args.warmup >= 0 else cycle
     K = args.steps if args.steps >= 0 else total - W
     use_graph = not args.no_graph and K % cycle == 0 and W % cycle == 0
-    if (K + W) % NL or K + W > total:
-        print("bench.py: steps + warmup must be a multiple of --layers and at most %d" % total,
-              file=sys.stderr)
+    if K < 1 or K + W > total:
+        print("bench.py: steps must be at least 1 and steps + warmup at most %d (one rollout of %d "
+              "tokens through %d layers)" % (total, G, NL), file=sys.stderr)
         sys.exit(2)
-    t0 = G - (K + W) // NL                      # tokens already generated when the warm-up starts
+    # the run ends at the end of the rollout; a count that is not a multiple of --layers simply
+    # stops part-way through the last token's layers (every layer-step is a step of its own cache)
+    t0 = G - (K + W + NL - 1) // NL             # tokens already generated when the warm-up starts
 
     # --- state: NL cache instances fast-forwarded to token t0, inputs resident in HBM ---------
     gen = torch.Generator(device=dev)
@@ -444,6 +446,9 @@ def main():
                  bk=rnd(wl.B, wl.Hkv, wl.d), bv=rnd(wl.B, wl.Hkv, wl.d)) for _ in range(n_pool)]
 
     faithful = args.beacon_attn and c > 0
+    if faithful and (K % NL or W % NL):
+        print("bench.py: with --beacon-attn steps and warmup must be multiples of --layers", file=sys.stderr)
+        sys.exit(2)
 
     def layer_step(i):
         """i-th layer-step of the rollout (counted from the warm-up start)."""
@@ -505,14 +510,15 @@ def main():
 
     err = max(rt.tables()[2] for rt in layers)
     nb_end, w_end, _ = layers[0].tables()
-    t_end = t0 + (W + K) // NL
+    t_end = t0 + (W + K + NL - 1) // NL         # tokens the first layer's cache has seen
     want = (t_end // c, t_end % c) if c > 0 else (0, t_end)
     assert err == 0 and (int(nb_end[0]), int(w_end[0])) == want, (err, nb_end[0], w_end[0], want)
     assert torch.isfinite(layers[0].out).all()
 
     tok_first = t0 + W // NL + 1
     step_bytes = [kv_bytes_per_step(wl, t) for t in range(tok_first, t_end + 1)]
-    total_bytes = sum(step_bytes) * NL
+    # layer-step i (counted from the warm-up start) belongs to token t0 + i // NL + 1
+    total_bytes = sum(step_bytes[(i // NL) - (W // NL)] for i in range(W, W + K))
     launches = K
     if faithful:     # the beacon steps read the full window plus the beacon itself
         row = wl.B * wl.Hkv * wl.d * 2 * 2
