@@ -229,3 +229,35 @@ def test_prefill_long_trajectory(dev):
     rows = sorted(set([0, 511, 512, 528, 529, S - 1, S - 2, S - 17, S - 18])
                   | set(int(x) for x in rng.integers(0, S, size=160)))
     _check_rows(pw, qkv, off, out, lse, 0, rows)
+
+
+class _PeakedKeys:
+    """A PrefillWorkload whose keys have a wide range of magnitudes: every 64th key row is scaled
+    by 4 and the last quarter of every trajectory by 2 (both exact in bf16), so that the softmax
+    is dominated by few keys and its running reference has to move many times."""
+
+    def __init__(self, pw):
+        self._pw = pw
+
+    def __getattr__(self, name):
+        return getattr(self._pw, name)
+
+    def qkv(self, b):
+        q, k, v = self._pw.qkv(b)
+        k = k.copy()
+        k[63::64] *= 4.0
+        k[3 * len(k) // 4:] *= 2.0
+        return q, k, v
+
+
+def test_prefill_peaked_keys_forward_and_backward(dev):
+    pw = _PeakedKeys(W.PrefillWorkload("pf_peak", 65, 3, 12, 2, 128, "bf16", np.array([5, 100, 256], np.int32),
+                                       np.array([600, 900, 300], np.int32), np.array([16, 4, 0], np.int32)))
+    qkv, off, out, lse = _run(pw, dev)
+    assert np.isfinite(out).all()
+    for b in range(pw.B):
+        _check_rows(pw, qkv, off, out, lse, b, list(range(int(pw.S[b]))))
+    qkv, dos, off, dq, dk, dv = _run_bwd(pw, dev)
+    assert np.isfinite(dq).all() and np.isfinite(dk).all() and np.isfinite(dv).all()
+    for b in range(pw.B):
+        _check_bwd(pw, qkv, dos, off, dq, dk, dv, b)
