@@ -610,3 +610,68 @@ def test_randomised_small_rollouts(dev, case):
     attn = sorted(set(int(x) for x in rng.integers(1, steps + 1, size=8)) | {1, steps})
     rollout(wl, rt, oc, steps, attn, (steps // 2, steps), tail_form=(form == 1),
             use_step_call=(form == 2), beacon_call=(form == 3))
+
+
+def test_fused_steps_under_graph_replay(dev):
+    # The benchmark replays a captured cycle of fused steps.  One runtime runs five 4-step cycles
+    # eagerly, a twin runs the first cycle eagerly, captures the cycle as a HIP graph and replays
+    # it four times with eager calls and synchronisations in between; every step's output, the
+    # tables and the slabs must be bit-equal, and the last outputs match the oracle.
+    import torch
+    bc = _bc()
+    B, cyc, ncyc = 8, 4, 5
+    wl = W.Workload("graph", 95, B, 12, 2, 128, "bf16", np.array([3, 40, 0, 17, 64, 5, 33, 1], np.int32),
+                    np.full(B, cyc * ncyc, np.int32), np.array([4, 2, 0, 1, 3, 4, 2, 4], np.int32))
+    rtE, oc = make(wl, dev)
+    rtG, _ = make(wl, dev)
+    pool = []
+    for j in range(1, cyc + 1):
+        k, v = wl.step_kv(j)
+        bk, bv = wl.beacon_kv(j)
+        host = dict(k=k, v=v, q=wl.step_q(j), bk=bk, bv=bv)
+        pool.append((host, {n: bc.to_device(a, "bf16", dev) for n, a in host.items()}))
+    outsE = [torch.empty_like(rtE.out) for _ in range(cyc)]
+    outsG = [torch.empty_like(rtG.out) for _ in range(cyc)]
+
+    def cycle(rt, outs):
+        for j in range(cyc):
+            x = pool[j][1]
+            rt.decode_step(x["k"], x["v"], x["q"], x["bk"], x["bv"], out=outs[j])
+
+    st = torch.cuda.Stream()
+    ref_out = []
+    for _ in range(ncyc):                                   # eager twin + oracle
+        cycle(rtE, outsE)
+        torch.cuda.synchronize()
+        ref_out.append([o.cpu().numpy().copy() for o in outsE])
+        for j in range(cyc):
+            h = pool[j][0]
+            oc.append(h["k"], h["v"])
+            last_ref = (h["q"], [OA.decode_attention(h["q"][s], *oc.resident(s), wl.scale) for s in range(B)])
+            oc.compress_evict(h["bk"], h["bv"])
+    with torch.cuda.stream(st):
+        cycle(rtG, outsG)                                   # first cycle eagerly
+        st.synchronize()
+        assert all(np.array_equal(a.cpu().numpy(), b) for a, b in zip(outsG, ref_out[0]))
+        saved = (rtG.nb.clone(), rtG.w.clone())
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=st):
+            cycle(rtG, outsG)
+        rtG.nb.copy_(saved[0]); rtG.w.copy_(saved[1])       # capture does not run; restore anyway
+        for r in range(1, ncyc):
+            g.replay()
+            st.synchronize()
+            got = [o.cpu().numpy().copy() for o in outsG]
+            for j in range(cyc):
+                assert np.array_equal(got[j], ref_out[r][j]), (r, j)
+            # the program's own eager work between replays: an attention call and a table read
+            rtG.decode_attn(pool[0][1]["q"], out=torch.empty_like(rtG.out))
+            nb, w, err = rtG.tables()
+            assert err == 0
+    nbE, wE, _ = rtE.tables()
+    nbG, wG, _ = rtG.tables()
+    assert list(nbE) == list(nbG) == oc.nb and list(wE) == list(wG) == oc.w
+    check_slabs(rtG, oc)
+    q, ref = last_ref
+    worst = max(float(np.abs(ref_out[-1][-1][s] - ref[s]).max()) for s in range(B))
+    assert worst <= TOL[wl.dtype], worst
