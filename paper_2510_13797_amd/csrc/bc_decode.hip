@@ -11,12 +11,12 @@
 // the sequences by resident length.
 //
 // Two main kernels:
-//  * decode_lds_kernel (bf16, d = 128): every wave streams 32-row K and V tiles from HBM
+//  * decode_lds_kernel (bf16, d = 128 or 64): every wave streams 32-row K and V tiles from HBM
 //    straight into its own LDS region with 16-byte LDS-DMA loads (1 KB of consecutive bytes
-//    per instruction, 16 KB in flight per wave), then forms the q.K products and the p.V
+//    per instruction, 16 KB in flight per wave at d = 128), then forms the q.K products and the p.V
 //    sums of all query heads of the group with 16x16x32 bf16 MFMA tiles fed from LDS (K by
 //    128-bit reads, V by the 16-bit transposing reads), softmax in registers.
-//  * decode_valu_kernel (fp32 and d = 64): rows held in registers, 16 bytes per lane, plain
+//  * decode_valu_kernel (fp32): rows held in registers, 16 bytes per lane, plain
 //    FMA dot products completed by a DPP all-reduce.
 #include "bc_common.h"
 
@@ -239,12 +239,11 @@ __device__ __forceinline__ void merge_waves_and_store(const DecodeParams& p, con
 }
 
 // ---------------------------------------------------------------------------
-// bf16, d = 128: LDS-DMA tiles + MFMA
+// bf16, d = 128 or 64: LDS-DMA tiles + MFMA
 // ---------------------------------------------------------------------------
 constexpr int kLdsWaves = 8;           // waves per workgroup
 constexpr int kTileRows = 32;          // rows per wave tile
-constexpr int kTileBytes = kTileRows * 256;   // one K (or V) tile: 8 KB
-constexpr int kLdsBytes = kLdsWaves * 2 * kTileBytes;   // 128 KB
+constexpr int kLdsBytes = kLdsWaves * 2 * kTileRows * 256;   // d = 128: 128 KB (half of it for d = 64)
 
 typedef __attribute__((address_space(3))) void lds_void_t;
 typedef __attribute__((address_space(1))) const void global_void_t;
@@ -274,12 +273,31 @@ __device__ __forceinline__ uint32_t bf16_rne_bits(float x) {     // finite x onl
   return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
+// Swizzle of the 16-byte units of a tile row in LDS: unit u of row `row` lives at position
+// u ^ tile_swz<D>(row).  D = 128 (16 units per row): lds_swz.  D = 64 (8 units per row, two rows
+// per 256 bytes of banks): the 128-bit reads of one unit from the 8 rows {a, a+1, a+2, a+3, a+8,
+// .., a+11} must hit 8 different 16-byte bank groups - the row parity gives two, bits 1 and 3 of
+// the row the other four - and the transposing 64-bit reads of a half wave (rows {a..a+3} and
+// {a+8..a+11}, two adjacent units each) the 32 different 8-byte slots, which the same bits give.
+template <int D> __device__ __forceinline__ int tile_swz(int row);
+template <> __device__ __forceinline__ int tile_swz<128>(int row) { return lds_swz(row); }
+template <> __device__ __forceinline__ int tile_swz<64>(int row) {
+  return (((row >> 1) & 1) << 1) | (((row >> 3) & 1) << 2);
+}
+
 // PROBES: honour the early exits of the timing probes (tuning variants 11..15).
 // STREAM: load K/V with the non-temporal policy (large launches; small ones are latency-bound
 // and about a microsecond faster with the default policy).
-template <bool PROBES, bool STREAM>
+template <bool PROBES, bool STREAM, int D>
 __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams p) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
+  constexpr int ROWB = D * 2;              // bytes of one row of one KV head: 256 or 128
+  constexpr int UPR = ROWB / 16;           // 16-byte units per row: 16 or 8
+  constexpr int RPI = 1024 / ROWB;         // rows one 1 KB LDS-DMA instruction brings: 4 or 8
+  constexpr int NDMA = kTileRows / RPI;    // such instructions per K (or V) tile: 8 or 4
+  constexpr int NI = D / 32;               // MFMAs (k = 32) along the head dimension: 4 or 2
+  constexpr int NJ = D / 16;               // 16-column blocks of the output: 8 or 4
+  constexpr int TILEB = kTileRows * ROWB;  // one K (or V) tile: 8 or 4 KB
   if (PROBES && p.debug_stage == 1) return;
   const PairInfo pi = pair_info(p);
   if (!pi.live) return;
@@ -287,36 +305,36 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, kb = lane >> 4;       // MFMA column / k-block of this lane
-  const int64_t stream_off = (pi.base * p.Hkv + (int64_t)pi.kvh * pi.cap) * 256;
+  const int64_t stream_off = (pi.base * p.Hkv + (int64_t)pi.kvh * pi.cap) * ROWB;
   const char* kbase = p.k_slab + stream_off;
   const char* vbase = p.v_slab + stream_off;
-  char* wk = lds + wave * (2 * kTileBytes);
-  char* wv = wk + kTileBytes;
+  char* wk = lds + wave * (2 * TILEB);
+  char* wv = wk + TILEB;
 
   // B operand of the score product: Q^T, column n = query head, k = head-dim index.
-  bf16x8_t qb[4];
+  bf16x8_t qb[NI];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < NI; ++i) {
     uint4 r = make_uint4(0u, 0u, 0u, 0u);
     if (n < p.g)
       r = *reinterpret_cast<const uint4*>(
-          p.q + ((int64_t)(pi.s * p.Hq + pi.kvh * p.g + n) * 128 + 32 * i + 8 * kb) * 2);
+          p.q + ((int64_t)(pi.s * p.Hq + pi.kvh * p.g + n) * D + 32 * i + 8 * kb) * 2);
     qb[i] = __builtin_bit_cast(bf16x8_t, r);
   }
 
-  // fused append: lanes 0..15 carry the new K row, lanes 16..31 the new V row (16 bytes each)
+  // fused append: lanes 0..UPR-1 carry the new K row, the next UPR lanes the new V row (16 bytes each)
   uint4 newrow = make_uint4(0u, 0u, 0u, 0u);
-  if (pi.new_row >= 0 && lane < 32) {
-    const char* src = (lane < 16 ? p.new_k : p.new_v) +
-                      (int64_t)(pi.s * p.Hkv + pi.kvh) * 256 + ((lane & 15) << 4);
+  if (pi.new_row >= 0 && lane < 2 * UPR) {
+    const char* src = (lane < UPR ? p.new_k : p.new_v) +
+                      (int64_t)(pi.s * p.Hkv + pi.kvh) * ROWB + ((lane & (UPR - 1)) << 4);
     newrow = *reinterpret_cast<const uint4*>(src);
   }
   // rows the tile loads may touch: the resident rows that are already in the slab
   const int last_slab_row = max((pi.new_row >= 0 ? pi.new_row : pi.L) - 1, 0);
 
-  f32x4_t O[8];
+  f32x4_t O[NJ];
 #pragma unroll
-  for (int j = 0; j < 8; ++j) O[j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  for (int j = 0; j < NJ; ++j) O[j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
   float m_run = kNegBig, l_run = 0.f;
 
   // Tiles wave, wave + 8, ... of the chunk belong to this wave.  The first goes from HBM to
@@ -324,25 +342,25 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
   // flight from the start.  Afterwards: copy the register tile to LDS, request the next tile
   // into the freed registers, compute - one tile always in flight behind the one in use.
   const int ntiles = (pi.row_end - pi.row0 + kTileRows - 1) / kTileRows;
-  const int r4 = lane >> 4, pos = lane & 15;
-  uint4 kreg[8], vreg[8];
+  const int r4 = lane / UPR, pos = lane & (UPR - 1);   // row within a 1 KB load, unit within the row
+  uint4 kreg[NDMA], vreg[NDMA];
 #pragma unroll
-  for (int j = 0; j < 8; ++j) kreg[j] = vreg[j] = make_uint4(0u, 0u, 0u, 0u);
+  for (int j = 0; j < NDMA; ++j) kreg[j] = vreg[j] = make_uint4(0u, 0u, 0u, 0u);
 #define BC_LOAD_TILE_REGS(TROW0)                                              \
-  _Pragma("unroll") for (int j = 0; j < 8; ++j) {                             \
-    const int grow_ = min((TROW0) + 4 * j + r4, last_slab_row);               \
-    const int64_t goff_ = (int64_t)grow_ * 256 + (pos << 4);                  \
+  _Pragma("unroll") for (int j = 0; j < NDMA; ++j) {                          \
+    const int grow_ = min((TROW0) + RPI * j + r4, last_slab_row);             \
+    const int64_t goff_ = (int64_t)grow_ * ROWB + (pos << 4);                 \
     kreg[j] = load16<STREAM>(kbase + goff_);                                  \
     vreg[j] = load16<STREAM>(vbase + goff_);                                  \
   }
   if (wave < ntiles) {
-    // ---- HBM -> LDS: 8 + 8 instructions, each 4 whole rows (1 KB), 16-byte units XOR-swizzled
+    // ---- HBM -> LDS: NDMA + NDMA instructions, each RPI whole rows (1 KB), 16-byte units XOR-swizzled
     const int trow0 = pi.row0 + wave * kTileRows;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int row = 4 * j + r4;
+    for (int j = 0; j < NDMA; ++j) {
+      const int row = RPI * j + r4;
       const int grow = min(trow0 + row, last_slab_row);     // stay inside the slab rows
-      const int64_t goff = (int64_t)grow * 256 + ((pos ^ lds_swz(row)) << 4);
+      const int64_t goff = (int64_t)grow * ROWB + ((pos ^ tile_swz<D>(row)) << 4);
       __builtin_amdgcn_global_load_lds((global_void_t*)(kbase + goff),
                                        (lds_void_t*)(wk + j * 1024), 16, 0, STREAM ? kStreamPolicy : 0);
       __builtin_amdgcn_global_load_lds((global_void_t*)(vbase + goff),
@@ -353,13 +371,15 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
   for (int tile = wave; tile < ntiles; tile += kLdsWaves) {
     const int trow0 = pi.row0 + tile * kTileRows;
     if (tile == wave) {
-      if (wave + kLdsWaves < ntiles) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-      else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      // the LDS-DMA loads have landed once at most the register loads behind them are pending
+      if (wave + kLdsWaves >= ntiles) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      else if (D == 128) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+      else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
     } else {
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const int row = 4 * j + r4;
-        const int o = row * 256 + ((pos ^ lds_swz(row)) << 4);
+      for (int j = 0; j < NDMA; ++j) {
+        const int row = RPI * j + r4;
+        const int o = row * ROWB + ((pos ^ tile_swz<D>(row)) << 4);
         *reinterpret_cast<uint4*>(wk + o) = kreg[j];
         *reinterpret_cast<uint4*>(wv + o) = vreg[j];
       }
@@ -371,17 +391,17 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
       // the appended row is not in the slab yet: place it in the tile, store it for later
       // steps (unless this step's eviction drops it at once), clear the V rows behind it
       const int ra = pi.new_row - trow0;
-      if (lane < 32) {
-        char* tile = lane < 16 ? wk : wv;
-        const int u = lane & 15;
-        *reinterpret_cast<uint4*>(tile + ra * 256 + ((u ^ lds_swz(ra)) << 4)) = newrow;
+      if (lane < 2 * UPR) {
+        char* tile = lane < UPR ? wk : wv;
+        const int u = lane & (UPR - 1);
+        *reinterpret_cast<uint4*>(tile + ra * ROWB + ((u ^ tile_swz<D>(ra)) << 4)) = newrow;
         if (pi.store_new_row) {
-          char* slab = const_cast<char*>(lane < 16 ? kbase : vbase);
-          *reinterpret_cast<uint4*>(slab + (int64_t)pi.new_row * 256 + (u << 4)) = newrow;
+          char* slab = const_cast<char*>(lane < UPR ? kbase : vbase);
+          *reinterpret_cast<uint4*>(slab + (int64_t)pi.new_row * ROWB + (u << 4)) = newrow;
         }
       }
-      for (int rr = ra + 1 + (lane >> 4); rr < kTileRows; rr += 4)
-        *reinterpret_cast<uint4*>(wv + rr * 256 + ((lane & 15) << 4)) = make_uint4(0u, 0u, 0u, 0u);
+      for (int rr = ra + 1 + r4; rr < kTileRows; rr += RPI)
+        *reinterpret_cast<uint4*>(wv + rr * ROWB + (pos << 4)) = make_uint4(0u, 0u, 0u, 0u);
     }
 
     // ---- scores, transposed: S^T[key][head] = K . Q^T.  Row m of sub-tile t is key
@@ -392,10 +412,10 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
       S[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
       const int row = ((n >> 2) << 3) + 4 * t + (n & 3);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < NI; ++i) {
         const int u = 4 * i + kb;
         const bf16x8_t a =
-            *reinterpret_cast<const bf16x8_t*>(wk + row * 256 + ((u ^ lds_swz(row)) << 4));
+            *reinterpret_cast<const bf16x8_t*>(wk + row * ROWB + ((u ^ tile_swz<D>(row)) << 4));
         S[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qb[i], S[t], 0, 0, 0);
       }
     }
@@ -436,15 +456,15 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
       const int r = lane & 15;
       const int key0 = 8 * kb + (r >> 2);
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
+      for (int j = 0; j < NJ; ++j) {
         O[j] *= alpha;
         const int u = 2 * j + ((r & 3) >> 1);
         const int sub = (r & 1) << 3;
         const int rowa = key0, rowb = key0 + 4;
         const s16x4_t a0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (lds_s16x4_t*)(wv + rowa * 256 + ((u ^ lds_swz(rowa)) << 4) + sub));
+            (lds_s16x4_t*)(wv + rowa * ROWB + ((u ^ tile_swz<D>(rowa)) << 4) + sub));
         const s16x4_t a1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (lds_s16x4_t*)(wv + rowb * 256 + ((u ^ lds_swz(rowb)) << 4) + sub));
+            (lds_s16x4_t*)(wv + rowb * ROWB + ((u ^ tile_swz<D>(rowb)) << 4) + sub));
         typedef __attribute__((ext_vector_type(8))) short s16x8_t;
         const s16x8_t a = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
         const bf16x8_t av = __builtin_bit_cast(bf16x8_t, a);
@@ -470,18 +490,18 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
     asm volatile("global_atomic_add %0, %1, %2, off sc0"
                  : "=v"(ticket) : "v"(p.tickets + pi.s), "v"(one) : "memory");
   }
-  float* s_acc = reinterpret_cast<float*>(lds);                    // [wave][8][128]
-  float* s_m = s_acc + kLdsWaves * 8 * 128;                        // [wave][8]
+  float* s_acc = reinterpret_cast<float*>(lds);                    // [wave][8][D]
+  float* s_m = s_acc + kLdsWaves * 8 * D;                          // [wave][8]
   float* s_l = s_m + kLdsWaves * 8;
   int* s_last = reinterpret_cast<int*>(s_l + kLdsWaves * 8);
   if (n < p.g) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j)
-      *reinterpret_cast<f32x4_t*>(s_acc + (wave * 8 + n) * 128 + 16 * j + 4 * kb) = O[j];
+    for (int j = 0; j < NJ; ++j)
+      *reinterpret_cast<f32x4_t*>(s_acc + (wave * 8 + n) * D + 16 * j + 4 * kb) = O[j];
     if (kb == 0) { s_m[wave * 8 + n] = m_run; s_l[wave * 8 + n] = l_run; }
   }
   __syncthreads();
-  merge_waves_and_store<kLdsWaves, 128>(p, pi, s_m, s_l, s_acc, 8);
+  merge_waves_and_store<kLdsWaves, D>(p, pi, s_m, s_l, s_acc, 8);
 
   // ---- the last workgroup of the sequence writes the beacon row and updates the tables
   if (!pi.update || (PROBES && p.debug_stage == 5)) return;
@@ -492,14 +512,14 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
   __syncthreads();
   if (!*s_last) return;
   if (pi.evict_due) {
-    const int n16 = p.Hkv * 16;                    // 16-byte units of one K (or V) entry
+    const int n16 = p.Hkv * UPR;                   // 16-byte units of one K (or V) entry
     for (int i = tid; i < 2 * n16; i += kLdsWaves * 64) {
       const int which = i >= n16, r = which ? i - n16 : i;
-      const int h = r >> 4, u = r & 15;
-      const char* src = (which ? p.bv : p.bk) + (int64_t)(pi.s * p.Hkv + h) * 256 + (u << 4);
+      const int h = r / UPR, u = r & (UPR - 1);
+      const char* src = (which ? p.bv : p.bk) + (int64_t)(pi.s * p.Hkv + h) * ROWB + (u << 4);
       char* slab = const_cast<char*>(which ? p.v_slab : p.k_slab);
       const int64_t dst =
-          (pi.base * p.Hkv + (int64_t)h * pi.cap + pi.P + pi.nb) * 256 + (u << 4);
+          (pi.base * p.Hkv + (int64_t)h * pi.cap + pi.P + pi.nb) * ROWB + (u << 4);
       *reinterpret_cast<uint4*>(slab + dst) = *reinterpret_cast<const uint4*>(src);
     }
   }
@@ -718,7 +738,7 @@ constexpr int kPlanForSizing = -1;    // rows_override value: size the workspace
 
 static DecodePlan make_plan(const bc_shape* sh, int max_cap, int rows_override, int variant) {
   DecodePlan pl;
-  pl.lds = sh->kv_dtype == BC_BF16 && sh->d == 128 && variant != 1;
+  pl.lds = sh->kv_dtype == BC_BF16 && variant != 1;
   if (pl.lds) {
     pl.Gp = 8;
     pl.rows_per_pass = kLdsWaves * kTileRows;
@@ -781,10 +801,12 @@ static int32_t enable_big_lds() {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return BC_ERR_HIP;
   if (done[dev]) return BC_OK;
-  const void* kernels[4] = {reinterpret_cast<const void*>(decode_lds_kernel<false, false>),
-                            reinterpret_cast<const void*>(decode_lds_kernel<false, true>),
-                            reinterpret_cast<const void*>(decode_lds_kernel<true, false>),
-                            reinterpret_cast<const void*>(decode_lds_kernel<true, true>)};
+  const void* kernels[6] = {reinterpret_cast<const void*>(decode_lds_kernel<false, false, 128>),
+                            reinterpret_cast<const void*>(decode_lds_kernel<false, true, 128>),
+                            reinterpret_cast<const void*>(decode_lds_kernel<true, false, 128>),
+                            reinterpret_cast<const void*>(decode_lds_kernel<true, true, 128>),
+                            reinterpret_cast<const void*>(decode_lds_kernel<false, false, 64>),
+                            reinterpret_cast<const void*>(decode_lds_kernel<false, true, 64>)};
   bool ok = true;
   for (const void* kfn : kernels)
     ok = ok && hipFuncSetAttribute(kfn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) ==
@@ -849,9 +871,15 @@ static int32_t launch_attention(const bc_shape* shape, const bc_cache* cache, co
     if (st != BC_OK) return st;
     // launches that cannot saturate the memory system are latency-bound: default cache policy
     const bool stream = (long)pairs * pl.max_chunks >= kStreamMinWorkgroups && g_variant != 4;
-    auto kfn = p.debug_stage ? (stream ? decode_lds_kernel<true, true> : decode_lds_kernel<true, false>)
-                             : (stream ? decode_lds_kernel<false, true> : decode_lds_kernel<false, false>);
-    kfn<<<grid, kLdsWaves * 64, kLdsBytes, hs>>>(p);
+    if (shape->d == 128) {
+      auto kfn = p.debug_stage
+                     ? (stream ? decode_lds_kernel<true, true, 128> : decode_lds_kernel<true, false, 128>)
+                     : (stream ? decode_lds_kernel<false, true, 128> : decode_lds_kernel<false, false, 128>);
+      kfn<<<grid, kLdsWaves * 64, kLdsBytes, hs>>>(p);
+    } else {
+      auto kfn = stream ? decode_lds_kernel<false, true, 64> : decode_lds_kernel<false, false, 64>;
+      kfn<<<grid, kLdsWaves * 64, kLdsBytes / 2, hs>>>(p);
+    }
   } else if (shape->kv_dtype == BC_BF16) {
     if (shape->d == 128) launch_valu<bf16_t, 128>(p, pl.Gp, grid, hs);
     else launch_valu<bf16_t, 64>(p, pl.Gp, grid, hs);

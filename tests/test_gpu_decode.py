@@ -154,10 +154,11 @@ def test_config1_fused_step_call(dev):
     rollout(wl, rt, oc, 64, range(1, 65), (16, 17, 64), use_step_call=True)
 
 
-@pytest.mark.parametrize("c,P", [(16, 256), (1, 5), (2, 0), (3, 31), (0, 40)])
-def test_fused_step_bf16_every_step(dev, c, P):
-    # bc_decode_step on the single-launch path (bf16, d = 128): tables, slabs, outputs each step
-    wl = W.Workload("fused", 70 + c, 6, 12, 2, 128, "bf16", np.full(6, P, np.int32),
+@pytest.mark.parametrize("c,P,d", [(16, 256, 128), (1, 5, 128), (2, 0, 128), (3, 31, 128), (0, 40, 128),
+                                   (16, 256, 64), (1, 5, 64), (3, 31, 64)])
+def test_fused_step_bf16_every_step(dev, c, P, d):
+    # bc_decode_step on the single-launch path (bf16, d = 128 or 64): tables, slabs, outputs each step
+    wl = W.Workload("fused", 70 + c, 6, 12, 2, d, "bf16", np.full(6, P, np.int32),
                     np.array([150, 150, 90, 150, 33, 150], np.int32), np.full(6, c, np.int32))
     rt, oc = make(wl, dev)
     steps = range(1, 151)
@@ -166,7 +167,8 @@ def test_fused_step_bf16_every_step(dev, c, P):
 
 @pytest.mark.parametrize("Hq,Hkv,dtype,d", [(1, 1, "bf16", 128), (4, 2, "bf16", 128), (3, 1, "bf16", 128),
                                              (10, 2, "bf16", 128), (7, 1, "bf16", 128), (16, 2, "bf16", 128),
-                                             (8, 1, "f32", 64), (6, 2, "bf16", 64), (5, 1, "f32", 128)])
+                                             (8, 1, "f32", 64), (6, 2, "bf16", 64), (5, 1, "f32", 128),
+                                             (1, 1, "bf16", 64), (7, 1, "bf16", 64), (16, 2, "bf16", 64)])
 def test_group_sizes_one_to_eight(dev, Hq, Hkv, dtype, d):
     # every group size g = Hq / Hkv from 1 to 8, on the MFMA kernel and on the plain-ALU kernel
     wl = W.Workload("groups", 89, 5, Hq, Hkv, d, dtype, np.array([0, 3, 31, 64, 100], np.int32),
@@ -175,9 +177,9 @@ def test_group_sizes_one_to_eight(dev, Hq, Hkv, dtype, d):
     rollout(wl, rt, oc, 70, (1, 2, 7, 8, 16, 17, 33, 70), (16, 70), use_step_call=True)
 
 
-@pytest.mark.parametrize("name,dtype,d", [("bstep", "bf16", 128), ("bstep32", "f32", 64)])
+@pytest.mark.parametrize("name,dtype,d", [("bstep", "bf16", 128), ("bstep32", "f32", 64), ("bstep64", "bf16", 64)])
 def test_beacon_step_rollout(dev, name, dtype, d):
-    # the beacon's own step: single launch on the bf16 d=128 path, three launches otherwise
+    # the beacon's own step: single launch on the bf16 paths, three launches otherwise
     c = np.array([1, 2, 4, 8, 16, 32, 0, 3], np.int32)
     wl = W.Workload(name, 85, 8, 12, 2, d, dtype,
                     np.array([0, 1, 31, 32, 33, 64, 7, 100], np.int32),
@@ -212,7 +214,7 @@ def test_beacon_step_leaves_other_sequences_alone(dev):
     check_slabs(rt, oc)
 
 
-@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64)])
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64), ("bf16", 64)])
 def test_small_batch_rows_spread_over_workgroups(dev, dtype, d):
     # few (sequence, KV head) pairs and long sequences: the rows of a sequence are spread evenly
     # over several workgroups whose partials a second launch merges; a short sequence in the same
@@ -244,7 +246,7 @@ def test_very_long_context_next_to_a_short_one(dev):
 
 
 @pytest.mark.parametrize("B,Hq,Hkv,dtype,d", [(160, 12, 2, "bf16", 128), (300, 4, 1, "bf16", 128),
-                                             (272, 2, 1, "f32", 64)])
+                                             (272, 2, 1, "f32", 64), (280, 8, 1, "bf16", 64)])
 def test_longest_first_dispatch_large_ragged_batch(dev, B, Hq, Hkv, dtype, d):
     # more (sequence, KV head) pairs than compute units: a sort kernel in front of the main one
     # ranks the sequences by resident length and workgroup i serves the i-th longest, in
@@ -449,7 +451,7 @@ def test_deterministic_and_split_invariant(dev):
 # ---------------------------------------------------------------------------
 # next rows: evaluation budget rule and mid-generation ratio change
 # ---------------------------------------------------------------------------
-@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64)])
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64), ("bf16", 64)])
 def test_budget_rule_interrupts_generation_on_device(dev, dtype, d):
     import torch
     B = 6
@@ -510,7 +512,7 @@ def test_budget_rule_large_batch_longest_first(dev):
     budget_rollout(wl, rt, oc, budget, 36, (1, 2, 5, 17, 36), dev)
 
 
-@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64)])
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64), ("bf16", 64)])
 def test_admission_into_finished_slots(dev, dtype, d):
     # continuous batching: the budget rule ends generations at different steps; every 10 steps
     # the finished slots take new sequences (new prompt length and ratio) and carry on
