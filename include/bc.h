@@ -85,6 +85,7 @@ typedef struct {
   int32_t *w;            /* [B] rows after the beacons   (updated by the library) */
   int32_t *err;          /* [1] sticky error bits                                 */
   int32_t max_cap;       /* HOST value: max_s cap[s]; sizes grids and workspace   */
+  const int32_t *order;  /* [B] optional dispatch order, see bc_sort_by_length(); or NULL */
 } bc_cache;
 
 const char *bc_status_str(int32_t status);
@@ -130,8 +131,7 @@ int32_t bc_append_kv(const bc_shape *shape, const bc_cache *cache, const void *k
 /* Bytes of workspace bc_decode_attn() and the step calls need for this shape and max_cap
  * (enough for the automatic plan; a chunk size forced by bc_set_decode_tuning() on a batch with
  * 128 or more (sequence, KV head) pairs may split a sequence into at most four chunks, beyond
- * that the calls return BC_ERR_WORKSPACE).  Besides partial results the workspace holds one
- * counter and one 48-byte dispatch record per sequence. */
+ * that the calls return BC_ERR_WORKSPACE). */
 size_t bc_decode_workspace_bytes(const bc_shape *shape, int32_t max_cap);
 
 /* Zero a freshly allocated workspace (it holds per-sequence counters that the library
@@ -266,10 +266,22 @@ int32_t bc_topk_kl_loss_bwd(int64_t T, int32_t V, int32_t k, const void *student
 int32_t bc_tables_to_host(const bc_shape *shape, const bc_cache *cache, int32_t *nb_host,
                           int32_t *w_host, int32_t *err_host, void *stream);
 
+/* Dispatch order for large ragged batches (not in the paper: a scheduling aid for its ragged
+ * caches).  Writes to order[B] (device) the sequence indices by decreasing resident length
+ * P + nb + w, inactive sequences last.  While cache->order points to such an array, decode calls
+ * (bc_decode_attn and all step calls) on batches with more than 256 (sequence, KV head) pairs -
+ * more workgroups than the chip runs at once - let workgroup i serve sequence order[i], so the
+ * longest sequences start first and the tail of the launch is short.  The array is only read by
+ * those calls and may be stale: any permutation of 0..B-1 gives the same results as no array
+ * (refreshing it once per window is enough; a uniform batch needs none).  An entry outside
+ * 0..B-1 sets the state bit and its workgroups do nothing.  B <= 4096, else BC_ERR_SHAPE. */
+int32_t bc_sort_by_length(const bc_shape *shape, const bc_cache *cache, const uint8_t *active,
+                          int32_t *order, void *stream);
+
 /* Tuning override for experiments: rows of one (sequence, KV head) stream handled by one
  * workgroup of bc_decode_attn (0 = automatic), and kernel variant: 0 = automatic, 1 = always the
- * plain-ALU kernel, 2 = the LDS/MFMA kernel or BC_ERR_SHAPE, 3 = automatic but without the
- * longest-sequence-first dispatch of large ragged batches, 4 = automatic but with the default
+ * plain-ALU kernel, 2 = the LDS/MFMA kernel or BC_ERR_SHAPE, 3 = automatic but ignoring
+ * cache->order, 4 = automatic but with the default
  * cache policy for the K/V loads of large launches; 11..15 = timing probes that leave
  * the LDS/MFMA kernel after a given stage (outputs are then meaningless). */
 void bc_set_decode_tuning(int32_t rows_per_workgroup, int32_t variant);

@@ -28,6 +28,7 @@ EXPORTS = [
     "bc_status_str", "bc_version", "bc_cache_init", "bc_cache_admit", "bc_append_kv",
     "bc_decode_workspace_bytes", "bc_workspace_init", "bc_decode_attn",
     "bc_compress_evict", "bc_decode_step", "bc_beacon_step", "bc_decode_step_budget", "bc_set_ratio",
+    "bc_sort_by_length",
     "bc_prefill_attn", "bc_prefill_bwd_workspace_bytes", "bc_prefill_attn_bwd",
     "bc_topk_kl_loss", "bc_topk_kl_loss_bwd", "bc_tables_to_host", "bc_set_decode_tuning",
 ]
@@ -42,7 +43,7 @@ class bc_cache(C.Structure):
     _fields_ = [("k_slab", C.c_void_p), ("v_slab", C.c_void_p), ("base", C.c_void_p),
                 ("cap", C.c_void_p), ("P", C.c_void_p), ("c", C.c_void_p),
                 ("nb", C.c_void_p), ("w", C.c_void_p), ("err", C.c_void_p),
-                ("max_cap", C.c_int32)]
+                ("max_cap", C.c_int32), ("order", C.c_void_p)]
 
 
 class BcError(RuntimeError):
@@ -72,6 +73,8 @@ def load():
     lib.bc_cache_init.argtypes = [sp, cp, vp, vp, vp, i64, vp]
     lib.bc_cache_admit.restype = i32
     lib.bc_cache_admit.argtypes = [sp, cp, vp, vp, vp, i64, vp, vp, vp, vp]
+    lib.bc_sort_by_length.restype = i32
+    lib.bc_sort_by_length.argtypes = [sp, cp, vp, vp, vp]
     lib.bc_append_kv.restype = i32
     lib.bc_append_kv.argtypes = [sp, cp, vp, vp, vp, i32, vp]
     lib.bc_decode_workspace_bytes.restype = sz
@@ -165,6 +168,10 @@ def bc_decode_step_budget(shape, cache, k, v, q, out, beacon_k, beacon_v, budget
                           stream):
     return load().bc_decode_step_budget(C.byref(shape), C.byref(cache), k, v, q, out, beacon_k, beacon_v,
                                         budget, live, ws, ws_bytes, stream)
+
+
+def bc_sort_by_length(shape, cache, active, order, stream):
+    return load().bc_sort_by_length(C.byref(shape), C.byref(cache), active, order, stream)
 
 
 def bc_set_ratio(shape, cache, new_c, active, stream):
@@ -273,7 +280,8 @@ class Runtime:
         self.cache = bc_cache(self.k_slab.data_ptr(), self.v_slab.data_ptr(), self.base.data_ptr(),
                               self.cap.data_ptr(), self.P.data_ptr(), self.c.data_ptr(),
                               self.nb.data_ptr(), self.w.data_ptr(), self.err.data_ptr(),
-                              self.max_cap)
+                              self.max_cap, None)
+        self.order = None
         self.ws_bytes = int(bc_decode_workspace_bytes(self.shape, self.max_cap))
         self.ws = torch.empty(max(self.ws_bytes, 16), dtype=torch.uint8, device=device)
         _check(bc_workspace_init(_ptr(self.ws), self.ws.numel(), _stream_ptr()))
@@ -376,6 +384,15 @@ class Runtime:
                                      _ptr(bk), _ptr(bv), _ptr(budget), _ptr(live), _ptr(self.ws),
                                      self.ws_bytes, _stream_ptr()))
         return out
+
+    def sort_by_length(self, active=None):
+        """Refresh the dispatch order (longest resident sequence first) and attach it to the cache:
+        large ragged batches then start their longest sequences first."""
+        if self.order is None:
+            self.order = self.torch.arange(self.B, dtype=self.torch.int32, device=self.device)
+            self.cache.order = self.order.data_ptr()
+        a = self.mask(active)
+        _check(bc_sort_by_length(self.shape, self.cache, _ptr(a), _ptr(self.order), _stream_ptr()))
 
     def set_ratio(self, new_c, active=None):
         nc = self.torch.from_numpy(np.asarray(new_c, dtype=np.int32)).to(self.device)

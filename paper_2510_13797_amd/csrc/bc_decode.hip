@@ -46,11 +46,10 @@ struct DecodeParams {
   const char* bk;
   const char* bv;
   int32_t* tickets;    // [B], zero between launches
-  struct OrderRec* order;   // [B] dispatch order of this launch (written by decode_order_kernel)
+  const int32_t* order;     // [B] dispatch order (workgroup i serves sequence order[i]) or null
   const int32_t* budget;   // [B] cap on nb + w (nullable), with
   uint8_t* live;           // [B] cleared when the cap is reached
   int32_t beacon_row;  // the fused row is the beacon closing a full window (bk = new_k, bv = new_v)
-  int32_t lpt;         // workgroups take the sequences in order of decreasing length (`order`)
   int32_t B;
   int32_t debug_stage; // experiments only: leave the kernel early (0 = run everything)
   int32_t Hq, Hkv, g;  // g = real group size
@@ -83,24 +82,25 @@ constexpr int kLptMaxLen = 1 << 19;
 constexpr int kLptMinPairs = 256;    // compute units of the chip: below this every workgroup starts at once
 
 // Longest sequence first: with more workgroups than the chip holds at once and ragged lengths,
-// the dispatch order decides the tail.  decode_order_kernel, launched in front of the main
-// kernel, ranks the B sequences by resident length (keys made unique by the index, so the ranks
-// are a permutation) and writes for every rank one record with the sequence and a snapshot of
-// its table entries.  Workgroup number i of the main kernel (in dispatch order) serves the
-// sequence of record i and takes the table values from the record: one read instead of the
-// seven table reads, and the values are the ones at the start of the launch even while a fused
-// step is already updating the tables of sequences that have finished.
-struct alignas(16) OrderRec {
-  int32_t s, act, P, nb;
-  int32_t w, cap, c, pad;
-  int64_t base, pad2;
+// the dispatch order decides the tail.  bc_sort_by_length ranks the B sequences by resident
+// length (keys made unique by the index, so the ranks are a permutation) into an array the
+// caller owns; with that array in bc_cache::order, workgroup number i of a decode launch (in
+// dispatch order) serves sequence order[i].  The array is only read by the decode launches, so
+// every workgroup sees the same permutation even while a fused step updates the tables, and it
+// may be as old as the caller likes.
+struct SortParams {
+  const uint8_t* active;
+  const int32_t *P, *nb, *w;
+  int32_t* order;
+  int32_t B;
 };
 
-__global__ __launch_bounds__(256) void decode_order_kernel(DecodeParams p) {
+__global__ __launch_bounds__(256) void sort_by_length_kernel(SortParams p) {
   __shared__ int s_key[kLptMaxB];
   for (int t = threadIdx.x; t < p.B; t += blockDim.x) {
     const int act = p.active ? p.active[t] : 1;
-    const int len = act ? p.P[t] + p.nb[t] + p.w[t] + 1 : 0;   // inactive sequences rank last
+    int len = act ? p.P[t] + p.nb[t] + p.w[t] + 1 : 0;         // inactive sequences rank last
+    len = min(max(len, 0), kLptMaxLen - 1);
     s_key[t] = (len << 12) | (kLptMaxB - 1 - t);
   }
   for (int t = p.B + threadIdx.x; t < ((p.B + 3) & ~3); t += blockDim.x) s_key[t] = -1;
@@ -113,32 +113,32 @@ __global__ __launch_bounds__(256) void decode_order_kernel(DecodeParams p) {
     const int4 o = *reinterpret_cast<const int4*>(s_key + u);
     rank += (o.x > mine) + (o.y > mine) + (o.z > mine) + (o.w > mine);
   }
-  OrderRec r;
-  r.s = t; r.act = p.active ? p.active[t] : 1; r.P = p.P[t]; r.nb = p.nb[t];
-  r.w = p.w[t]; r.cap = p.cap[t]; r.c = p.c ? p.c[t] : 0; r.pad = 0;
-  r.base = p.base[t]; r.pad2 = 0;
-  p.order[rank] = r;
+  p.order[rank] = t;
 }
 
 __device__ __forceinline__ PairInfo pair_info(const DecodeParams& p) {
   PairInfo pi;
   int act, w;
-  if (p.lpt) {
-    const int rank = blockIdx.y / p.Hkv;
-    const OrderRec& r = p.order[rank];
-    pi.s = r.s; pi.kvh = blockIdx.y - rank * p.Hkv;
-    act = r.act; pi.P = r.P; pi.nb = r.nb; w = r.w; pi.cap = r.cap; pi.c = r.c; pi.base = r.base;
-  } else {
-    const int pair = blockIdx.y;
-    pi.s = pair / p.Hkv;
-    pi.kvh = pair - pi.s * p.Hkv;
-    act = p.active ? p.active[pi.s] : 1;
-    pi.P = p.P[pi.s];
-    pi.nb = p.nb[pi.s];
-    w = p.w[pi.s];
-    pi.cap = p.cap[pi.s];
-    pi.base = p.base[pi.s];
-    pi.c = p.c ? p.c[pi.s] : 0;
+  int pair = blockIdx.y;
+  bool bad_order = false;
+  if (p.order) {
+    const int rank = pair / p.Hkv;
+    const int s = p.order[rank];
+    bad_order = (unsigned)s >= (unsigned)p.B;        // not written by bc_sort_by_length
+    pair = (bad_order ? 0 : s) * p.Hkv + (pair - rank * p.Hkv);
+  }
+  pi.s = pair / p.Hkv;
+  pi.kvh = pair - pi.s * p.Hkv;
+  act = p.active ? p.active[pi.s] : 1;
+  pi.P = p.P[pi.s];
+  pi.nb = p.nb[pi.s];
+  w = p.w[pi.s];
+  pi.cap = p.cap[pi.s];
+  pi.base = p.base[pi.s];
+  pi.c = p.c ? p.c[pi.s] : 0;
+  if (bad_order) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(p.err, BC_ERRBIT_STATE);
+    act = 0;
   }
   const bool herald = blockIdx.x == 0 && pi.kvh == 0 && threadIdx.x == 0;   // reports errors
   pi.live = false;
@@ -727,8 +727,8 @@ struct DecodePlan {
   int rows_per_pass;  // rows one pass of a workgroup covers
   int R;              // rows per workgroup
   int max_chunks;
-  size_t tickets_bytes, order_bytes, part_n_bytes, part_o_bytes, part_ml_bytes;
-  size_t total() const { return tickets_bytes + order_bytes + part_n_bytes + part_o_bytes + part_ml_bytes; }
+  size_t tickets_bytes, part_n_bytes, part_o_bytes, part_ml_bytes;
+  size_t total() const { return tickets_bytes + part_n_bytes + part_o_bytes + part_ml_bytes; }
 };
 
 static int padded_group(int g) { return g <= 1 ? 1 : g <= 2 ? 2 : g <= 4 ? 4 : g <= 6 ? 6 : 8; }
@@ -777,7 +777,6 @@ static DecodePlan make_plan(const bc_shape* sh, int max_cap, int rows_override, 
   if (rows_override == kPlanForSizing) pl.max_chunks = npairs < 128 ? 64 : 4;
   const size_t pairs = (size_t)sh->B * sh->Hkv;
   pl.tickets_bytes = align256((size_t)sh->B * 4);
-  pl.order_bytes = align256((size_t)sh->B * sizeof(OrderRec));
   pl.part_n_bytes = align256(pairs * 4);
   pl.part_o_bytes = align256(pairs * pl.max_chunks * pl.Gp * sh->d * 4);
   pl.part_ml_bytes = align256(pairs * pl.max_chunks * 2 * pl.Gp * 4);
@@ -839,8 +838,7 @@ static int32_t launch_attention(const bc_shape* shape, const bc_cache* cache, co
   p.active = active;
   char* ws = static_cast<char*>(workspace);
   p.tickets = reinterpret_cast<int32_t*>(ws);
-  p.order = reinterpret_cast<OrderRec*>(ws + pl.tickets_bytes);
-  char* parts = ws + pl.tickets_bytes + pl.order_bytes;
+  char* parts = ws + pl.tickets_bytes;
   p.part_n = pl.max_chunks > 1 ? reinterpret_cast<int32_t*>(parts) : nullptr;
   p.part_o = reinterpret_cast<float*>(parts + pl.part_n_bytes);
   p.part_ml = reinterpret_cast<float*>(parts + pl.part_n_bytes + pl.part_o_bytes);
@@ -850,11 +848,10 @@ static int32_t launch_attention(const bc_shape* shape, const bc_cache* cache, co
   p.budget = budget; p.live = live;
   p.beacon_row = beacon_row ? 1 : 0;
   p.B = shape->B;
-  // Batches that need more than one round of workgroups: longest sequence first (see
-  // decode_order_kernel).  The fused steps take part as well: the records are a snapshot.
-  p.lpt = (pl.max_chunks == 1 && shape->B <= kLptMaxB &&
-           shape->B * shape->Hkv > kLptMinPairs && cache->max_cap < kLptMaxLen && g_variant != 3)
-              ? 1 : 0;
+  // Batches that need more than one round of workgroups follow the caller's dispatch order
+  // (bc_sort_by_length), if there is one; with fewer workgroups everything starts at once.
+  p.order = (cache->order && pl.max_chunks == 1 && shape->B * shape->Hkv > kLptMinPairs && g_variant != 3)
+                ? cache->order : nullptr;
   p.Hq = shape->Hq; p.Hkv = shape->Hkv; p.g = shape->Hq / shape->Hkv;
   p.Gp = pl.Gp;
   p.D = shape->d;
@@ -865,7 +862,6 @@ static int32_t launch_attention(const bc_shape* shape, const bc_cache* cache, co
 
   const int pairs = shape->B * shape->Hkv;
   const dim3 grid(pl.max_chunks, pairs);
-  if (p.lpt) decode_order_kernel<<<(shape->B + 255) / 256, 256, 0, hs>>>(p);
   if (pl.lds) {
     const int32_t st = enable_big_lds();
     if (st != BC_OK) return st;
@@ -917,6 +913,21 @@ using namespace bc;
 extern "C" void bc_set_decode_tuning(int32_t rows_per_workgroup, int32_t variant) {
   g_rows_per_wg = rows_per_workgroup > 0 ? rows_per_workgroup : 0;
   g_variant = variant;
+}
+
+extern "C" int32_t bc_sort_by_length(const bc_shape* shape, const bc_cache* cache,
+                                     const uint8_t* active, int32_t* order, void* stream) {
+  int32_t st = check_shape(shape);
+  if (st != BC_OK) return st;
+  st = check_cache(cache);
+  if (st != BC_OK) return st;
+  if (!order) return BC_ERR_ARG;
+  if (shape->B > kLptMaxB) return BC_ERR_SHAPE;
+  SortParams p;
+  p.active = active; p.P = cache->P; p.nb = cache->nb; p.w = cache->w;
+  p.order = order; p.B = shape->B;
+  sort_by_length_kernel<<<(shape->B + 255) / 256, 256, 0, as_stream(stream)>>>(p);
+  return launch_status();
 }
 
 extern "C" size_t bc_decode_workspace_bytes(const bc_shape* shape, int32_t max_cap) {

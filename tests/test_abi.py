@@ -30,7 +30,37 @@ def test_struct_layouts_match_header():
     from paper_2510_13797_amd import bc
     assert C.sizeof(bc.bc_shape) == 24
     assert bc.bc_shape.scale.offset == 20
-    assert C.sizeof(bc.bc_cache) == 80 and bc.bc_cache.max_cap.offset == 72
+    assert C.sizeof(bc.bc_cache) == 88 and bc.bc_cache.max_cap.offset == 72
+    assert bc.bc_cache.order.offset == 80
+
+
+def test_header_is_plain_c_and_agrees_with_the_binding(tmp_path):
+    # compile a C program against include/bc.h with the host C compiler and compare the struct
+    # layouts it prints with the ctypes declarations
+    import ctypes as C
+    import shutil
+    import subprocess
+    from paper_2510_13797_amd import bc
+    cc = shutil.which("gcc") or shutil.which("cc")
+    if cc is None:
+        import pytest
+        pytest.skip("no host C compiler")
+    src = tmp_path / "layout.c"
+    src.write_text(
+        '#include <stdio.h>\n#include <stddef.h>\n#include "bc.h"\n'
+        'int main(void) {\n'
+        '  printf("%zu %zu %zu %zu %zu %zu %zu\\n", sizeof(bc_shape), offsetof(bc_shape, scale),\n'
+        '         sizeof(bc_cache), offsetof(bc_cache, base), offsetof(bc_cache, err),\n'
+        '         offsetof(bc_cache, max_cap), offsetof(bc_cache, order));\n'
+        '  return 0;\n}\n')
+    exe = tmp_path / "layout"
+    subprocess.check_call([cc, "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"),
+                           str(src), "-o", str(exe)])
+    got = [int(x) for x in subprocess.check_output([str(exe)]).split()]
+    want = [C.sizeof(bc.bc_shape), bc.bc_shape.scale.offset, C.sizeof(bc.bc_cache),
+            bc.bc_cache.base.offset, bc.bc_cache.err.offset, bc.bc_cache.max_cap.offset,
+            bc.bc_cache.order.offset]
+    assert got == want, (got, want)
 
 
 def test_product_does_not_import_the_oracle():

@@ -248,11 +248,12 @@ def test_very_long_context_next_to_a_short_one(dev):
 @pytest.mark.parametrize("B,Hq,Hkv,dtype,d", [(160, 12, 2, "bf16", 128), (300, 4, 1, "bf16", 128),
                                              (272, 2, 1, "f32", 64), (280, 8, 1, "bf16", 64)])
 def test_longest_first_dispatch_large_ragged_batch(dev, B, Hq, Hkv, dtype, d):
-    # more (sequence, KV head) pairs than compute units: a sort kernel in front of the main one
-    # ranks the sequences by resident length and workgroup i serves the i-th longest, in
+    # more (sequence, KV head) pairs than compute units: bc_sort_by_length ranks the sequences by
+    # resident length into the cache's dispatch order and workgroup i serves the i-th longest, in
     # bc_decode_attn and in the fused steps (B = 300: the ranking itself spans two workgroups).
-    # Against the oracle with and without an inactive stripe, and bit-equality with the plain
-    # dispatch order (tuning variant 3).
+    # The order is refreshed every fourth step only (a stale permutation is as good as a fresh
+    # one).  Against the oracle with and without an inactive stripe, bit-equality with the plain
+    # dispatch order (tuning variant 3), and a corrupt entry in the order.
     bc = _bc()
     rng = np.random.default_rng(23)
     P = rng.integers(1, 700, size=B).astype(np.int32)
@@ -267,6 +268,8 @@ def test_longest_first_dispatch_large_ragged_batch(dev, B, Hq, Hkv, dtype, d):
         q = wl.step_q(t)
         bk, bv = wl.beacon_kv(t)
         act = active if t % 3 == 0 else None
+        if t % 4 == 1:
+            rt.sort_by_length(active=act)
         o = rt.decode_step(k, v, q, bk, bv, active=act).cpu().numpy()
         oc.append(k, v, active=act)
         seqs = [s for s in range(B) if act is None or act[s]]
@@ -290,6 +293,21 @@ def test_longest_first_dispatch_large_ragged_batch(dev, B, Hq, Hkv, dtype, d):
         check_attention(a, q, oc, wl, seqs, 99)
         if act is not None:
             assert np.all(a[5::7] == -3.0)
+    # the order really is the lengths sorted, longest first, inactive sequences last
+    rt.sort_by_length(active=active)
+    order = rt.order.cpu().numpy()
+    assert sorted(order.tolist()) == list(range(B))
+    L = np.array([wl.P[s] + oc.nb[s] + oc.w[s] for s in range(B)])
+    key = np.where(active > 0, L + 1, 0)
+    assert all(key[order[i]] >= key[order[i + 1]] for i in range(B - 1))
+    # an entry that is no sequence index: state bit, its workgroups do nothing, the rest is served
+    lost = int(order[3])
+    rt.order[3] = B + 1000
+    rt.out.fill_(-3.0)
+    a = rt.decode_attn(q).cpu().numpy().copy()
+    assert np.all(a[lost] == -3.0)
+    check_attention(a, q, oc, wl, [s for s in range(B) if s != lost], 99)
+    assert rt.tables()[2] & ERR_STATE
 
 
 def test_fused_step_ragged_ratios_and_errors(dev):
@@ -463,7 +481,7 @@ def test_budget_rule_interrupts_generation_on_device(dev, dtype, d):
     budget_rollout(wl, rt, oc, budget, 120, None, dev)
 
 
-def budget_rollout(wl, rt, oc, budget, steps, attention_steps, dev):
+def budget_rollout(wl, rt, oc, budget, steps, attention_steps, dev, sort_every=0):
     """Steps under the evaluation cap: outputs, live flags, tables and the step at which every
     sequence ends against the oracle; attention_steps = None checks every step."""
     import torch
@@ -477,6 +495,8 @@ def budget_rollout(wl, rt, oc, budget, steps, attention_steps, dev):
         q = wl.step_q(t)
         bk, bv = wl.beacon_kv(t)
         rt.out.fill_(77.0)
+        if sort_every and t % sort_every == 1:
+            rt.sort_by_length(active=live_d)
         o = rt.decode_step_budget(k, v, q, bk, bv, bud_d, live_d).cpu().numpy()
         was = list(live)
         oc.append(k, v, active=was)
@@ -500,8 +520,8 @@ def budget_rollout(wl, rt, oc, budget, steps, attention_steps, dev):
 
 
 def test_budget_rule_large_batch_longest_first(dev):
-    # more pairs than compute units: the budget step runs behind the sort kernel, whose records
-    # are a snapshot of tables and live flags taken before any workgroup updates them
+    # more pairs than compute units: the budget step follows a dispatch order that is refreshed
+    # every fifth step from the live flags and lengths of that moment
     B = 300
     rng = np.random.default_rng(31)
     P = rng.integers(1, 400, size=B).astype(np.int32)
@@ -509,7 +529,7 @@ def test_budget_rule_large_batch_longest_first(dev):
     wl = W.Workload("budget_lpt", 93, B, 4, 1, 128, "bf16", P, np.full(B, 60, np.int32), c)
     rt, oc = make(wl, dev)
     budget = rng.integers(4, 30, size=B).astype(np.int32)
-    budget_rollout(wl, rt, oc, budget, 36, (1, 2, 5, 17, 36), dev)
+    budget_rollout(wl, rt, oc, budget, 36, (1, 2, 5, 17, 36), dev, sort_every=5)
 
 
 @pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64), ("bf16", 64)])
