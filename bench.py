@@ -367,9 +367,56 @@ def bench_copy(args):
                       "copies": reps}))
 
 
+def bench_readfloor(args):
+    """What a read-only kernel of the decode step's size costs: bc_diag_stream_read over 33.5 MB
+    (the K/V bytes of one step at L = 512) from 16 rotating buffers, with the decode grid's 128
+    workgroups and with larger grids, as back-to-back launches replayed from a HIP graph."""
+    import torch
+    from paper_2510_13797_amd import bc
+    bc.load()
+    dev = torch.device("cuda:0")
+    nbytes = 64 * 512 * 2 * 128 * 2 * 2                 # B x L x Hkv x d x 2 bytes x (K and V)
+    bufs = [torch.empty(nbytes, dtype=torch.uint8, device=dev).fill_(i + 1) for i in range(16)]
+    sink = torch.zeros(4096, dtype=torch.int32, device=dev)
+    st = torch.cuda.Stream()
+    n_launch, reps = 256, 8
+
+    def timed(nb, wgs):
+        with torch.cuda.stream(st):
+            sp = st.cuda_stream
+
+            def run():
+                for i in range(n_launch):
+                    rc = bc.bc_diag_stream_read(bufs[i % 16].data_ptr() if nb else None, nb, wgs,
+                                                sink.data_ptr(), sp)
+                    assert rc == 0, rc
+            run()
+            st.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=st):
+                run()
+            g.replay()
+            st.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(st)
+            for _ in range(reps):
+                g.replay()
+            e1.record(st)
+            st.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / (reps * n_launch)
+
+    empty_us = timed(0, 128)
+    res = []
+    for wgs in (128, 256, 512, 1024, 2048):
+        us = timed(nbytes, wgs)
+        res.append({"workgroups": wgs, "us_per_launch": round(us, 3), "GBps": round(nbytes / us / 1e3, 1)})
+    print(json.dumps({"workload": "readfloor", "bytes_per_launch": nbytes, "launches_per_graph": n_launch,
+                      "empty_kernel_us": round(empty_us, 3), "results": res}))
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--workload", default="decode", choices=["decode", "prefill", "prefill_bwd", "distill", "copy"])
+    ap.add_argument("--workload", default="decode", choices=["decode", "prefill", "prefill_bwd", "distill", "copy", "readfloor"])
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=-1)
     ap.add_argument("--warmup", type=int, default=-1)
@@ -402,6 +449,8 @@ def main():
         return bench_distill(args)
     if args.workload == "copy":
         return bench_copy(args)
+    if args.workload == "readfloor":
+        return bench_readfloor(args)
     if args.rows_per_wg:
         bc.bc_set_decode_tuning(args.rows_per_wg, 0)
 

@@ -278,6 +278,13 @@ int32_t bc_tables_to_host(const bc_shape *shape, const bc_cache *cache, int32_t 
 int32_t bc_sort_by_length(const bc_shape *shape, const bc_cache *cache, const uint8_t *active,
                           int32_t *order, void *stream);
 
+/* Measurement aid (no operation of the paper): `workgroups` workgroups of 512 threads read
+ * `bytes` bytes (a multiple of 16, 16-byte aligned, device) from `src` with coalesced streaming
+ * loads and write one word each to sink[workgroups] (device, may be NULL).  With bytes == 0 it is
+ * an empty kernel.  bench.py --workload readfloor times it at the decode step's size and grid. */
+int32_t bc_diag_stream_read(const void *src, size_t bytes, int32_t workgroups, uint32_t *sink,
+                            void *stream);
+
 /* Tuning override for experiments: rows of one (sequence, KV head) stream handled by one
  * workgroup of bc_decode_attn (0 = automatic), and kernel variant: 0 = automatic, 1 = always the
  * plain-ALU kernel, 2 = the LDS/MFMA kernel or BC_ERR_SHAPE, 3 = automatic but ignoring

@@ -28,7 +28,7 @@ EXPORTS = [
     "bc_status_str", "bc_version", "bc_cache_init", "bc_cache_admit", "bc_append_kv",
     "bc_decode_workspace_bytes", "bc_workspace_init", "bc_decode_attn",
     "bc_compress_evict", "bc_decode_step", "bc_beacon_step", "bc_decode_step_budget", "bc_set_ratio",
-    "bc_sort_by_length",
+    "bc_sort_by_length", "bc_diag_stream_read",
     "bc_prefill_attn", "bc_prefill_bwd_workspace_bytes", "bc_prefill_attn_bwd",
     "bc_topk_kl_loss", "bc_topk_kl_loss_bwd", "bc_tables_to_host", "bc_set_decode_tuning",
 ]
@@ -73,6 +73,8 @@ def load():
     lib.bc_cache_init.argtypes = [sp, cp, vp, vp, vp, i64, vp]
     lib.bc_cache_admit.restype = i32
     lib.bc_cache_admit.argtypes = [sp, cp, vp, vp, vp, i64, vp, vp, vp, vp]
+    lib.bc_diag_stream_read.restype = i32
+    lib.bc_diag_stream_read.argtypes = [vp, sz, i32, vp, vp]
     lib.bc_sort_by_length.restype = i32
     lib.bc_sort_by_length.argtypes = [sp, cp, vp, vp, vp]
     lib.bc_append_kv.restype = i32
@@ -168,6 +170,10 @@ def bc_decode_step_budget(shape, cache, k, v, q, out, beacon_k, beacon_v, budget
                           stream):
     return load().bc_decode_step_budget(C.byref(shape), C.byref(cache), k, v, q, out, beacon_k, beacon_v,
                                         budget, live, ws, ws_bytes, stream)
+
+
+def bc_diag_stream_read(src, nbytes, workgroups, sink, stream):
+    return load().bc_diag_stream_read(src, nbytes, workgroups, sink, stream)
 
 
 def bc_sort_by_length(shape, cache, active, order, stream):
