@@ -116,10 +116,10 @@ __global__ __launch_bounds__(256) void sort_by_length_kernel(SortParams p) {
   p.order[rank] = t;
 }
 
-__device__ __forceinline__ PairInfo pair_info(const DecodeParams& p) {
+__device__ __forceinline__ PairInfo pair_info(const DecodeParams& p, int pair_index) {
   PairInfo pi;
   int act, w;
-  int pair = blockIdx.y;
+  int pair = pair_index;
   bool bad_order = false;
   if (p.order) {
     const int rank = pair / p.Hkv;
@@ -205,15 +205,16 @@ __device__ __forceinline__ PairInfo pair_info(const DecodeParams& p) {
 
 // Epilogue shared by both kernels: s_m/s_l/s_acc hold one (m, l, o) per wave in LDS;
 // merge them in wave order and write the result or the chunk partial.
-template <int NW, int D>
+template <int NW, int D, int DOUT = D>
 __device__ __forceinline__ void merge_waves_and_store(const DecodeParams& p, const PairInfo& pi,
                                                       const float* s_m, const float* s_l,
-                                                      const float* s_acc, int gstride) {
+                                                      const float* s_acc, int gstride, int col0 = 0) {
+  // D: columns this workgroup holds (all DOUT of a head, or one half starting at col0)
   const int nout = p.g * D;
   const int pair = pi.s * p.Hkv + pi.kvh;
   float* po = p.part_o + ((int64_t)pair * p.max_chunks + pi.chunk) * (p.Gp * D);
   float* pml = p.part_ml + ((int64_t)pair * p.max_chunks + pi.chunk) * (2 * p.Gp);
-  float* outp = p.out + (int64_t)(pi.s * p.Hq + pi.kvh * p.g) * D;
+  float* outp = p.out + (int64_t)(pi.s * p.Hq + pi.kvh * p.g) * DOUT + col0;
   for (int i = threadIdx.x; i < nout; i += blockDim.x) {
     const int h = i / D, x = i - h * D;
     float mx = s_m[h];
@@ -227,7 +228,7 @@ __device__ __forceinline__ void merge_waves_and_store(const DecodeParams& p, con
       o += s_acc[(wv * gstride + h) * D + x] * a;
     }
     if (pi.nchunks == 1) {
-      __builtin_nontemporal_store(o / lsum, outp + i);   // streamed out: nothing left dirty in L2
+      __builtin_nontemporal_store(o / lsum, outp + (D == DOUT ? i : h * DOUT + x));   // streamed out: nothing left dirty in L2
     } else {
       __builtin_nontemporal_store(o, po + i);
       if (x == 0) {
@@ -288,18 +289,32 @@ template <> __device__ __forceinline__ int tile_swz<64>(int row) {
 // PROBES: honour the early exits of the timing probes (tuning variants 11..15).
 // STREAM: load K/V with the non-temporal policy (large launches; small ones are latency-bound
 // and about a microsecond faster with the default policy).
-template <bool PROBES, bool STREAM, int D>
+// VS: workgroups per (sequence, KV head) pair.  With VS = 2 (batches of at most 128 pairs, which
+// would leave half of the compute units idle) two workgroups serve a pair: both read all K rows
+// and compute the same scores and weights, each reads one half of every V row and produces that
+// half of the output columns - no partial results to merge.  The partner's workgroup index is
+// larger by the number of pairs, which is the same XCD (same L2) when that number is a
+// multiple of 8: the K rows then come from HBM once.
+template <bool PROBES, bool STREAM, int D, int VS>
 __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams p) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
+  constexpr int DV = D / VS;               // V (and output) columns of this workgroup
+  constexpr int VROWB = DV * 2;            // bytes of its part of a V row, = row pitch of the V tile in LDS
+  constexpr int VUPR = VROWB / 16;
+  constexpr int VRPI = 1024 / VROWB;
+  constexpr int VNDMA = kTileRows / VRPI;
+  constexpr int VTILEB = kTileRows * VROWB;
   constexpr int ROWB = D * 2;              // bytes of one row of one KV head: 256 or 128
   constexpr int UPR = ROWB / 16;           // 16-byte units per row: 16 or 8
   constexpr int RPI = 1024 / ROWB;         // rows one 1 KB LDS-DMA instruction brings: 4 or 8
   constexpr int NDMA = kTileRows / RPI;    // such instructions per K (or V) tile: 8 or 4
   constexpr int NI = D / 32;               // MFMAs (k = 32) along the head dimension: 4 or 2
-  constexpr int NJ = D / 16;               // 16-column blocks of the output: 8 or 4
+  constexpr int NJ = DV / 16;              // 16-column blocks of the output held here: 8 or 4
   constexpr int TILEB = kTileRows * ROWB;  // one K (or V) tile: 8 or 4 KB
   if (PROBES && p.debug_stage == 1) return;
-  const PairInfo pi = pair_info(p);
+  const int npairs = p.B * p.Hkv;
+  const int vhalf = VS == 1 ? 0 : (int)blockIdx.y / npairs;
+  const PairInfo pi = pair_info(p, VS == 1 ? (int)blockIdx.y : (int)blockIdx.y - vhalf * npairs);
   if (!pi.live) return;
   if (PROBES && p.debug_stage == 2) { if (pi.L == 12345678) p.out[0] = 1.f; return; }
 
@@ -307,8 +322,8 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
   const int n = lane & 15, kb = lane >> 4;       // MFMA column / k-block of this lane
   const int64_t stream_off = (pi.base * p.Hkv + (int64_t)pi.kvh * pi.cap) * ROWB;
   const char* kbase = p.k_slab + stream_off;
-  const char* vbase = p.v_slab + stream_off;
-  char* wk = lds + wave * (2 * TILEB);
+  const char* vbase = p.v_slab + stream_off + vhalf * VROWB;
+  char* wk = lds + wave * (TILEB + VTILEB);
   char* wv = wk + TILEB;
 
   // B operand of the score product: Q^T, column n = query head, k = head-dim index.
@@ -322,11 +337,17 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
     qb[i] = __builtin_bit_cast(bf16x8_t, r);
   }
 
-  // fused append: lanes 0..UPR-1 carry the new K row, the next UPR lanes the new V row (16 bytes each)
+  // fused append: lanes 0..UPR-1 carry the new K row, the next VUPR lanes this workgroup's part
+  // of the new V row (16 bytes each)
   uint4 newrow = make_uint4(0u, 0u, 0u, 0u);
-  if (pi.new_row >= 0 && lane < 2 * UPR) {
-    const char* src = (lane < UPR ? p.new_k : p.new_v) +
-                      (int64_t)(pi.s * p.Hkv + pi.kvh) * ROWB + ((lane & (UPR - 1)) << 4);
+  if (pi.new_row >= 0 && lane < UPR + VUPR) {
+    const char* src;
+    if constexpr (VS == 1)
+      src = (lane < UPR ? p.new_k : p.new_v) + (int64_t)(pi.s * p.Hkv + pi.kvh) * ROWB + ((lane & (UPR - 1)) << 4);
+    else
+      src = lane < UPR
+          ? p.new_k + (int64_t)(pi.s * p.Hkv + pi.kvh) * ROWB + (lane << 4)
+          : p.new_v + (int64_t)(pi.s * p.Hkv + pi.kvh) * ROWB + vhalf * VROWB + ((lane - UPR) << 4);
     newrow = *reinterpret_cast<const uint4*>(src);
   }
   // rows the tile loads may touch: the resident rows that are already in the slab
@@ -343,15 +364,21 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
   // into the freed registers, compute - one tile always in flight behind the one in use.
   const int ntiles = (pi.row_end - pi.row0 + kTileRows - 1) / kTileRows;
   const int r4 = lane / UPR, pos = lane & (UPR - 1);   // row within a 1 KB load, unit within the row
-  uint4 kreg[NDMA], vreg[NDMA];
+  const int r4v = lane / VUPR, posv = lane & (VUPR - 1);   // the same for this workgroup's part of V
+  uint4 kreg[NDMA], vreg[VNDMA];
 #pragma unroll
-  for (int j = 0; j < NDMA; ++j) kreg[j] = vreg[j] = make_uint4(0u, 0u, 0u, 0u);
+  for (int j = 0; j < NDMA; ++j) kreg[j] = make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+  for (int j = 0; j < VNDMA; ++j) vreg[j] = make_uint4(0u, 0u, 0u, 0u);
 #define BC_LOAD_TILE_REGS(TROW0)                                              \
   _Pragma("unroll") for (int j = 0; j < NDMA; ++j) {                          \
     const int grow_ = min((TROW0) + RPI * j + r4, last_slab_row);             \
     const int64_t goff_ = (int64_t)grow_ * ROWB + (pos << 4);                 \
     kreg[j] = load16<STREAM>(kbase + goff_);                                  \
-    vreg[j] = load16<STREAM>(vbase + goff_);                                  \
+    if (j < VNDMA) {                                                          \
+      const int vrow_ = min((TROW0) + VRPI * j + r4v, last_slab_row);         \
+      vreg[j] = load16<STREAM>(vbase + (VS == 1 ? goff_ : (int64_t)vrow_ * ROWB + (posv << 4)));  \
+    }                                                                         \
   }
   if (wave < ntiles) {
     // ---- HBM -> LDS: NDMA + NDMA instructions, each RPI whole rows (1 KB), 16-byte units XOR-swizzled
@@ -363,8 +390,13 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
       const int64_t goff = (int64_t)grow * ROWB + ((pos ^ tile_swz<D>(row)) << 4);
       __builtin_amdgcn_global_load_lds((global_void_t*)(kbase + goff),
                                        (lds_void_t*)(wk + j * 1024), 16, 0, STREAM ? kStreamPolicy : 0);
-      __builtin_amdgcn_global_load_lds((global_void_t*)(vbase + goff),
-                                       (lds_void_t*)(wv + j * 1024), 16, 0, STREAM ? kStreamPolicy : 0);
+      if (j < VNDMA) {
+        const int vrow = VRPI * j + r4v;
+        const int vgrow = min(trow0 + vrow, last_slab_row);
+        const int64_t vgoff = VS == 1 ? goff : (int64_t)vgrow * ROWB + ((posv ^ tile_swz<DV>(vrow)) << 4);
+        __builtin_amdgcn_global_load_lds((global_void_t*)(vbase + vgoff),
+                                         (lds_void_t*)(wv + j * 1024), 16, 0, STREAM ? kStreamPolicy : 0);
+      }
     }
     if (wave + kLdsWaves < ntiles) { BC_LOAD_TILE_REGS(trow0 + kLdsWaves * kTileRows) }
   }
@@ -373,7 +405,8 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
     if (tile == wave) {
       // the LDS-DMA loads have landed once at most the register loads behind them are pending
       if (wave + kLdsWaves >= ntiles) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      else if (D == 128) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+      else if (NDMA + VNDMA == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+      else if (NDMA + VNDMA == 12) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
       else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
     } else {
 #pragma unroll
@@ -381,7 +414,10 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
         const int row = RPI * j + r4;
         const int o = row * ROWB + ((pos ^ tile_swz<D>(row)) << 4);
         *reinterpret_cast<uint4*>(wk + o) = kreg[j];
-        *reinterpret_cast<uint4*>(wv + o) = vreg[j];
+        if (j < VNDMA) {
+          const int vrow = VRPI * j + r4v;
+          *reinterpret_cast<uint4*>(wv + (VS == 1 ? o : vrow * VROWB + ((posv ^ tile_swz<DV>(vrow)) << 4))) = vreg[j];
+        }
       }
       if (tile + kLdsWaves < ntiles) { BC_LOAD_TILE_REGS(trow0 + kLdsWaves * kTileRows) }
     }
@@ -391,17 +427,30 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
       // the appended row is not in the slab yet: place it in the tile, store it for later
       // steps (unless this step's eviction drops it at once), clear the V rows behind it
       const int ra = pi.new_row - trow0;
-      if (lane < 2 * UPR) {
-        char* tile = lane < UPR ? wk : wv;
-        const int u = lane & (UPR - 1);
-        *reinterpret_cast<uint4*>(tile + ra * ROWB + ((u ^ tile_swz<D>(ra)) << 4)) = newrow;
-        if (pi.store_new_row) {
-          char* slab = const_cast<char*>(lane < UPR ? kbase : vbase);
-          *reinterpret_cast<uint4*>(slab + (int64_t)pi.new_row * ROWB + (u << 4)) = newrow;
+      if constexpr (VS == 1) {
+        if (lane < 2 * UPR) {
+          char* tile = lane < UPR ? wk : wv;
+          const int u = lane & (UPR - 1);
+          *reinterpret_cast<uint4*>(tile + ra * ROWB + ((u ^ tile_swz<D>(ra)) << 4)) = newrow;
+          if (pi.store_new_row) {
+            char* slab = const_cast<char*>(lane < UPR ? kbase : vbase);
+            *reinterpret_cast<uint4*>(slab + (int64_t)pi.new_row * ROWB + (u << 4)) = newrow;
+          }
+        }
+      } else {
+        if (lane < UPR) {
+          *reinterpret_cast<uint4*>(wk + ra * ROWB + ((lane ^ tile_swz<D>(ra)) << 4)) = newrow;
+          if (pi.store_new_row && vhalf == 0)
+            *reinterpret_cast<uint4*>(const_cast<char*>(kbase) + (int64_t)pi.new_row * ROWB + (lane << 4)) = newrow;
+        } else if (lane < UPR + VUPR) {
+          const int u = lane - UPR;
+          *reinterpret_cast<uint4*>(wv + ra * VROWB + ((u ^ tile_swz<DV>(ra)) << 4)) = newrow;
+          if (pi.store_new_row)
+            *reinterpret_cast<uint4*>(const_cast<char*>(vbase) + (int64_t)pi.new_row * ROWB + (u << 4)) = newrow;
         }
       }
-      for (int rr = ra + 1 + r4; rr < kTileRows; rr += RPI)
-        *reinterpret_cast<uint4*>(wv + rr * ROWB + (pos << 4)) = make_uint4(0u, 0u, 0u, 0u);
+      for (int rr = ra + 1 + r4v; rr < kTileRows; rr += VRPI)
+        *reinterpret_cast<uint4*>(wv + rr * VROWB + (posv << 4)) = make_uint4(0u, 0u, 0u, 0u);
     }
 
     // ---- scores, transposed: S^T[key][head] = K . Q^T.  Row m of sub-tile t is key
@@ -462,9 +511,9 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
         const int sub = (r & 1) << 3;
         const int rowa = key0, rowb = key0 + 4;
         const s16x4_t a0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (lds_s16x4_t*)(wv + rowa * ROWB + ((u ^ tile_swz<D>(rowa)) << 4) + sub));
+            (lds_s16x4_t*)(wv + rowa * VROWB + ((u ^ tile_swz<DV>(rowa)) << 4) + sub));
         const s16x4_t a1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (lds_s16x4_t*)(wv + rowb * ROWB + ((u ^ tile_swz<D>(rowb)) << 4) + sub));
+            (lds_s16x4_t*)(wv + rowb * VROWB + ((u ^ tile_swz<DV>(rowb)) << 4) + sub));
         typedef __attribute__((ext_vector_type(8))) short s16x8_t;
         const s16x8_t a = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
         const bf16x8_t av = __builtin_bit_cast(bf16x8_t, a);
@@ -490,24 +539,24 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
     asm volatile("global_atomic_add %0, %1, %2, off sc0"
                  : "=v"(ticket) : "v"(p.tickets + pi.s), "v"(one) : "memory");
   }
-  float* s_acc = reinterpret_cast<float*>(lds);                    // [wave][8][D]
-  float* s_m = s_acc + kLdsWaves * 8 * D;                          // [wave][8]
+  float* s_acc = reinterpret_cast<float*>(lds);                    // [wave][8][DV]
+  float* s_m = s_acc + kLdsWaves * 8 * DV;                         // [wave][8]
   float* s_l = s_m + kLdsWaves * 8;
   int* s_last = reinterpret_cast<int*>(s_l + kLdsWaves * 8);
   if (n < p.g) {
 #pragma unroll
     for (int j = 0; j < NJ; ++j)
-      *reinterpret_cast<f32x4_t*>(s_acc + (wave * 8 + n) * D + 16 * j + 4 * kb) = O[j];
+      *reinterpret_cast<f32x4_t*>(s_acc + (wave * 8 + n) * DV + 16 * j + 4 * kb) = O[j];
     if (kb == 0) { s_m[wave * 8 + n] = m_run; s_l[wave * 8 + n] = l_run; }
   }
   __syncthreads();
-  merge_waves_and_store<kLdsWaves, D>(p, pi, s_m, s_l, s_acc, 8);
+  merge_waves_and_store<kLdsWaves, DV, D>(p, pi, s_m, s_l, s_acc, 8, vhalf * DV);
 
   // ---- the last workgroup of the sequence writes the beacon row and updates the tables
   if (!pi.update || (PROBES && p.debug_stage == 5)) return;
   if (tid == 0) {
     asm volatile("s_waitcnt vmcnt(0)" : "+v"(ticket) : : "memory");   // the ticket has arrived
-    *s_last = (ticket == p.Hkv * pi.nchunks - 1) ? 1 : 0;
+    *s_last = (ticket == p.Hkv * pi.nchunks * VS - 1) ? 1 : 0;
   }
   __syncthreads();
   if (!*s_last) return;
@@ -545,7 +594,7 @@ __global__ __launch_bounds__(256) void decode_valu_kernel(DecodeParams p) {
   constexpr int RB = D * ES;            // row bytes
   constexpr int ROWS_PER_PASS = kValuWaves * RPI * U;
 
-  const PairInfo pi = pair_info(p);
+  const PairInfo pi = pair_info(p, blockIdx.y);
   if (!pi.live) return;
   const int L = pi.L, row_end = pi.row_end;
 
@@ -800,12 +849,14 @@ static int32_t enable_big_lds() {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return BC_ERR_HIP;
   if (done[dev]) return BC_OK;
-  const void* kernels[6] = {reinterpret_cast<const void*>(decode_lds_kernel<false, false, 128>),
-                            reinterpret_cast<const void*>(decode_lds_kernel<false, true, 128>),
-                            reinterpret_cast<const void*>(decode_lds_kernel<true, false, 128>),
-                            reinterpret_cast<const void*>(decode_lds_kernel<true, true, 128>),
-                            reinterpret_cast<const void*>(decode_lds_kernel<false, false, 64>),
-                            reinterpret_cast<const void*>(decode_lds_kernel<false, true, 64>)};
+  const void* kernels[8] = {reinterpret_cast<const void*>(decode_lds_kernel<false, false, 128, 1>),
+                            reinterpret_cast<const void*>(decode_lds_kernel<false, true, 128, 1>),
+                            reinterpret_cast<const void*>(decode_lds_kernel<true, false, 128, 1>),
+                            reinterpret_cast<const void*>(decode_lds_kernel<true, true, 128, 1>),
+                            reinterpret_cast<const void*>(decode_lds_kernel<false, false, 64, 1>),
+                            reinterpret_cast<const void*>(decode_lds_kernel<false, true, 64, 1>),
+                            reinterpret_cast<const void*>(decode_lds_kernel<false, false, 128, 2>),
+                            reinterpret_cast<const void*>(decode_lds_kernel<false, true, 128, 2>)};
   bool ok = true;
   for (const void* kfn : kernels)
     ok = ok && hipFuncSetAttribute(kfn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) ==
@@ -867,13 +918,23 @@ static int32_t launch_attention(const bc_shape* shape, const bc_cache* cache, co
     if (st != BC_OK) return st;
     // launches that cannot saturate the memory system are latency-bound: default cache policy
     const bool stream = (long)pairs * pl.max_chunks >= kStreamMinWorkgroups && g_variant != 4;
-    if (shape->d == 128) {
+    // two workgroups per pair (each one half of the V columns) while that still fits the chip
+    // (and while the K rows of the whole batch, which both workgroups of a pair read, stay in the
+    // caches between the two reads: measured faster up to about 64 MB of K, slower beyond)
+    const bool vsplit = shape->d == 128 && pl.max_chunks == 1 && 2 * pairs <= kLptMinPairs &&
+                        (int64_t)pairs * cache->max_cap * 256 <= (64LL << 20) &&
+                        !p.debug_stage && g_variant != 5;
+    if (vsplit) {
+      const bool stream2 = 2L * pairs >= kStreamMinWorkgroups && g_variant != 4;
+      auto kfn = stream2 ? decode_lds_kernel<false, true, 128, 2> : decode_lds_kernel<false, false, 128, 2>;
+      kfn<<<dim3(1, 2 * pairs), kLdsWaves * 64, kLdsBytes * 3 / 4, hs>>>(p);
+    } else if (shape->d == 128) {
       auto kfn = p.debug_stage
-                     ? (stream ? decode_lds_kernel<true, true, 128> : decode_lds_kernel<true, false, 128>)
-                     : (stream ? decode_lds_kernel<false, true, 128> : decode_lds_kernel<false, false, 128>);
+                     ? (stream ? decode_lds_kernel<true, true, 128, 1> : decode_lds_kernel<true, false, 128, 1>)
+                     : (stream ? decode_lds_kernel<false, true, 128, 1> : decode_lds_kernel<false, false, 128, 1>);
       kfn<<<grid, kLdsWaves * 64, kLdsBytes, hs>>>(p);
     } else {
-      auto kfn = stream ? decode_lds_kernel<false, true, 64> : decode_lds_kernel<false, false, 64>;
+      auto kfn = stream ? decode_lds_kernel<false, true, 64, 1> : decode_lds_kernel<false, false, 64, 1>;
       kfn<<<grid, kLdsWaves * 64, kLdsBytes / 2, hs>>>(p);
     }
   } else if (shape->kv_dtype == BC_BF16) {
