@@ -289,7 +289,8 @@ int32_t bc_diag_stream_read(const void *src, size_t bytes, int32_t workgroups, u
  * workgroup of bc_decode_attn (0 = automatic), and kernel variant: 0 = automatic, 1 = always the
  * plain-ALU kernel, 2 = the LDS/MFMA kernel or BC_ERR_SHAPE, 3 = automatic but ignoring
  * cache->order, 4 = automatic but with the default
- * cache policy for the K/V loads of large launches; 11..15 = timing probes that leave
+ * cache policy for the K/V loads of large launches, 5 = automatic but always one workgroup per
+ * (sequence, KV head) pair; 11..15 = timing probes that leave
  * the LDS/MFMA kernel after a given stage (outputs are then meaningless). */
 void bc_set_decode_tuning(int32_t rows_per_workgroup, int32_t variant);
 
