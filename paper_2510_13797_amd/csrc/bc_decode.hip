@@ -312,9 +312,12 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
   constexpr int NJ = DV / 16;              // 16-column blocks of the output held here: 8 or 4
   constexpr int TILEB = kTileRows * ROWB;  // one K (or V) tile: 8 or 4 KB
   if (PROBES && p.debug_stage == 1) return;
-  const int npairs = p.B * p.Hkv;
-  const int vhalf = VS == 1 ? 0 : (int)blockIdx.y / npairs;
-  const PairInfo pi = pair_info(p, VS == 1 ? (int)blockIdx.y : (int)blockIdx.y - vhalf * npairs);
+  // VS = 2: the grid holds the pairs twice, padded to a multiple of 8 so that a pair's two
+  // workgroups are 8k apart in dispatch order (workgroups go to the XCDs in turn)
+  const int npairs = p.B * p.Hkv, stride = (npairs + 7) & ~7;
+  const int vhalf = VS == 1 ? 0 : (int)blockIdx.y / stride;
+  if (VS != 1 && (int)blockIdx.y - vhalf * stride >= npairs) return;
+  const PairInfo pi = pair_info(p, VS == 1 ? (int)blockIdx.y : (int)blockIdx.y - vhalf * stride);
   if (!pi.live) return;
   if (PROBES && p.debug_stage == 2) { if (pi.L == 12345678) p.out[0] = 1.f; return; }
 
@@ -921,13 +924,14 @@ static int32_t launch_attention(const bc_shape* shape, const bc_cache* cache, co
     // two workgroups per pair (each one half of the V columns) while that still fits the chip
     // (and while the K rows of the whole batch, which both workgroups of a pair read, stay in the
     // caches between the two reads: measured faster up to about 64 MB of K, slower beyond)
-    const bool vsplit = shape->d == 128 && pl.max_chunks == 1 && 2 * pairs <= kLptMinPairs &&
+    const int pairs8 = (pairs + 7) & ~7;
+    const bool vsplit = shape->d == 128 && pl.max_chunks == 1 && 2 * pairs8 <= kLptMinPairs &&
                         (int64_t)pairs * cache->max_cap * 256 <= (64LL << 20) &&
                         !p.debug_stage && g_variant != 5;
     if (vsplit) {
       const bool stream2 = 2L * pairs >= kStreamMinWorkgroups && g_variant != 4;
       auto kfn = stream2 ? decode_lds_kernel<false, true, 128, 2> : decode_lds_kernel<false, false, 128, 2>;
-      kfn<<<dim3(1, 2 * pairs), kLdsWaves * 64, kLdsBytes * 3 / 4, hs>>>(p);
+      kfn<<<dim3(1, 2 * pairs8), kLdsWaves * 64, kLdsBytes * 3 / 4, hs>>>(p);
     } else if (shape->d == 128) {
       auto kfn = p.debug_stage
                      ? (stream ? decode_lds_kernel<true, true, 128, 1> : decode_lds_kernel<true, false, 128, 1>)
