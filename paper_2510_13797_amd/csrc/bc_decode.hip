@@ -7,8 +7,9 @@
 // workgroups (sequences under 1024 rows stay whole); every chunk writes an (m, l, o) partial
 // and a second, small kernel folds the partials of each pair in chunk order.  No float atomics
 // and no fences: results are bit-reproducible.  Large ragged batches (more pairs than compute
-// units) dispatch the longest sequences first: a small kernel in front of the main one sorts
-// the sequences by resident length.
+// units) can dispatch the longest sequences first (bc_sort_by_length).  Batches of at most 128
+// pairs with short caches use two workgroups per pair, each with all K rows and one half of the
+// V columns, so that all compute units pull data and nothing has to be merged.
 //
 // Two main kernels:
 //  * decode_lds_kernel (bf16, d = 128 or 64): every wave streams 32-row K and V tiles from HBM
