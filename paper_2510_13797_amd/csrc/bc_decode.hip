@@ -288,17 +288,20 @@ template <> __device__ __forceinline__ int tile_swz<64>(int row) {
 }
 
 // PROBES: honour the early exits of the timing probes (tuning variants 11..15).
-// STREAM: load K/V with the non-temporal policy (large launches; small ones are latency-bound
-// and about a microsecond faster with the default policy).
+// STREAM: 1 = load K and V with the non-temporal policy (large launches; small ones are
+// latency-bound and about a microsecond faster with the default policy, 0); 2 = V only: with two
+// workgroups per pair and long caches the K lines, which the partner reads a little later, are
+// better kept cacheable.
 // VS: workgroups per (sequence, KV head) pair.  With VS = 2 (batches of at most 128 pairs, which
 // would leave half of the compute units idle) two workgroups serve a pair: both read all K rows
 // and compute the same scores and weights, each reads one half of every V row and produces that
 // half of the output columns - no partial results to merge.  The partner's workgroup index is
 // larger by the number of pairs, which is the same XCD (same L2) when that number is a
 // multiple of 8: the K rows then come from HBM once.
-template <bool PROBES, bool STREAM, int D, int VS>
+template <bool PROBES, int STREAM, int D, int VS>
 __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams p) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
+  constexpr bool KSTREAM = STREAM == 1, VSTREAM = STREAM >= 1;
   constexpr int DV = D / VS;               // V (and output) columns of this workgroup
   constexpr int VROWB = DV * 2;            // bytes of its part of a V row, = row pitch of the V tile in LDS
   constexpr int VUPR = VROWB / 16;
@@ -378,10 +381,10 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
   _Pragma("unroll") for (int j = 0; j < NDMA; ++j) {                          \
     const int grow_ = min((TROW0) + RPI * j + r4, last_slab_row);             \
     const int64_t goff_ = (int64_t)grow_ * ROWB + (pos << 4);                 \
-    kreg[j] = load16<STREAM>(kbase + goff_);                                  \
+    kreg[j] = load16<KSTREAM>(kbase + goff_);                                 \
     if (j < VNDMA) {                                                          \
       const int vrow_ = min((TROW0) + VRPI * j + r4v, last_slab_row);         \
-      vreg[j] = load16<STREAM>(vbase + (VS == 1 ? goff_ : (int64_t)vrow_ * ROWB + (posv << 4)));  \
+      vreg[j] = load16<VSTREAM>(vbase + (VS == 1 ? goff_ : (int64_t)vrow_ * ROWB + (posv << 4)));  \
     }                                                                         \
   }
   if (wave < ntiles) {
@@ -393,13 +396,13 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
       const int grow = min(trow0 + row, last_slab_row);     // stay inside the slab rows
       const int64_t goff = (int64_t)grow * ROWB + ((pos ^ tile_swz<D>(row)) << 4);
       __builtin_amdgcn_global_load_lds((global_void_t*)(kbase + goff),
-                                       (lds_void_t*)(wk + j * 1024), 16, 0, STREAM ? kStreamPolicy : 0);
+                                       (lds_void_t*)(wk + j * 1024), 16, 0, KSTREAM ? kStreamPolicy : 0);
       if (j < VNDMA) {
         const int vrow = VRPI * j + r4v;
         const int vgrow = min(trow0 + vrow, last_slab_row);
         const int64_t vgoff = VS == 1 ? goff : (int64_t)vgrow * ROWB + ((posv ^ tile_swz<DV>(vrow)) << 4);
         __builtin_amdgcn_global_load_lds((global_void_t*)(vbase + vgoff),
-                                         (lds_void_t*)(wv + j * 1024), 16, 0, STREAM ? kStreamPolicy : 0);
+                                         (lds_void_t*)(wv + j * 1024), 16, 0, VSTREAM ? kStreamPolicy : 0);
       }
     }
     if (wave + kLdsWaves < ntiles) { BC_LOAD_TILE_REGS(trow0 + kLdsWaves * kTileRows) }
@@ -853,14 +856,15 @@ static int32_t enable_big_lds() {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return BC_ERR_HIP;
   if (done[dev]) return BC_OK;
-  const void* kernels[8] = {reinterpret_cast<const void*>(decode_lds_kernel<false, false, 128, 1>),
-                            reinterpret_cast<const void*>(decode_lds_kernel<false, true, 128, 1>),
-                            reinterpret_cast<const void*>(decode_lds_kernel<true, false, 128, 1>),
-                            reinterpret_cast<const void*>(decode_lds_kernel<true, true, 128, 1>),
-                            reinterpret_cast<const void*>(decode_lds_kernel<false, false, 64, 1>),
-                            reinterpret_cast<const void*>(decode_lds_kernel<false, true, 64, 1>),
-                            reinterpret_cast<const void*>(decode_lds_kernel<false, false, 128, 2>),
-                            reinterpret_cast<const void*>(decode_lds_kernel<false, true, 128, 2>)};
+  const void* kernels[9] = {reinterpret_cast<const void*>(decode_lds_kernel<false, 0, 128, 1>),
+                            reinterpret_cast<const void*>(decode_lds_kernel<false, 1, 128, 1>),
+                            reinterpret_cast<const void*>(decode_lds_kernel<true, 0, 128, 1>),
+                            reinterpret_cast<const void*>(decode_lds_kernel<true, 1, 128, 1>),
+                            reinterpret_cast<const void*>(decode_lds_kernel<false, 0, 64, 1>),
+                            reinterpret_cast<const void*>(decode_lds_kernel<false, 1, 64, 1>),
+                            reinterpret_cast<const void*>(decode_lds_kernel<false, 0, 128, 2>),
+                            reinterpret_cast<const void*>(decode_lds_kernel<false, 1, 128, 2>),
+                            reinterpret_cast<const void*>(decode_lds_kernel<false, 2, 128, 2>)};
   bool ok = true;
   for (const void* kfn : kernels)
     ok = ok && hipFuncSetAttribute(kfn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) ==
@@ -923,23 +927,25 @@ static int32_t launch_attention(const bc_shape* shape, const bc_cache* cache, co
     // launches that cannot saturate the memory system are latency-bound: default cache policy
     const bool stream = (long)pairs * pl.max_chunks >= kStreamMinWorkgroups && g_variant != 4;
     // two workgroups per pair (each one half of the V columns) while that still fits the chip
-    // (and while the K rows of the whole batch, which both workgroups of a pair read, stay in the
-    // caches between the two reads: measured faster up to about 64 MB of K, slower beyond)
     const int pairs8 = (pairs + 7) & ~7;
     const bool vsplit = shape->d == 128 && pl.max_chunks == 1 && 2 * pairs8 <= kLptMinPairs &&
-                        (int64_t)pairs * cache->max_cap * 256 <= (64LL << 20) &&
                         !p.debug_stage && g_variant != 5;
     if (vsplit) {
+      // K lines are read by both workgroups of a pair: streamed while the batch's K is small
+      // enough for the partner's request to find the line still on its way or in the L2
+      // (measured up to about 48 MB), cacheable beyond
       const bool stream2 = 2L * pairs >= kStreamMinWorkgroups && g_variant != 4;
-      auto kfn = stream2 ? decode_lds_kernel<false, true, 128, 2> : decode_lds_kernel<false, false, 128, 2>;
+      const bool small_k = (int64_t)pairs * cache->max_cap * 256 <= (48LL << 20);
+      auto kfn = !stream2 ? decode_lds_kernel<false, 0, 128, 2>
+                          : (small_k ? decode_lds_kernel<false, 1, 128, 2> : decode_lds_kernel<false, 2, 128, 2>);
       kfn<<<dim3(1, 2 * pairs8), kLdsWaves * 64, kLdsBytes * 3 / 4, hs>>>(p);
     } else if (shape->d == 128) {
       auto kfn = p.debug_stage
-                     ? (stream ? decode_lds_kernel<true, true, 128, 1> : decode_lds_kernel<true, false, 128, 1>)
-                     : (stream ? decode_lds_kernel<false, true, 128, 1> : decode_lds_kernel<false, false, 128, 1>);
+                     ? (stream ? decode_lds_kernel<true, 1, 128, 1> : decode_lds_kernel<true, 0, 128, 1>)
+                     : (stream ? decode_lds_kernel<false, 1, 128, 1> : decode_lds_kernel<false, 0, 128, 1>);
       kfn<<<grid, kLdsWaves * 64, kLdsBytes, hs>>>(p);
     } else {
-      auto kfn = stream ? decode_lds_kernel<false, true, 64, 1> : decode_lds_kernel<false, false, 64, 1>;
+      auto kfn = stream ? decode_lds_kernel<false, 1, 64, 1> : decode_lds_kernel<false, 0, 64, 1>;
       kfn<<<grid, kLdsWaves * 64, kLdsBytes / 2, hs>>>(p);
     }
   } else if (shape->kv_dtype == BC_BF16) {
