@@ -412,10 +412,14 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dkv_kernel(BwdPa
   const int ld_rr = 4 * wave + (lane >> 4);
   // tiles are issued in order, so the (head, row tile) pair of the next tile to issue is kept
   // in two counters instead of being recovered by a division
-  int issue_h = h_begin, issue_rt = 0;
+  // Row tiles are streamed from the last row of the range backwards: all dense key blocks of a
+  // (trajectory, KV head) pair need the rows from the end of the trajectory back to their own
+  // keys, start together (they are neighbours in dispatch order, on the same XCD) and so walk the
+  // same tiles at the same time - the later readers of a tile find it in the L2.
+  int issue_h = h_begin, issue_rt = ntile - 1;
   auto issue_tile = [&](int stage) {
     const int h = issue_h, rt = issue_rt;
-    if (++issue_rt == ntile) { issue_rt = 0; ++issue_h; }
+    if (--issue_rt < 0) { issue_rt = ntile - 1; ++issue_h; }
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
       const int tr = ld_rr + 16 * half;                       // entry of the tile
@@ -442,7 +446,7 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dkv_kernel(BwdPa
 #pragma unroll
   for (int j = 0; j < 8; ++j) { dK[j] = f32x4_t{0.f, 0.f, 0.f, 0.f}; dV[j] = f32x4_t{0.f, 0.f, 0.f, 0.f}; }
 
-  int stage = 0, cur_rt = 0;
+  int stage = 0, cur_rt = ntile - 1;
   for (int it = 0; it < NT; ++it) {
     if (it + 1 >= NT) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     else if (wave == 0) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");     // one more load per tile
@@ -454,7 +458,7 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dkv_kernel(BwdPa
     const float* tstat = reinterpret_cast<const float*>(lds + kBwLds + stage * 256);
     stage = stage + 1 == kBwStages ? 0 : stage + 1;
     const int rt = cur_rt;
-    if (++cur_rt == ntile) cur_rt = 0;
+    if (--cur_rt < 0) cur_rt = ntile - 1;
     const int row0 = rs + rt * kBwBN + 8 * kb;          // this lane's 8 rows: row0 + e
 
     // per-row statistics of this lane's rows (head-major, 8 rows = 64 contiguous bytes)
