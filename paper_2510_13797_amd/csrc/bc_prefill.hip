@@ -50,6 +50,8 @@ struct PrefillParams {
   float* lse;
   int32_t Hq, Hkv, g;
   int32_t hsplit;     // the group's heads are split over this many workgroups (HPW heads each)
+  int32_t npairs;     // (trajectory, KV head) pairs
+  int32_t pstride;    // npairs rounded up to a multiple of 8
   float qscale;       // softmax scale * log2(e)
 };
 
@@ -62,9 +64,12 @@ constexpr float kPfLazy = 5.0f;
 template <int HPW>     // query heads per wave (the group's heads are split over p.hsplit workgroups)
 __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams p) {
   __shared__ __attribute__((aligned(1024))) char lds[kPfLds];
-  // grid: x = (trajectory, KV head, head split), y = query tile; workgroups are dispatched
+  // grid: x = (head split, trajectory, KV head), y = query tile; workgroups are dispatched
   // x-fastest, so the longest tiles of every trajectory start first
-  const int pair = blockIdx.x / p.hsplit, hh = blockIdx.x - pair * p.hsplit;
+  // (the head splits of a pair are `pstride` workgroups apart, a multiple of 8: workgroups go to the
+  // XCDs in turn, so the splits - which read the same K/V tiles - share an L2)
+  const int hh = blockIdx.x / p.pstride, pair = blockIdx.x - hh * p.pstride;
+  if (pair >= p.npairs) return;
   const int kvh = pair % p.Hkv, b = pair / p.Hkv;
   const int64_t off0 = p.row_off[b];
   const int S = (int)(p.row_off[b + 1] - off0);
@@ -351,7 +356,9 @@ extern "C" int32_t bc_prefill_attn(const bc_shape* shape, const void* q, const v
   // file): one workgroup for a single head, two for groups up to six, three for seven and eight
   p.hsplit = p.g == 1 ? 1 : (p.g <= 6 ? 2 : 3);
   const int hpw = (p.g + p.hsplit - 1) / p.hsplit;
-  const dim3 grid(p.hsplit * shape->Hkv * shape->B, (max_rows + kPfBM - 1) / kPfBM);
+  p.npairs = shape->Hkv * shape->B;
+  p.pstride = (p.npairs + 7) & ~7;
+  const dim3 grid(p.hsplit * p.pstride, (max_rows + kPfBM - 1) / kPfBM);
   hipStream_t hs = as_stream(stream);
   switch (hpw) {
     case 1: prefill_kernel<1><<<grid, kPfWaves * 64, 0, hs>>>(p); break;

@@ -59,6 +59,8 @@ struct BwdParams {
   int32_t hsplit;       // head splits of a dense key block (1: none), heads per split = ceil(g / hsplit)
   int64_t total_rows;
   int32_t Hq, Hkv, g;
+  int32_t npairs;       // (trajectory, KV head) pairs
+  int32_t pstride;      // npairs rounded up to a multiple of 8
   float scale;
   float qscale;         // scale * log2(e)
 };
@@ -127,10 +129,13 @@ constexpr int kDqHeads = 2;      // query heads per workgroup
 
 __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dq_kernel(BwdParams p) {
   __shared__ __attribute__((aligned(1024))) char lds[kBwLds];
-  // grid: x = (trajectory, KV head, head pair), y = query tile, longest tiles of every
+  // grid: x = (head pair, trajectory, KV head), y = query tile, longest tiles of every
   // trajectory first (workgroups are dispatched x-fastest)
-  const int nhg = (p.g + kDqHeads - 1) / kDqHeads;
-  const int hh = blockIdx.x % nhg, kvh = (blockIdx.x / nhg) % p.Hkv, b = blockIdx.x / (nhg * p.Hkv);
+  // (the head pairs of one (trajectory, KV head) are `pstride` workgroups apart, a multiple of 8:
+  // workgroups go to the XCDs in turn, so the workgroups that read the same K/V tiles share an L2)
+  const int hh = blockIdx.x / p.pstride, pair = blockIdx.x - hh * p.pstride;
+  if (pair >= p.npairs) return;
+  const int kvh = pair % p.Hkv, b = pair / p.Hkv;
   const int64_t off0 = p.row_off[b];
   const int S = (int)(p.row_off[b + 1] - off0);
   const int qt = gridDim.y - 1 - blockIdx.y;
@@ -617,7 +622,9 @@ extern "C" int32_t bc_prefill_attn_bwd(const bc_shape* shape, const void* q, con
   hipStream_t hs = as_stream(stream);
   const int tiles = (max_rows + kBwBM - 1) / kBwBM;
   const int nhg = (p.g + kDqHeads - 1) / kDqHeads;
-  prefill_bwd_dq_kernel<<<dim3(shape->B * shape->Hkv * nhg, tiles), kBwWaves * 64, 0, hs>>>(p);
+  p.npairs = shape->B * shape->Hkv;
+  p.pstride = (p.npairs + 7) & ~7;
+  prefill_bwd_dq_kernel<<<dim3(p.pstride * nhg, tiles), kBwWaves * 64, 0, hs>>>(p);
   // key blocks: at most `tiles` dense-causal blocks + the gathered beacons + `tiles` response blocks
   prefill_bwd_dkv_kernel<<<dim3(shape->B * shape->Hkv, (2 * tiles + 2) * p.hsplit + tiles),
                            kBwWaves * 64, 0, hs>>>(p);
