@@ -333,6 +333,7 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dkv_kernel(BwdPa
   __shared__ __attribute__((aligned(1024))) char lds[kBwLds + kBwStatLds];
   // grid: x = (trajectory, KV head), y = key block; the long dense blocks of every trajectory
   // are dispatched before any short one
+  if ((int)blockIdx.x >= p.npairs) return;      // the grid's x extent is padded to a multiple of 8 (XCD count)
   const int kvh = blockIdx.x % p.Hkv, b = blockIdx.x / p.Hkv;
   const int64_t off0 = p.row_off[b];
   const int S = (int)(p.row_off[b + 1] - off0);
@@ -626,7 +627,7 @@ extern "C" int32_t bc_prefill_attn_bwd(const bc_shape* shape, const void* q, con
   p.pstride = (p.npairs + 7) & ~7;
   prefill_bwd_dq_kernel<<<dim3(p.pstride * nhg, tiles), kBwWaves * 64, 0, hs>>>(p);
   // key blocks: at most `tiles` dense-causal blocks + the gathered beacons + `tiles` response blocks
-  prefill_bwd_dkv_kernel<<<dim3(shape->B * shape->Hkv, (2 * tiles + 2) * p.hsplit + tiles),
+  prefill_bwd_dkv_kernel<<<dim3(p.pstride, (2 * tiles + 2) * p.hsplit + tiles),
                            kBwWaves * 64, 0, hs>>>(p);
   if (p.hsplit > 1) {
     const int64_t blocks = (total_rows * shape->Hkv * 32 + 255) / 256;
