@@ -244,8 +244,12 @@ __device__ __forceinline__ void merge_waves_and_store(const DecodeParams& p, con
 // bf16, d = 128 or 64: LDS-DMA tiles + MFMA
 // ---------------------------------------------------------------------------
 constexpr int kLdsWaves = 8;           // waves per workgroup
+constexpr int kLdsWavesSplit = 12;     // ... of the two-workgroups-per-pair form on short caches (12 KB of LDS per wave)
+constexpr int kSplitWaves12MaxCap = 1100;   // rows: beyond this eight waves are as fast or faster (measured)
 constexpr int kTileRows = 32;          // rows per wave tile
 constexpr int kLdsBytes = kLdsWaves * 2 * kTileRows * 256;   // d = 128: 128 KB (half of it for d = 64)
+constexpr int kLdsBytesSplit = kLdsWavesSplit * 3 * kTileRows * 128;   // K tile + half a V tile per wave: 144 KB
+constexpr int kLdsBytesMax = kLdsBytesSplit > kLdsBytes ? kLdsBytesSplit : kLdsBytes;
 
 typedef __attribute__((address_space(3))) void lds_void_t;
 typedef __attribute__((address_space(1))) const void global_void_t;
@@ -298,8 +302,10 @@ template <> __device__ __forceinline__ int tile_swz<64>(int row) {
 // half of the output columns - no partial results to merge.  The partner's workgroup index is
 // larger by the number of pairs, which is the same XCD (same L2) when that number is a
 // multiple of 8: the K rows then come from HBM once.
-template <bool PROBES, int STREAM, int D, int VS>
-__global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams p) {
+// NW: waves per workgroup, 8 or (two workgroups per pair, short caches: every wave then has one or
+// two tiles, and twelve waves finish a sequence of up to 384 rows in one pass) 12.
+template <bool PROBES, int STREAM, int D, int VS, int NW>
+__global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   constexpr bool KSTREAM = STREAM == 1, VSTREAM = STREAM >= 1;
   constexpr int DV = D / VS;               // V (and output) columns of this workgroup
@@ -405,13 +411,13 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
                                          (lds_void_t*)(wv + j * 1024), 16, 0, VSTREAM ? kStreamPolicy : 0);
       }
     }
-    if (wave + kLdsWaves < ntiles) { BC_LOAD_TILE_REGS(trow0 + kLdsWaves * kTileRows) }
+    if (wave + NW < ntiles) { BC_LOAD_TILE_REGS(trow0 + NW * kTileRows) }
   }
-  for (int tile = wave; tile < ntiles; tile += kLdsWaves) {
+  for (int tile = wave; tile < ntiles; tile += NW) {
     const int trow0 = pi.row0 + tile * kTileRows;
     if (tile == wave) {
       // the LDS-DMA loads have landed once at most the register loads behind them are pending
-      if (wave + kLdsWaves >= ntiles) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      if (wave + NW >= ntiles) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       else if (NDMA + VNDMA == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
       else if (NDMA + VNDMA == 12) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
       else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
@@ -426,7 +432,7 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
           *reinterpret_cast<uint4*>(wv + (VS == 1 ? o : vrow * VROWB + ((posv ^ tile_swz<DV>(vrow)) << 4))) = vreg[j];
         }
       }
-      if (tile + kLdsWaves < ntiles) { BC_LOAD_TILE_REGS(trow0 + kLdsWaves * kTileRows) }
+      if (tile + NW < ntiles) { BC_LOAD_TILE_REGS(trow0 + NW * kTileRows) }
     }
     if (PROBES && p.debug_stage == 3) continue;
 
@@ -547,9 +553,9 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
                  : "=v"(ticket) : "v"(p.tickets + pi.s), "v"(one) : "memory");
   }
   float* s_acc = reinterpret_cast<float*>(lds);                    // [wave][8][DV]
-  float* s_m = s_acc + kLdsWaves * 8 * DV;                         // [wave][8]
-  float* s_l = s_m + kLdsWaves * 8;
-  int* s_last = reinterpret_cast<int*>(s_l + kLdsWaves * 8);
+  float* s_m = s_acc + NW * 8 * DV;                         // [wave][8]
+  float* s_l = s_m + NW * 8;
+  int* s_last = reinterpret_cast<int*>(s_l + NW * 8);
   if (n < p.g) {
 #pragma unroll
     for (int j = 0; j < NJ; ++j)
@@ -557,7 +563,7 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
     if (kb == 0) { s_m[wave * 8 + n] = m_run; s_l[wave * 8 + n] = l_run; }
   }
   __syncthreads();
-  merge_waves_and_store<kLdsWaves, DV, D>(p, pi, s_m, s_l, s_acc, 8, vhalf * DV);
+  merge_waves_and_store<NW, DV, D>(p, pi, s_m, s_l, s_acc, 8, vhalf * DV);
 
   // ---- the last workgroup of the sequence writes the beacon row and updates the tables
   if (!pi.update || (PROBES && p.debug_stage == 5)) return;
@@ -569,7 +575,7 @@ __global__ __launch_bounds__(kLdsWaves * 64) void decode_lds_kernel(DecodeParams
   if (!*s_last) return;
   if (pi.evict_due) {
     const int n16 = p.Hkv * UPR;                   // 16-byte units of one K (or V) entry
-    for (int i = tid; i < 2 * n16; i += kLdsWaves * 64) {
+    for (int i = tid; i < 2 * n16; i += NW * 64) {
       const int which = i >= n16, r = which ? i - n16 : i;
       const int h = r / UPR, u = r & (UPR - 1);
       const char* src = (which ? p.bv : p.bk) + (int64_t)(pi.s * p.Hkv + h) * ROWB + (u << 4);
@@ -856,18 +862,22 @@ static int32_t enable_big_lds() {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return BC_ERR_HIP;
   if (done[dev]) return BC_OK;
-  const void* kernels[9] = {reinterpret_cast<const void*>(decode_lds_kernel<false, 0, 128, 1>),
-                            reinterpret_cast<const void*>(decode_lds_kernel<false, 1, 128, 1>),
-                            reinterpret_cast<const void*>(decode_lds_kernel<true, 0, 128, 1>),
-                            reinterpret_cast<const void*>(decode_lds_kernel<true, 1, 128, 1>),
-                            reinterpret_cast<const void*>(decode_lds_kernel<false, 0, 64, 1>),
-                            reinterpret_cast<const void*>(decode_lds_kernel<false, 1, 64, 1>),
-                            reinterpret_cast<const void*>(decode_lds_kernel<false, 0, 128, 2>),
-                            reinterpret_cast<const void*>(decode_lds_kernel<false, 1, 128, 2>),
-                            reinterpret_cast<const void*>(decode_lds_kernel<false, 2, 128, 2>)};
+  const void* kernels[13] = {reinterpret_cast<const void*>(decode_lds_kernel<false, 0, 128, 1, 8>),
+                             reinterpret_cast<const void*>(decode_lds_kernel<false, 1, 128, 1, 8>),
+                             reinterpret_cast<const void*>(decode_lds_kernel<true, 0, 128, 1, 8>),
+                             reinterpret_cast<const void*>(decode_lds_kernel<true, 1, 128, 1, 8>),
+                             reinterpret_cast<const void*>(decode_lds_kernel<false, 0, 64, 1, 8>),
+                             reinterpret_cast<const void*>(decode_lds_kernel<false, 1, 64, 1, 8>),
+                             reinterpret_cast<const void*>(decode_lds_kernel<false, 0, 128, 2, 8>),
+                             reinterpret_cast<const void*>(decode_lds_kernel<false, 1, 128, 2, 8>),
+                             reinterpret_cast<const void*>(decode_lds_kernel<false, 2, 128, 2, 8>),
+                             reinterpret_cast<const void*>(decode_lds_kernel<false, 0, 128, 2, 12>),
+                             reinterpret_cast<const void*>(decode_lds_kernel<false, 1, 128, 2, 12>),
+                             reinterpret_cast<const void*>(decode_lds_kernel<true, 1, 128, 2, 8>),
+                             reinterpret_cast<const void*>(decode_lds_kernel<true, 1, 128, 2, 12>)};
   bool ok = true;
   for (const void* kfn : kernels)
-    ok = ok && hipFuncSetAttribute(kfn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) ==
+    ok = ok && hipFuncSetAttribute(kfn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytesMax) ==
                    hipSuccess;
   if (!ok)
     return BC_ERR_HIP;
@@ -929,23 +939,28 @@ static int32_t launch_attention(const bc_shape* shape, const bc_cache* cache, co
     // two workgroups per pair (each one half of the V columns) while that still fits the chip
     const int pairs8 = (pairs + 7) & ~7;
     const bool vsplit = shape->d == 128 && pl.max_chunks == 1 && 2 * pairs8 <= kLptMinPairs &&
-                        !p.debug_stage && g_variant != 5;
+                        g_variant != 5;
     if (vsplit) {
       // K lines are read by both workgroups of a pair: streamed while the batch's K is small
       // enough for the partner's request to find the line still on its way or in the L2
       // (measured up to about 48 MB), cacheable beyond
       const bool stream2 = 2L * pairs >= kStreamMinWorkgroups && g_variant != 4;
       const bool small_k = (int64_t)pairs * cache->max_cap * 256 <= (48LL << 20);
-      auto kfn = !stream2 ? decode_lds_kernel<false, 0, 128, 2>
-                          : (small_k ? decode_lds_kernel<false, 1, 128, 2> : decode_lds_kernel<false, 2, 128, 2>);
-      kfn<<<dim3(1, 2 * pairs8), kLdsWaves * 64, kLdsBytes * 3 / 4, hs>>>(p);
+      // short caches: twelve waves (most sequences then need one pass); long ones: eight
+      const bool w12 = cache->max_cap <= kSplitWaves12MaxCap;
+      auto kfn = p.debug_stage ? (w12 ? decode_lds_kernel<true, 1, 128, 2, 12> : decode_lds_kernel<true, 1, 128, 2, 8>)
+                 : !stream2    ? (w12 ? decode_lds_kernel<false, 0, 128, 2, 12> : decode_lds_kernel<false, 0, 128, 2, 8>)
+                 : small_k     ? (w12 ? decode_lds_kernel<false, 1, 128, 2, 12> : decode_lds_kernel<false, 1, 128, 2, 8>)
+                               : decode_lds_kernel<false, 2, 128, 2, 8>;
+      const int nw = w12 ? kLdsWavesSplit : kLdsWaves;
+      kfn<<<dim3(1, 2 * pairs8), nw * 64, nw * 3 * kTileRows * 128, hs>>>(p);
     } else if (shape->d == 128) {
       auto kfn = p.debug_stage
-                     ? (stream ? decode_lds_kernel<true, 1, 128, 1> : decode_lds_kernel<true, 0, 128, 1>)
-                     : (stream ? decode_lds_kernel<false, 1, 128, 1> : decode_lds_kernel<false, 0, 128, 1>);
+                     ? (stream ? decode_lds_kernel<true, 1, 128, 1, 8> : decode_lds_kernel<true, 0, 128, 1, 8>)
+                     : (stream ? decode_lds_kernel<false, 1, 128, 1, 8> : decode_lds_kernel<false, 0, 128, 1, 8>);
       kfn<<<grid, kLdsWaves * 64, kLdsBytes, hs>>>(p);
     } else {
-      auto kfn = stream ? decode_lds_kernel<false, 1, 64, 1> : decode_lds_kernel<false, 0, 64, 1>;
+      auto kfn = stream ? decode_lds_kernel<false, 1, 64, 1, 8> : decode_lds_kernel<false, 0, 64, 1, 8>;
       kfn<<<grid, kLdsWaves * 64, kLdsBytes / 2, hs>>>(p);
     }
   } else if (shape->kv_dtype == BC_BF16) {
