@@ -648,7 +648,7 @@ def main():
                    "layers_round_robin": NL, "hip_graph": graph is not None, "beacon_token_attention": bool(faithful),
                    "step": "bc_decode_step for one layer: append_kv + decode_attn + compress_evict, one launch",
                    "kv_bytes_per_step_mean": int(np.mean(step_bytes))},
-        "roofline": {"bound": "hbm", "kernel": "bc::decode_lds_kernel<false, 1, 128, 2> (bc_decode_step: append + attention + eviction)",
+        "roofline": {"bound": "hbm", "kernel": "bc::decode_lds_kernel<false, 1, 128, 2, 12> (bc_decode_step: append + attention + eviction)",
                      "achieved": round(achieved, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": (stored_traffic() or {}).get("bytes_per_launch"),
                      "traffic_detail": stored_traffic(),
