@@ -206,10 +206,11 @@ __device__ __forceinline__ PairInfo pair_info(const DecodeParams& p, int pair_in
 
 // Epilogue shared by both kernels: s_m/s_l/s_acc hold one (m, l, o) per wave in LDS;
 // merge them in wave order and write the result or the chunk partial.
-template <int NW, int D, int DOUT = D>
+template <int NW, int D, int DOUT = D, int APITCH = D>
 __device__ __forceinline__ void merge_waves_and_store(const DecodeParams& p, const PairInfo& pi,
                                                       const float* s_m, const float* s_l,
                                                       const float* s_acc, int gstride, int col0 = 0) {
+  // APITCH: floats between the accumulator rows of two heads in s_acc
   // D: columns this workgroup holds (all DOUT of a head, or one half starting at col0)
   const int nout = p.g * D;
   const int pair = pi.s * p.Hkv + pi.kvh;
@@ -226,7 +227,7 @@ __device__ __forceinline__ void merge_waves_and_store(const DecodeParams& p, con
     for (int wv = 0; wv < NW; ++wv) {
       const float a = fast_exp2(s_m[wv * gstride + h] - mx);
       lsum += s_l[wv * gstride + h] * a;
-      o += s_acc[(wv * gstride + h) * D + x] * a;
+      o += s_acc[(wv * gstride + h) * APITCH + x] * a;
     }
     if (pi.nchunks == 1) {
       __builtin_nontemporal_store(o / lsum, outp + (D == DOUT ? i : h * DOUT + x));   // streamed out: nothing left dirty in L2
@@ -552,18 +553,21 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
     asm volatile("global_atomic_add %0, %1, %2, off sc0"
                  : "=v"(ticket) : "v"(p.tickets + pi.s), "v"(one) : "memory");
   }
-  float* s_acc = reinterpret_cast<float*>(lds);                    // [wave][8][DV]
-  float* s_m = s_acc + NW * 8 * DV;                         // [wave][8]
+  // (rows of DV floats would all start on the same LDS bank: a pitch of DV + 4 floats spreads the
+  // 128-bit writes of the up to eight heads over the banks)
+  constexpr int APITCH = DV + 4;
+  float* s_acc = reinterpret_cast<float*>(lds);                    // [wave][8][APITCH]
+  float* s_m = s_acc + NW * 8 * APITCH;                     // [wave][8]
   float* s_l = s_m + NW * 8;
   int* s_last = reinterpret_cast<int*>(s_l + NW * 8);
   if (n < p.g) {
 #pragma unroll
     for (int j = 0; j < NJ; ++j)
-      *reinterpret_cast<f32x4_t*>(s_acc + (wave * 8 + n) * DV + 16 * j + 4 * kb) = O[j];
+      *reinterpret_cast<f32x4_t*>(s_acc + (wave * 8 + n) * APITCH + 16 * j + 4 * kb) = O[j];
     if (kb == 0) { s_m[wave * 8 + n] = m_run; s_l[wave * 8 + n] = l_run; }
   }
   __syncthreads();
-  merge_waves_and_store<NW, DV, D>(p, pi, s_m, s_l, s_acc, 8, vhalf * DV);
+  merge_waves_and_store<NW, DV, D, APITCH>(p, pi, s_m, s_l, s_acc, 8, vhalf * DV);
 
   // ---- the last workgroup of the sequence writes the beacon row and updates the tables
   if (!pi.update || (PROBES && p.debug_stage == 5)) return;
