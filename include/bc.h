@@ -220,7 +220,7 @@ int32_t bc_set_ratio(const bc_shape *shape, const bc_cache *cache, const int32_t
  * q: [total_rows, Hq, d]; k, v: [total_rows, Hkv, d] (kv_dtype must be BC_BF16);
  * out: [total_rows, Hq, d] fp32; lse (nullable): [total_rows, Hq] fp32, natural log of
  * the softmax denominator.  row_offsets: device [B+1] int64; P, c: device [B] int32;
- * max_rows: HOST value >= the longest trajectory (sizes the grid), < 2^26.  scale must be > 0. */
+ * max_rows: HOST value >= the longest trajectory (sizes the grid), < 2^26.  scale must be > 0 and finite (else BC_ERR_ARG). */
 int32_t bc_prefill_attn(const bc_shape *shape, const void *q, const void *k, const void *v,
                         const int64_t *row_offsets, const int32_t *P, const int32_t *c,
                         int32_t max_rows, float *out, float *lse, void *stream);
@@ -231,7 +231,7 @@ int32_t bc_prefill_attn(const bc_shape *shape, const void *q, const void *k, con
  * dq [total_rows, Hq, d], dk and dv [total_rows, Hkv, d] (summed over the query heads of a
  * group); every element is written, nothing needs zeroing.  total_rows: HOST copy of
  * row_offsets[B].  workspace: bc_prefill_bwd_workspace_bytes() bytes, no initialisation.
- * No atomics: results are reproducible.  scale must be > 0. */
+ * No atomics: results are reproducible.  scale must be > 0 and finite (else BC_ERR_ARG). */
 size_t bc_prefill_bwd_workspace_bytes(const bc_shape *shape, int64_t total_rows);
 int32_t bc_prefill_attn_bwd(const bc_shape *shape, const void *q, const void *k, const void *v,
                             const float *out, const float *lse, const void *dout,

@@ -108,6 +108,14 @@ inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s);
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// x > 0 and finite, decided on the bit pattern: a floating-point comparison would let a NaN
+// through in files built with the assumption that NaNs do not occur.
+inline bool positive_finite(float x) {
+  uint32_t u;
+  __builtin_memcpy(&u, &x, sizeof(u));
+  return u > 0u && u < 0x7f800000u;
+}
+
 inline int32_t check_shape(const bc_shape* sh) {
   if (!sh) return BC_ERR_ARG;
   if (sh->B < 1 || sh->Hq < 1 || sh->Hkv < 1) return BC_ERR_SHAPE;

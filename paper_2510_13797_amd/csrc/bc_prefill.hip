@@ -343,7 +343,7 @@ extern "C" int32_t bc_prefill_attn(const bc_shape* shape, const void* q, const v
   if (!q || !k || !v || !row_offsets || !P || !c || !out) return BC_ERR_ARG;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return BC_ERR_ARG;
   if (max_rows < 1 || max_rows >= (1 << 26)) return BC_ERR_ARG;
-  if (!(shape->scale > 0.f)) return BC_ERR_ARG;       // the kernel takes maxima of unscaled scores
+  if (!positive_finite(shape->scale)) return BC_ERR_ARG;       // the kernel takes maxima of unscaled scores
   PrefillParams p;
   p.q = static_cast<const char*>(q);
   p.k = static_cast<const char*>(k);

@@ -603,7 +603,7 @@ extern "C" int32_t bc_prefill_attn_bwd(const bc_shape* shape, const void* q, con
       !aligned16(dq) || !aligned16(dk) || !aligned16(dv))
     return BC_ERR_ARG;
   if (max_rows < 1 || max_rows >= (1 << 26) || total_rows < max_rows) return BC_ERR_ARG;
-  if (!(shape->scale > 0.f)) return BC_ERR_ARG;
+  if (!positive_finite(shape->scale)) return BC_ERR_ARG;
   if (!workspace || !aligned16(workspace) ||
       workspace_bytes < bc_prefill_bwd_workspace_bytes(shape, total_rows))
     return BC_ERR_WORKSPACE;
