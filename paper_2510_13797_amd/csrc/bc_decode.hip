@@ -19,6 +19,7 @@
 //    128-bit reads, V by the 16-bit transposing reads), softmax in registers.
 //  * decode_valu_kernel (fp32): rows held in registers, 16 bytes per lane, plain
 //    FMA dot products completed by a DPP all-reduce.
+#include <atomic>
 #include "bc_common.h"
 
 namespace bc {
@@ -117,34 +118,47 @@ __global__ __launch_bounds__(256) void sort_by_length_kernel(SortParams p) {
   p.order[rank] = t;
 }
 
-__device__ __forceinline__ PairInfo pair_info(const DecodeParams& p, int pair_index) {
+// The kernel arguments span four 64-byte lines that the code below would touch one after the
+// other, each a miss of the scalar cache on the way to the first tile request: ask for all four
+// at once.
+__device__ __forceinline__ void touch_kernel_arguments() {
+  typedef __attribute__((address_space(4))) const int const_int_t;
+  const_int_t* ka = (const_int_t*)__builtin_amdgcn_kernarg_segment_ptr();
+  static_assert(sizeof(DecodeParams) > 48 * 4, "the last line touched lies inside the arguments");
+  const int a = ka[0], b = ka[16], c = ka[32], d = ka[48];
+  asm volatile("" : : "s"(a), "s"(b), "s"(c), "s"(d));
+}
+
+// slot: the sequence's index, or its rank in the dispatch order when there is one.  The grid
+// carries (chunk, KV head, slot) in its three dimensions, so that nothing has to be divided
+// before the tables can be requested; all of them are requested together.
+__device__ __forceinline__ PairInfo pair_info(const DecodeParams& p, int slot, int kvh, int chunk) {
   PairInfo pi;
   int act, w;
-  int pair = pair_index;
+  int s = slot;
   bool bad_order = false;
   if (p.order) {
-    const int rank = pair / p.Hkv;
-    const int s = p.order[rank];
+    s = p.order[slot];
     bad_order = (unsigned)s >= (unsigned)p.B;        // not written by bc_sort_by_length
-    pair = (bad_order ? 0 : s) * p.Hkv + (pair - rank * p.Hkv);
+    if (bad_order) s = 0;
   }
-  pi.s = pair / p.Hkv;
-  pi.kvh = pair - pi.s * p.Hkv;
-  act = p.active ? p.active[pi.s] : 1;
+  pi.s = s;
+  pi.kvh = kvh;
   pi.P = p.P[pi.s];
   pi.nb = p.nb[pi.s];
   w = p.w[pi.s];
   pi.cap = p.cap[pi.s];
   pi.base = p.base[pi.s];
-  pi.c = p.c ? p.c[pi.s] : 0;
+  pi.c = p.c[pi.s];
+  act = p.active ? p.active[pi.s] : 1;
   if (bad_order) {
-    if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(p.err, BC_ERRBIT_STATE);
+    if (chunk == 0 && threadIdx.x == 0) atomicOr(p.err, BC_ERRBIT_STATE);
     act = 0;
   }
-  const bool herald = blockIdx.x == 0 && pi.kvh == 0 && threadIdx.x == 0;   // reports errors
+  const bool herald = chunk == 0 && pi.kvh == 0 && threadIdx.x == 0;   // reports errors
   pi.live = false;
   pi.update = false; pi.evict_due = false; pi.new_row = -1; pi.store_new_row = false;
-  pi.L = 0; pi.nchunks = 0; pi.chunk = blockIdx.x; pi.row0 = 0; pi.row_end = 0; pi.w_att = w;
+  pi.L = 0; pi.nchunks = 0; pi.chunk = chunk; pi.row0 = 0; pi.row_end = 0; pi.w_att = w;
   // beacon step: only sequences whose window is full take part; one that has no room for the
   // beacon at the tail is reported and left alone
   bool take = act != 0;
@@ -183,12 +197,17 @@ __device__ __forceinline__ PairInfo pair_info(const DecodeParams& p, int pair_in
       // rows per chunk: the forced size, or the sequence's rows spread evenly over as many of
       // the max_chunks workgroups as have at least kMinChunkRows rows to read
       int rpc = p.rows_per_wg;
-      if (rpc <= 0) {
-        // (a short sequence stays whole: its partial would cost more than the split saves)
-        const int nc = pi.L < kMinSplitRows ? 1 : min(p.max_chunks, pi.L / kMinChunkRows);
-        rpc = (((pi.L + nc - 1) / nc) + 31) & ~31;
+      if (rpc <= 0 && p.max_chunks == 1) {
+        rpc = (pi.L + 31) & ~31;              // one workgroup has the whole sequence
+        pi.nchunks = 1;
+      } else {
+        if (rpc <= 0) {
+          // (a short sequence stays whole: its partial would cost more than the split saves)
+          const int nc = pi.L < kMinSplitRows ? 1 : min(p.max_chunks, pi.L / kMinChunkRows);
+          rpc = (((pi.L + nc - 1) / nc) + 31) & ~31;
+        }
+        pi.nchunks = (pi.L + rpc - 1) / rpc;
       }
-      pi.nchunks = (pi.L + rpc - 1) / rpc;
       // the evaluation cap is tested on what this step's attention sees, whether or not the
       // append went through
       pi.update = append_ok || pi.evict_due ||
@@ -200,7 +219,7 @@ __device__ __forceinline__ PairInfo pair_info(const DecodeParams& p, int pair_in
       }
     }
   }
-  if (p.part_n && blockIdx.x == 0 && threadIdx.x == 0) p.part_n[pi.s * p.Hkv + pi.kvh] = pi.nchunks;
+  if (p.part_n && chunk == 0 && threadIdx.x == 0) p.part_n[pi.s * p.Hkv + pi.kvh] = pi.nchunks;
   return pi;
 }
 
@@ -209,30 +228,81 @@ __device__ __forceinline__ PairInfo pair_info(const DecodeParams& p, int pair_in
 template <int NW, int D, int DOUT = D, int APITCH = D>
 __device__ __forceinline__ void merge_waves_and_store(const DecodeParams& p, const PairInfo& pi,
                                                       const float* s_m, const float* s_l,
-                                                      const float* s_acc, int gstride, int col0 = 0) {
+                                                      const float* s_acc, int ml_stride,
+                                                      int acc_stride, int col0 = 0) {
   // APITCH: floats between the accumulator rows of two heads in s_acc
+  // ml_stride, acc_stride: floats between the entries of two waves in s_m / s_l and in s_acc
   // D: columns this workgroup holds (all DOUT of a head, or one half starting at col0)
   const int nout = p.g * D;
   const int pair = pi.s * p.Hkv + pi.kvh;
   float* po = p.part_o + ((int64_t)pair * p.max_chunks + pi.chunk) * (p.Gp * D);
   float* pml = p.part_ml + ((int64_t)pair * p.max_chunks + pi.chunk) * (2 * p.Gp);
   float* outp = p.out + (int64_t)(pi.s * p.Hq + pi.kvh * p.g) * DOUT + col0;
-  for (int i = threadIdx.x; i < nout; i += blockDim.x) {
+  // (NW * 64 threads: the block size read from the launch descriptor would be one more scalar-cache miss)
+  for (int i = threadIdx.x; i < nout; i += NW * 64) {
     const int h = i / D, x = i - h * D;
     float mx = s_m[h];
 #pragma unroll
-    for (int wv = 1; wv < NW; ++wv) mx = fmaxf(mx, s_m[wv * gstride + h]);
+    for (int wv = 1; wv < NW; ++wv) mx = fmaxf(mx, s_m[wv * ml_stride + h]);
     float lsum = 0.f, o = 0.f;
 #pragma unroll
     for (int wv = 0; wv < NW; ++wv) {
-      const float a = fast_exp2(s_m[wv * gstride + h] - mx);
-      lsum += s_l[wv * gstride + h] * a;
-      o += s_acc[(wv * gstride + h) * APITCH + x] * a;
+      const float a = fast_exp2(s_m[wv * ml_stride + h] - mx);
+      lsum += s_l[wv * ml_stride + h] * a;
+      o += s_acc[wv * acc_stride + h * APITCH + x] * a;
     }
     if (pi.nchunks == 1) {
       __builtin_nontemporal_store(o / lsum, outp + (D == DOUT ? i : h * DOUT + x));   // streamed out: nothing left dirty in L2
     } else {
       __builtin_nontemporal_store(o, po + i);
+      if (x == 0) {
+        __builtin_nontemporal_store(mx, pml + h);
+        __builtin_nontemporal_store(lsum, pml + p.Gp + h);
+      }
+    }
+  }
+}
+
+// The same merge, four output columns per thread (128-bit LDS reads and stores): fewer waves
+// take part, which shortens this serial tail of the matrix-core kernel.
+template <int NW, int D, int DOUT, int APITCH>
+__device__ __forceinline__ void merge_waves_and_store4(const DecodeParams& p, const PairInfo& pi,
+                                                       const float* s_m, const float* s_l,
+                                                       const float* s_acc, int wave_stride, int col0) {
+  constexpr int Q = D / 4;                       // column quads per head
+  const int nitems = p.g * Q;
+  const int pair = pi.s * p.Hkv + pi.kvh;
+  float* po = p.part_o + ((int64_t)pair * p.max_chunks + pi.chunk) * (p.Gp * D);
+  float* pml = p.part_ml + ((int64_t)pair * p.max_chunks + pi.chunk) * (2 * p.Gp);
+  float* outp = p.out + (int64_t)(pi.s * p.Hq + pi.kvh * p.g) * DOUT + col0;
+  for (int i = threadIdx.x; i < nitems; i += NW * 64) {
+    const int h = i / Q, x = (i - h * Q) * 4;
+    // all reads first: the merge is one LDS round trip, not one per wave
+    float mw[NW], lw[NW];
+    f32x4_t ow[NW];
+#pragma unroll
+    for (int wv = 0; wv < NW; ++wv) {
+      mw[wv] = s_m[wv * wave_stride + h];
+      lw[wv] = s_l[wv * wave_stride + h];
+      ow[wv] = *reinterpret_cast<const f32x4_t*>(s_acc + wv * wave_stride + h * APITCH + x);
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    float mx = mw[0];
+#pragma unroll
+    for (int wv = 1; wv < NW; ++wv) mx = fmaxf(mx, mw[wv]);
+    float lsum = 0.f;
+    f32x4_t o = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int wv = 0; wv < NW; ++wv) {
+      const float a = fast_exp2(mw[wv] - mx);
+      lsum += lw[wv] * a;
+      o += ow[wv] * a;
+    }
+    if (pi.nchunks == 1) {
+      const float inv = 1.0f / lsum;
+      __builtin_nontemporal_store(o * inv, reinterpret_cast<f32x4_t*>(outp + h * DOUT + x));
+    } else {
+      __builtin_nontemporal_store(o, reinterpret_cast<f32x4_t*>(po + h * D + x));
       if (x == 0) {
         __builtin_nontemporal_store(mx, pml + h);
         __builtin_nontemporal_store(lsum, pml + p.Gp + h);
@@ -322,13 +392,14 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
   constexpr int NI = D / 32;               // MFMAs (k = 32) along the head dimension: 4 or 2
   constexpr int NJ = DV / 16;              // 16-column blocks of the output held here: 8 or 4
   constexpr int TILEB = kTileRows * ROWB;  // one K (or V) tile: 8 or 4 KB
+  touch_kernel_arguments();
   if (PROBES && p.debug_stage == 1) return;
-  // VS = 2: the grid holds the pairs twice, padded to a multiple of 8 so that a pair's two
-  // workgroups are 8k apart in dispatch order (workgroups go to the XCDs in turn)
-  const int npairs = p.B * p.Hkv, stride = (npairs + 7) & ~7;
-  const int vhalf = VS == 1 ? 0 : (int)blockIdx.y / stride;
-  if (VS != 1 && (int)blockIdx.y - vhalf * stride >= npairs) return;
-  const PairInfo pi = pair_info(p, VS == 1 ? (int)blockIdx.y : (int)blockIdx.y - vhalf * stride);
+  // grid: VS = 1: (chunk, KV head, slot); VS = 2: (KV head, slot, V half), the slots padded so
+  // that a pair's two workgroups are 8k apart in dispatch order (workgroups go to the XCDs in turn)
+  const int vhalf = VS == 1 ? 0 : (int)blockIdx.z;
+  if (VS != 1 && (int)blockIdx.y >= p.B) return;
+  const PairInfo pi = VS == 1 ? pair_info(p, (int)blockIdx.z, (int)blockIdx.y, (int)blockIdx.x)
+                              : pair_info(p, (int)blockIdx.y, (int)blockIdx.x, 0);
   if (!pi.live) return;
   if (PROBES && p.debug_stage == 2) { if (pi.L == 12345678) p.out[0] = 1.f; return; }
 
@@ -542,7 +613,24 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
   // denominators: sum the four k-blocks of each head
   l_run = rows_allreduce_sum(l_run);
 
-  // ---- merge the waves through LDS (the tile regions are free once everyone is here)
+  // ---- merge the waves through LDS.  Every wave leaves its (m, l, o) at the start of its own
+  // tile region, which nobody else touches, as soon as it is done: one barrier, and the early
+  // waves' writes do not wait for the late ones.
+  // (rows of DV floats would all start on the same LDS bank: a pitch of DV + 4 floats spreads the
+  // 128-bit writes of the up to eight heads over the banks)
+  constexpr int APITCH = DV + 4;
+  constexpr int WSTRIDE = (TILEB + VTILEB) / 4;                   // floats between two waves' regions
+  static_assert((8 * APITCH + 16 + 1) * 4 <= TILEB + VTILEB, "the partial fits the wave's region");
+  float* s_acc = reinterpret_cast<float*>(lds);                    // wave w: [8][APITCH] at w * WSTRIDE
+  float* s_m = s_acc + 8 * APITCH;                                 //         [8] behind it
+  float* s_l = s_m + 8;
+  int* s_last = reinterpret_cast<int*>(s_l + 8);                   // (in wave 0's region)
+  if (n < p.g) {
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+      *reinterpret_cast<f32x4_t*>(s_acc + wave * WSTRIDE + n * APITCH + 16 * j + 4 * kb) = O[j];
+    if (kb == 0) { s_m[wave * WSTRIDE + n] = m_run; s_l[wave * WSTRIDE + n] = l_run; }
+  }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // this wave's slab store has landed
   __syncthreads();
   // fused step: every workgroup of the sequence takes a ticket once it has stopped reading
@@ -553,21 +641,7 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
     asm volatile("global_atomic_add %0, %1, %2, off sc0"
                  : "=v"(ticket) : "v"(p.tickets + pi.s), "v"(one) : "memory");
   }
-  // (rows of DV floats would all start on the same LDS bank: a pitch of DV + 4 floats spreads the
-  // 128-bit writes of the up to eight heads over the banks)
-  constexpr int APITCH = DV + 4;
-  float* s_acc = reinterpret_cast<float*>(lds);                    // [wave][8][APITCH]
-  float* s_m = s_acc + NW * 8 * APITCH;                     // [wave][8]
-  float* s_l = s_m + NW * 8;
-  int* s_last = reinterpret_cast<int*>(s_l + NW * 8);
-  if (n < p.g) {
-#pragma unroll
-    for (int j = 0; j < NJ; ++j)
-      *reinterpret_cast<f32x4_t*>(s_acc + (wave * 8 + n) * APITCH + 16 * j + 4 * kb) = O[j];
-    if (kb == 0) { s_m[wave * 8 + n] = m_run; s_l[wave * 8 + n] = l_run; }
-  }
-  __syncthreads();
-  merge_waves_and_store<NW, DV, D, APITCH>(p, pi, s_m, s_l, s_acc, 8, vhalf * DV);
+  merge_waves_and_store4<NW, DV, D, APITCH>(p, pi, s_m, s_l, s_acc, WSTRIDE, vhalf * DV);
 
   // ---- the last workgroup of the sequence writes the beacon row and updates the tables
   if (!pi.update || (PROBES && p.debug_stage == 5)) return;
@@ -611,7 +685,8 @@ __global__ __launch_bounds__(256) void decode_valu_kernel(DecodeParams p) {
   constexpr int RB = D * ES;            // row bytes
   constexpr int ROWS_PER_PASS = kValuWaves * RPI * U;
 
-  const PairInfo pi = pair_info(p, blockIdx.y);
+  touch_kernel_arguments();
+  const PairInfo pi = pair_info(p, (int)blockIdx.z, (int)blockIdx.y, (int)blockIdx.x);
   if (!pi.live) return;
   const int L = pi.L, row_end = pi.row_end;
 
@@ -733,7 +808,7 @@ __global__ __launch_bounds__(256) void decode_valu_kernel(DecodeParams p) {
     }
   }
   __syncthreads();
-  merge_waves_and_store<kValuWaves, D>(p, pi, s_m, s_l, s_acc, G);
+  merge_waves_and_store<kValuWaves, D>(p, pi, s_m, s_l, s_acc, G, G * D);
 }
 
 // ---------------------------------------------------------------------------
@@ -752,7 +827,7 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeParams p) {
   // chunks are folded in order, sixteen at a time: the loads of a batch are independent and in
   // flight together (the partials come from memory, not from this compute unit's caches)
   constexpr int kBatch = 16;
-  for (int i = threadIdx.x; i < nout; i += blockDim.x) {
+  for (int i = threadIdx.x; i < nout; i += 256) {
     const int h = i / D;
     float mx = kNegBig, lsum = 0.f, o = 0.f;
     for (int ch0 = 0; ch0 < nchunks; ch0 += kBatch) {
@@ -860,12 +935,13 @@ static void launch_valu(const DecodeParams& p, int G, dim3 grid, hipStream_t st)
   }
 }
 
-// The LDS kernel needs 128 KB of dynamic LDS: opt in once per device.
+// The LDS kernel needs 128 KB of dynamic LDS: opt in once per device.  Two host threads that get
+// here together both set the (same) attributes; the flag only saves the later calls.
 static int32_t enable_big_lds() {
-  static bool done[64] = {};
+  static std::atomic<bool> done[64];
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return BC_ERR_HIP;
-  if (done[dev]) return BC_OK;
+  if (done[dev].load(std::memory_order_acquire)) return BC_OK;
   const void* kernels[13] = {reinterpret_cast<const void*>(decode_lds_kernel<false, 0, 128, 1, 8>),
                              reinterpret_cast<const void*>(decode_lds_kernel<false, 1, 128, 1, 8>),
                              reinterpret_cast<const void*>(decode_lds_kernel<true, 0, 128, 1, 8>),
@@ -885,7 +961,7 @@ static int32_t enable_big_lds() {
                    hipSuccess;
   if (!ok)
     return BC_ERR_HIP;
-  done[dev] = true;
+  done[dev].store(true, std::memory_order_release);
   return BC_OK;
 }
 
@@ -934,15 +1010,16 @@ static int32_t launch_attention(const bc_shape* shape, const bc_cache* cache, co
   p.debug_stage = g_variant >= 10 ? g_variant - 10 : 0;
 
   const int pairs = shape->B * shape->Hkv;
-  const dim3 grid(pl.max_chunks, pairs);
+  const dim3 grid(pl.max_chunks, shape->Hkv, shape->B);
   if (pl.lds) {
     const int32_t st = enable_big_lds();
     if (st != BC_OK) return st;
     // launches that cannot saturate the memory system are latency-bound: default cache policy
     const bool stream = (long)pairs * pl.max_chunks >= kStreamMinWorkgroups && g_variant != 4;
     // two workgroups per pair (each one half of the V columns) while that still fits the chip
-    const int pairs8 = (pairs + 7) & ~7;
-    const bool vsplit = shape->d == 128 && pl.max_chunks == 1 && 2 * pairs8 <= kLptMinPairs &&
+    int slots = shape->B;                   // padded until the pairs are a multiple of 8
+    while ((slots * shape->Hkv) & 7) ++slots;
+    const bool vsplit = shape->d == 128 && pl.max_chunks == 1 && 2 * slots * shape->Hkv <= kLptMinPairs &&
                         g_variant != 5;
     if (vsplit) {
       // K lines are read by both workgroups of a pair: streamed while the batch's K is small
@@ -957,7 +1034,7 @@ static int32_t launch_attention(const bc_shape* shape, const bc_cache* cache, co
                  : small_k     ? (w12 ? decode_lds_kernel<false, 1, 128, 2, 12> : decode_lds_kernel<false, 1, 128, 2, 8>)
                                : decode_lds_kernel<false, 2, 128, 2, 8>;
       const int nw = w12 ? kLdsWavesSplit : kLdsWaves;
-      kfn<<<dim3(1, 2 * pairs8), nw * 64, nw * 3 * kTileRows * 128, hs>>>(p);
+      kfn<<<dim3(shape->Hkv, slots, 2), nw * 64, nw * 3 * kTileRows * 128, hs>>>(p);
     } else if (shape->d == 128) {
       auto kfn = p.debug_stage
                      ? (stream ? decode_lds_kernel<true, 1, 128, 1, 8> : decode_lds_kernel<true, 0, 128, 1, 8>)
@@ -986,6 +1063,7 @@ static int32_t check_attention_args(const bc_shape* shape, const bc_cache* cache
   st = check_cache(cache);
   if (st != BC_OK) return st;
   if (!q || !out || !aligned16(q) || !aligned16(out)) return BC_ERR_ARG;
+  if (shape->B > 65535 || shape->Hkv > 65535) return BC_ERR_SHAPE;      // grid dimensions
   *pl = make_plan(shape, cache->max_cap, g_rows_per_wg, g_variant);
   if (g_variant == 2 && !pl->lds) return BC_ERR_SHAPE;
   if (!workspace || !aligned16(workspace) || workspace_bytes < pl->total()) return BC_ERR_WORKSPACE;
