@@ -72,7 +72,8 @@ typedef struct {
   int32_t Hkv;       /* KV heads; Hq % Hkv == 0, group g = Hq/Hkv <= 8            */
   int32_t d;         /* head dim: 64 or 128                                       */
   int32_t kv_dtype;  /* bc_dtype of q, k, v and the slabs; outputs are fp32       */
-  float scale;       /* softmax scale; the paper is silent, callers pass 1/sqrt(d) */
+  float scale;       /* softmax scale; the paper is silent, callers pass 1/sqrt(d).
+                      * Attention calls need a finite scale >= 0 (prefill: > 0), else BC_ERR_ARG */
 } bc_shape;
 
 typedef struct {

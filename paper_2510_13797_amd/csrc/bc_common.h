@@ -44,6 +44,11 @@ __device__ __forceinline__ HalfSelectors half_selectors() {
   asm volatile("" : "+s"(low), "+s"(high));                // opaque: stay in scalar registers
   return HalfSelectors{low, high};
 }
+// two floats -> one bf16 pair (round to nearest even, a in the low half)
+__device__ __forceinline__ uint32_t pack2_bf16(float a, float b) {
+  typedef __attribute__((ext_vector_type(2))) float f32x2_t_;
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t_{a, b}, bf16x2_t));
+}
 __device__ __forceinline__ float minus_half(float x, uint32_t hp, uint32_t selector) {
   return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, hp),
                                          __builtin_bit_cast(bf16x2_t, selector), x, false);
@@ -114,6 +119,11 @@ inline bool positive_finite(float x) {
   uint32_t u;
   __builtin_memcpy(&u, &x, sizeof(u));
   return u > 0u && u < 0x7f800000u;
+}
+inline bool nonnegative_finite(float x) {      // either zero included
+  uint32_t u;
+  __builtin_memcpy(&u, &x, sizeof(u));
+  return u < 0x7f800000u || u == 0x80000000u;
 }
 
 inline int32_t check_shape(const bc_shape* sh) {

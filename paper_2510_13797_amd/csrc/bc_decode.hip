@@ -24,6 +24,10 @@
 
 namespace bc {
 
+// Every sequence's ticket counter has a 128-byte line to itself: the workgroups of a launch finish
+// close together, and their atomics on a shared line would queue up behind each other.
+constexpr int kTicketStride = 32;
+
 struct DecodeParams {
   const char* k_slab;
   const char* v_slab;
@@ -47,7 +51,7 @@ struct DecodeParams {
   const char* new_v;
   const char* bk;
   const char* bv;
-  int32_t* tickets;    // [B], zero between launches
+  int32_t* tickets;    // [B] counters kTicketStride ints apart, zero between launches
   const int32_t* order;     // [B] dispatch order (workgroup i serves sequence order[i]) or null
   const int32_t* budget;   // [B] cap on nb + w (nullable), with
   uint8_t* live;           // [B] cleared when the cap is reached
@@ -345,11 +349,6 @@ __device__ __forceinline__ uint4 load16_stream(const char* p) {
 
 template <> __device__ __forceinline__ uint4 load16<true>(const char* p) { return load16_stream(p); }
 
-__device__ __forceinline__ uint32_t bf16_rne_bits(float x) {     // finite x only
-  const uint32_t u = __float_as_uint(x);
-  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-}
-
 // Swizzle of the 16-byte units of a tile row in LDS: unit u of row `row` lives at position
 // u ^ tile_swz<D>(row).  D = 128 (16 units per row): lds_swz.  D = 64 (8 units per row, two rows
 // per 256 bytes of banks): the 128-bit reads of one unit from the 8 rows {a, a+1, a+2, a+3, a+8,
@@ -405,6 +404,7 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, kb = lane >> 4;       // MFMA column / k-block of this lane
+  const HalfSelectors sel = half_selectors();
   const int64_t stream_off = (pi.base * p.Hkv + (int64_t)pi.kvh * pi.cap) * ROWB;
   const char* kbase = p.k_slab + stream_off;
   const char* vbase = p.v_slab + stream_off + vhalf * VROWB;
@@ -553,34 +553,48 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
         S[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qb[i], S[t], 0, 0, 0);
       }
     }
-    // lane (n, kb) now holds head n, keys trow0 + 8*kb + e, e = 4*t + r
+    // lane (n, kb) now holds head n, keys trow0 + 8*kb + e, e = 4*t + r.  The scores stay
+    // unscaled: the softmax scale (>= 0) enters through one fused multiply-add per key,
+    // p = 2^(s*qs - m).  Only a sequence's last tile has rows beyond its end; the tests for
+    // them sit behind a branch that is uniform over the wave.
+    const bool partial = trow0 + kTileRows > pi.row_end;
+    const int nvalid = pi.row_end - trow0 - 8 * kb;        // keys e < nvalid of this lane exist
     float sv[8];
-    float tmax = kNegBig;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const bool valid = trow0 + 8 * kb + e < pi.row_end;
-      sv[e] = valid ? S[e >> 2][e & 3] * p.qscale : kNegBig;
-      tmax = fmaxf(tmax, sv[e]);
+    for (int e = 0; e < 8; ++e) sv[e] = S[e >> 2][e & 3];
+    if (partial) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) sv[e] = e < nvalid ? sv[e] : kNegBig;
     }
+    float tmax = fmaxf(fmaxf(fmaxf(fmaxf(sv[0], sv[1]), sv[2]), fmaxf(fmaxf(sv[3], sv[4]), sv[5])),
+                       fmaxf(sv[6], sv[7]));
     tmax = rows_allreduce_max(tmax);
-    const float m_new = fmaxf(m_run, tmax);
-    const float alpha = fast_exp2(m_run - m_new);
-    m_run = m_new;
-    float psum = 0.f;
+    const float m_new = fmaxf(m_run, tmax * p.qscale);
+    float pe[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) pe[e] = fast_exp2(fmaf(sv[e], p.qscale, -m_new));
+    if (partial) {      // (with a scale of zero the fused form gives 1 for the missing keys, not 0)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) pe[e] = e < nvalid ? pe[e] : 0.f;
+    }
+    const float psum = ((pe[0] + pe[1]) + (pe[2] + pe[3])) + ((pe[4] + pe[5]) + (pe[6] + pe[7]));
+    // p = hi + lo with both parts bf16: the p.V product keeps ~16 bits of p
     uint32_t hi[4], lo[4];
 #pragma unroll
     for (int e = 0; e < 8; e += 2) {
-      float pa = (trow0 + 8 * kb + e < pi.row_end) ? fast_exp2(sv[e] - m_new) : 0.f;
-      float pb = (trow0 + 8 * kb + e + 1 < pi.row_end) ? fast_exp2(sv[e + 1] - m_new) : 0.f;
-      psum += pa + pb;
-      // p = hi + lo with both parts bf16: the p.V product keeps ~16 bits of p
-      const uint32_t ha = __float_as_uint(pa) & 0xffff0000u, hb = __float_as_uint(pb) & 0xffff0000u;
-      const uint32_t la = bf16_rne_bits(pa - __uint_as_float(ha));
-      const uint32_t lb = bf16_rne_bits(pb - __uint_as_float(hb));
-      hi[e >> 1] = (ha >> 16) | hb;
-      lo[e >> 1] = la | (lb << 16);
+      const uint32_t hp = pack2_bf16(pe[e], pe[e + 1]);
+      hi[e >> 1] = hp;
+      lo[e >> 1] = pack2_bf16(minus_half(pe[e], hp, sel.low), minus_half(pe[e + 1], hp, sel.high));
     }
-    l_run = l_run * alpha + psum;
+    // a wave's first tile finds empty accumulators: nothing to rescale
+    if (tile != wave) {
+      const float alpha = fast_exp2(m_run - m_new);
+      l_run *= alpha;
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) O[j] *= alpha;
+    }
+    m_run = m_new;
+    l_run += psum;
     const bf16x8_t phi = __builtin_bit_cast(bf16x8_t, make_uint4(hi[0], hi[1], hi[2], hi[3]));
     const bf16x8_t plo = __builtin_bit_cast(bf16x8_t, make_uint4(lo[0], lo[1], lo[2], lo[3]));
 
@@ -591,7 +605,6 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
       const int key0 = 8 * kb + (r >> 2);
 #pragma unroll
       for (int j = 0; j < NJ; ++j) {
-        O[j] *= alpha;
         const int u = 2 * j + ((r & 3) >> 1);
         const int sub = (r & 1) << 3;
         const int rowa = key0, rowb = key0 + 4;
@@ -639,7 +652,7 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
   if (pi.update && tid == 0) {
     const int one = 1;
     asm volatile("global_atomic_add %0, %1, %2, off sc0"
-                 : "=v"(ticket) : "v"(p.tickets + pi.s), "v"(one) : "memory");
+                 : "=v"(ticket) : "v"(p.tickets + pi.s * kTicketStride), "v"(one) : "memory");
   }
   merge_waves_and_store4<NW, DV, D, APITCH>(p, pi, s_m, s_l, s_acc, WSTRIDE, vhalf * DV);
 
@@ -664,7 +677,7 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
     }
   }
   if (tid == 0) {
-    p.tickets[pi.s] = 0;
+    p.tickets[pi.s * kTicketStride] = 0;
     p.nb_rw[pi.s] = pi.nb + (pi.evict_due ? 1 : 0);
     p.w_rw[pi.s] = pi.evict_due ? 0 : pi.w_att;
     if (p.budget && pi.nb + pi.w_att >= p.budget[pi.s]) p.live[pi.s] = 0;   // generation interrupted
@@ -917,7 +930,7 @@ static DecodePlan make_plan(const bc_shape* sh, int max_cap, int rows_override, 
   // otherwise); a forced chunk size on a large batch may use up to four.
   if (rows_override == kPlanForSizing) pl.max_chunks = npairs < 128 ? 64 : 4;
   const size_t pairs = (size_t)sh->B * sh->Hkv;
-  pl.tickets_bytes = align256((size_t)sh->B * 4);
+  pl.tickets_bytes = align256((size_t)sh->B * kTicketStride * 4);
   pl.part_n_bytes = align256(pairs * 4);
   pl.part_o_bytes = align256(pairs * pl.max_chunks * pl.Gp * sh->d * 4);
   pl.part_ml_bytes = align256(pairs * pl.max_chunks * 2 * pl.Gp * 4);
@@ -1064,6 +1077,7 @@ static int32_t check_attention_args(const bc_shape* shape, const bc_cache* cache
   if (st != BC_OK) return st;
   if (!q || !out || !aligned16(q) || !aligned16(out)) return BC_ERR_ARG;
   if (shape->B > 65535 || shape->Hkv > 65535) return BC_ERR_SHAPE;      // grid dimensions
+  if (!nonnegative_finite(shape->scale)) return BC_ERR_ARG;   // the kernels take maxima of unscaled scores
   *pl = make_plan(shape, cache->max_cap, g_rows_per_wg, g_variant);
   if (g_variant == 2 && !pl->lds) return BC_ERR_SHAPE;
   if (!workspace || !aligned16(workspace) || workspace_bytes < pl->total()) return BC_ERR_WORKSPACE;

@@ -90,6 +90,11 @@ def test_decode_entry_points_check_their_own_pointers_and_the_workspace():
     assert bc.bc_decode_attn(s, c, PTR, None, None, PTR, big, None) == bc.BC_ERR_ARG
     assert bc.bc_decode_attn(s, c, ODD, PTR, None, PTR, big, None) == bc.BC_ERR_ARG
     assert bc.bc_decode_attn(s, c, PTR, ODD, None, PTR, big, None) == bc.BC_ERR_ARG
+    # the softmax scale: finite and not negative (zero is the uniform-weights special case)
+    for bad in (-0.125, float("nan"), float("inf"), -float("inf")):
+        assert bc.bc_decode_attn(shape(scale=bad), c, PTR, PTR, None, PTR, big, None) == bc.BC_ERR_ARG
+        assert bc.bc_decode_step(shape(scale=bad), c, PTR, PTR, PTR, PTR, None, None, None, PTR, big,
+                                 None) == bc.BC_ERR_ARG
     # workspace: missing, misaligned, one byte short
     assert bc.bc_decode_attn(s, c, PTR, PTR, None, None, big, None) == bc.BC_ERR_WORKSPACE
     assert bc.bc_decode_attn(s, c, PTR, PTR, None, ODD, big, None) == bc.BC_ERR_WORKSPACE
