@@ -337,6 +337,34 @@ typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
 constexpr int kStreamPolicy = 2;
 constexpr int kStreamMinWorkgroups = 48;
 
+// One LDS-DMA instruction: every lane's 16 bytes at g go to LDS at lds_addr + 16 * lane (lds_addr
+// the same for all lanes; the instruction takes it from M0).  Written out by hand so that the
+// compiler does not know about it: it cannot tell which LDS reads such a load feeds and would
+// put a wait for ALL outstanding loads (the next tile's among them, and the fused step's ticket)
+// in front of the tile reads in every pass of the tile loop.  The waits are the explicit ones in
+// the kernel.  (M0 is not named as clobbered - the compiler reserves it and says so - and nothing
+// else in these kernels uses it.)
+template <bool STREAM>
+__device__ __forceinline__ void lds_dma16(const char* g, const char* lds_dst) {
+  const uint32_t a = __builtin_amdgcn_readfirstlane(
+      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)lds_dst);
+  if (STREAM)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt"
+                 : : "s"(a), "v"(g) : "memory");
+  else
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 : : "s"(a), "v"(g) : "memory");
+}
+
+// A 16-byte load into registers that the compiler does not count either (same reason).  The value
+// is there only after an explicit wait: nothing may read the result before it.
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+template <bool STREAM>
+__device__ __forceinline__ void load16_uncounted(u32x4_t& dst, const char* g) {
+  if (STREAM) asm volatile("global_load_dwordx4 %0, %1, off nt" : "=v"(dst) : "v"(g) : "memory");
+  else asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(g) : "memory");
+}
+
 template <bool STREAM> __device__ __forceinline__ uint4 load16(const char* p);
 template <> __device__ __forceinline__ uint4 load16<false>(const char* p) {
   return *reinterpret_cast<const uint4*>(p);
@@ -412,19 +440,26 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
   char* wv = wk + TILEB;
 
   // B operand of the score product: Q^T, column n = query head, k = head-dim index.
+  // The loads are written out by hand so that the compiler does not count them: it cannot tell
+  // the order in which they and the LDS-DMA loads complete, and would put a wait for ALL
+  // outstanding loads - the next tile's among them - in front of the first use in every pass of
+  // the tile loop.  They are the oldest loads of the wave: every wait for a first tile below (or
+  // the explicit one of a wave without tiles) covers them.
   bf16x8_t qb[NI];
 #pragma unroll
   for (int i = 0; i < NI; ++i) {
-    uint4 r = make_uint4(0u, 0u, 0u, 0u);
-    if (n < p.g)
-      r = *reinterpret_cast<const uint4*>(
-          p.q + ((int64_t)(pi.s * p.Hq + pi.kvh * p.g + n) * D + 32 * i + 8 * kb) * 2);
+    __attribute__((ext_vector_type(4))) uint32_t r = {0u, 0u, 0u, 0u};
+    if (n < p.g) {
+      const char* src = p.q + ((int64_t)(pi.s * p.Hq + pi.kvh * p.g + n) * D + 32 * i + 8 * kb) * 2;
+      asm volatile("global_load_dwordx4 %0, %1, off" : "+v"(r) : "v"(src) : "memory");
+    }
     qb[i] = __builtin_bit_cast(bf16x8_t, r);
   }
 
   // fused append: lanes 0..UPR-1 carry the new K row, the next VUPR lanes this workgroup's part
   // of the new V row (16 bytes each)
-  uint4 newrow = make_uint4(0u, 0u, 0u, 0u);
+  // (loaded by hand like the query above, for the same reason)
+  u32x4_t newrow_v = u32x4_t{0u, 0u, 0u, 0u};
   if (pi.new_row >= 0 && lane < UPR + VUPR) {
     const char* src;
     if constexpr (VS == 1)
@@ -433,8 +468,9 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
       src = lane < UPR
           ? p.new_k + (int64_t)(pi.s * p.Hkv + pi.kvh) * ROWB + (lane << 4)
           : p.new_v + (int64_t)(pi.s * p.Hkv + pi.kvh) * ROWB + vhalf * VROWB + ((lane - UPR) << 4);
-    newrow = *reinterpret_cast<const uint4*>(src);
+    asm volatile("global_load_dwordx4 %0, %1, off" : "+v"(newrow_v) : "v"(src) : "memory");
   }
+  const uint4 newrow = make_uint4(newrow_v.x, newrow_v.y, newrow_v.z, newrow_v.w);
   // rows the tile loads may touch: the resident rows that are already in the slab
   const int last_slab_row = max((pi.new_row >= 0 ? pi.new_row : pi.L) - 1, 0);
 
@@ -450,19 +486,18 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
   const int ntiles = (pi.row_end - pi.row0 + kTileRows - 1) / kTileRows;
   const int r4 = lane / UPR, pos = lane & (UPR - 1);   // row within a 1 KB load, unit within the row
   const int r4v = lane / VUPR, posv = lane & (VUPR - 1);   // the same for this workgroup's part of V
-  uint4 kreg[NDMA], vreg[VNDMA];
-#pragma unroll
-  for (int j = 0; j < NDMA; ++j) kreg[j] = make_uint4(0u, 0u, 0u, 0u);
-#pragma unroll
-  for (int j = 0; j < VNDMA; ++j) vreg[j] = make_uint4(0u, 0u, 0u, 0u);
+  // (not initialised, and written at one place only, the top of the tile loop: the loads are
+  // invisible to the compiler, so a register-to-register copy between a load and its wait - such
+  // as one that joins two definitions - would copy what is not there yet)
+  u32x4_t kreg[NDMA], vreg[VNDMA];
 #define BC_LOAD_TILE_REGS(TROW0)                                              \
   _Pragma("unroll") for (int j = 0; j < NDMA; ++j) {                          \
     const int grow_ = min((TROW0) + RPI * j + r4, last_slab_row);             \
     const int64_t goff_ = (int64_t)grow_ * ROWB + (pos << 4);                 \
-    kreg[j] = load16<KSTREAM>(kbase + goff_);                                 \
+    load16_uncounted<KSTREAM>(kreg[j], kbase + goff_);                        \
     if (j < VNDMA) {                                                          \
       const int vrow_ = min((TROW0) + VRPI * j + r4v, last_slab_row);         \
-      vreg[j] = load16<VSTREAM>(vbase + (VS == 1 ? goff_ : (int64_t)vrow_ * ROWB + (posv << 4)));  \
+      load16_uncounted<VSTREAM>(vreg[j], vbase + (VS == 1 ? goff_ : (int64_t)vrow_ * ROWB + (posv << 4)));  \
     }                                                                         \
   }
   if (wave < ntiles) {
@@ -473,40 +508,55 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
       const int row = RPI * j + r4;
       const int grow = min(trow0 + row, last_slab_row);     // stay inside the slab rows
       const int64_t goff = (int64_t)grow * ROWB + ((pos ^ tile_swz<D>(row)) << 4);
-      __builtin_amdgcn_global_load_lds((global_void_t*)(kbase + goff),
-                                       (lds_void_t*)(wk + j * 1024), 16, 0, KSTREAM ? kStreamPolicy : 0);
+      lds_dma16<KSTREAM>(kbase + goff, wk + j * 1024);
       if (j < VNDMA) {
         const int vrow = VRPI * j + r4v;
         const int vgrow = min(trow0 + vrow, last_slab_row);
         const int64_t vgoff = VS == 1 ? goff : (int64_t)vgrow * ROWB + ((posv ^ tile_swz<DV>(vrow)) << 4);
-        __builtin_amdgcn_global_load_lds((global_void_t*)(vbase + vgoff),
-                                         (lds_void_t*)(wv + j * 1024), 16, 0, VSTREAM ? kStreamPolicy : 0);
+        lds_dma16<VSTREAM>(vbase + vgoff, wv + j * 1024);
       }
     }
-    if (wave + NW < ntiles) { BC_LOAD_TILE_REGS(trow0 + NW * kTileRows) }
+  }
+  // Fused step: every wave of every workgroup of the sequence takes a ticket as soon as its last
+  // load from the slab has landed (the tables were read at the start); whoever draws the last one
+  // may write the beacon row and update the tables.  The answer is only looked at after the wave
+  // merge, so the atomic's round trip (about a microsecond) hides behind the remaining compute.
+  int ticket = -1;
+#define BC_TAKE_TICKET()                                                                    \
+  if (pi.update && lane == 0) {                                                             \
+    const int one_ = 1;                                                                     \
+    asm volatile("global_atomic_add %0, %1, %2, off sc0"                                    \
+                 : "=v"(ticket) : "v"(p.tickets + pi.s * kTicketStride), "v"(one_) : "memory"); \
+  }
+  if (wave >= ntiles) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the query loads, before their registers are reused
+    BC_TAKE_TICKET()
   }
   for (int tile = wave; tile < ntiles; tile += NW) {
     const int trow0 = pi.row0 + tile * kTileRows;
+    if (tile != wave) {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // the register tile has arrived
+#pragma unroll
+      for (int j = 0; j < NDMA; ++j) {
+        const int row = RPI * j + r4;
+        const int o = row * ROWB + ((pos ^ tile_swz<D>(row)) << 4);
+        *reinterpret_cast<u32x4_t*>(wk + o) = kreg[j];
+        if (j < VNDMA) {
+          const int vrow = VRPI * j + r4v;
+          *reinterpret_cast<u32x4_t*>(wv + (VS == 1 ? o : vrow * VROWB + ((posv ^ tile_swz<DV>(vrow)) << 4))) = vreg[j];
+        }
+      }
+    }
+    // the next tile of this wave goes to registers while this one is in use
+    if (tile + NW < ntiles) { BC_LOAD_TILE_REGS(trow0 + NW * kTileRows) }
     if (tile == wave) {
       // the LDS-DMA loads have landed once at most the register loads behind them are pending
       if (wave + NW >= ntiles) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       else if (NDMA + VNDMA == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
       else if (NDMA + VNDMA == 12) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
       else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-    } else {
-#pragma unroll
-      for (int j = 0; j < NDMA; ++j) {
-        const int row = RPI * j + r4;
-        const int o = row * ROWB + ((pos ^ tile_swz<D>(row)) << 4);
-        *reinterpret_cast<uint4*>(wk + o) = kreg[j];
-        if (j < VNDMA) {
-          const int vrow = VRPI * j + r4v;
-          *reinterpret_cast<uint4*>(wv + (VS == 1 ? o : vrow * VROWB + ((posv ^ tile_swz<DV>(vrow)) << 4))) = vreg[j];
-        }
-      }
-      if (tile + NW < ntiles) { BC_LOAD_TILE_REGS(trow0 + NW * kTileRows) }
     }
-    if (PROBES && p.debug_stage == 3) continue;
+    if (PROBES && p.debug_stage == 3) { if (tile + NW >= ntiles) { BC_TAKE_TICKET() } continue; }
 
     if (pi.new_row >= trow0 && pi.new_row < trow0 + kTileRows) {
       // the appended row is not in the slab yet: place it in the tile, store it for later
@@ -537,6 +587,10 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
       for (int rr = ra + 1 + r4v; rr < kTileRows; rr += VRPI)
         *reinterpret_cast<uint4*>(wv + rr * VROWB + (posv << 4)) = make_uint4(0u, 0u, 0u, 0u);
     }
+    // this wave's last tile is in LDS (a register tile has been waited for by its copy above) and
+    // the appended row, whose load the compiler waits for just above, is out of the way: nothing
+    // between here and the end of the kernel waits for memory, so the ticket's answer can stay out
+    if (tile + NW >= ntiles) { BC_TAKE_TICKET() }
 
     // ---- scores, transposed: S^T[key][head] = K . Q^T.  Row m of sub-tile t is key
     //      8*(m/4) + 4*t + m%4, so that a lane ends up with 8 consecutive keys of one head.
@@ -623,6 +677,7 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
 
   if (PROBES && (p.debug_stage == 3 || p.debug_stage == 4)) { if (m_run == 123.f) p.out[0] = l_run + O[0][0]; return; }
 #undef BC_LOAD_TILE_REGS
+#undef BC_TAKE_TICKET
   // denominators: sum the four k-blocks of each head
   l_run = rows_allreduce_sum(l_run);
 
@@ -637,36 +692,22 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
   float* s_acc = reinterpret_cast<float*>(lds);                    // wave w: [8][APITCH] at w * WSTRIDE
   float* s_m = s_acc + 8 * APITCH;                                 //         [8] behind it
   float* s_l = s_m + 8;
-  int* s_last = reinterpret_cast<int*>(s_l + 8);                   // (in wave 0's region)
   if (n < p.g) {
 #pragma unroll
     for (int j = 0; j < NJ; ++j)
       *reinterpret_cast<f32x4_t*>(s_acc + wave * WSTRIDE + n * APITCH + 16 * j + 4 * kb) = O[j];
     if (kb == 0) { s_m[wave * WSTRIDE + n] = m_run; s_l[wave * WSTRIDE + n] = l_run; }
   }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // this wave's slab store has landed
   __syncthreads();
-  // fused step: every workgroup of the sequence takes a ticket once it has stopped reading
-  // the slab; the answer is only needed at the very end, so its latency hides behind the merge
-  int ticket = 0;
-  if (pi.update && tid == 0) {
-    const int one = 1;
-    asm volatile("global_atomic_add %0, %1, %2, off sc0"
-                 : "=v"(ticket) : "v"(p.tickets + pi.s * kTicketStride), "v"(one) : "memory");
-  }
   merge_waves_and_store4<NW, DV, D, APITCH>(p, pi, s_m, s_l, s_acc, WSTRIDE, vhalf * DV);
 
-  // ---- the last workgroup of the sequence writes the beacon row and updates the tables
+  // ---- the wave that drew the sequence's last ticket writes the beacon row and updates the tables
   if (!pi.update || (PROBES && p.debug_stage == 5)) return;
-  if (tid == 0) {
-    asm volatile("s_waitcnt vmcnt(0)" : "+v"(ticket) : : "memory");   // the ticket has arrived
-    *s_last = (ticket == p.Hkv * pi.nchunks * VS - 1) ? 1 : 0;
-  }
-  __syncthreads();
-  if (!*s_last) return;
+  asm volatile("s_waitcnt vmcnt(0)" : "+v"(ticket) : : "memory");     // the ticket has arrived
+  if (__builtin_amdgcn_readfirstlane(ticket) != p.Hkv * pi.nchunks * VS * NW - 1) return;
   if (pi.evict_due) {
     const int n16 = p.Hkv * UPR;                   // 16-byte units of one K (or V) entry
-    for (int i = tid; i < 2 * n16; i += NW * 64) {
+    for (int i = lane; i < 2 * n16; i += 64) {
       const int which = i >= n16, r = which ? i - n16 : i;
       const int h = r / UPR, u = r & (UPR - 1);
       const char* src = (which ? p.bv : p.bk) + (int64_t)(pi.s * p.Hkv + h) * ROWB + (u << 4);
@@ -676,7 +717,7 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
       *reinterpret_cast<uint4*>(slab + dst) = *reinterpret_cast<const uint4*>(src);
     }
   }
-  if (tid == 0) {
+  if (lane == 0) {
     p.tickets[pi.s * kTicketStride] = 0;
     p.nb_rw[pi.s] = pi.nb + (pi.evict_due ? 1 : 0);
     p.w_rw[pi.s] = pi.evict_due ? 0 : pi.w_att;
