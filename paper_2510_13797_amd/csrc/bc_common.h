@@ -54,6 +54,35 @@ __device__ __forceinline__ float minus_half(float x, uint32_t hp, uint32_t selec
                                          __builtin_bit_cast(bf16x2_t, selector), x, false);
 }
 
+// One LDS-DMA instruction: every lane's 16 bytes at g go to LDS at lds_addr + 16 * lane (lds_addr
+// the same for all lanes; the instruction takes it from M0).  Written out by hand so that the
+// compiler does not know about it: it cannot tell which LDS reads such a load feeds and would
+// put a wait for ALL outstanding loads (the next tiles' among them, and the fused decode step's
+// ticket) in front of the tile reads in every pass of a tile loop.  The waits are the explicit ones in
+// the kernel.  (M0 is not named as clobbered - the compiler reserves it and says so - and nothing
+// else in these kernels uses it.)
+template <bool STREAM>
+__device__ __forceinline__ void lds_dma16(const char* g, const char* lds_dst) {
+  const uint32_t a = __builtin_amdgcn_readfirstlane(
+      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)lds_dst);
+  if (STREAM)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt"
+                 : : "s"(a), "v"(g) : "memory");
+  else
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 : : "s"(a), "v"(g) : "memory");
+}
+
+// A 16-byte load into registers that the compiler does not count either (same reason).  The value
+// is there only after an explicit wait: nothing may read the result before it.
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+template <bool STREAM>
+__device__ __forceinline__ void load16_uncounted(u32x4_t& dst, const char* g) {
+  if (STREAM) asm volatile("global_load_dwordx4 %0, %1, off nt" : "=v"(dst) : "v"(g) : "memory");
+  else asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(g) : "memory");
+}
+// (tests/test_isa_guards.py checks the generated code for reads of such a register before a wait)
+
 // 16 bytes of a row -> floats
 __device__ __forceinline__ void unpack16(const uint4& r, float (&f)[4], float) {
   f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y);

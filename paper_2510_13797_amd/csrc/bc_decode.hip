@@ -337,34 +337,6 @@ typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
 constexpr int kStreamPolicy = 2;
 constexpr int kStreamMinWorkgroups = 48;
 
-// One LDS-DMA instruction: every lane's 16 bytes at g go to LDS at lds_addr + 16 * lane (lds_addr
-// the same for all lanes; the instruction takes it from M0).  Written out by hand so that the
-// compiler does not know about it: it cannot tell which LDS reads such a load feeds and would
-// put a wait for ALL outstanding loads (the next tile's among them, and the fused step's ticket)
-// in front of the tile reads in every pass of the tile loop.  The waits are the explicit ones in
-// the kernel.  (M0 is not named as clobbered - the compiler reserves it and says so - and nothing
-// else in these kernels uses it.)
-template <bool STREAM>
-__device__ __forceinline__ void lds_dma16(const char* g, const char* lds_dst) {
-  const uint32_t a = __builtin_amdgcn_readfirstlane(
-      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)lds_dst);
-  if (STREAM)
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt"
-                 : : "s"(a), "v"(g) : "memory");
-  else
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                 : : "s"(a), "v"(g) : "memory");
-}
-
-// A 16-byte load into registers that the compiler does not count either (same reason).  The value
-// is there only after an explicit wait: nothing may read the result before it.
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
-template <bool STREAM>
-__device__ __forceinline__ void load16_uncounted(u32x4_t& dst, const char* g) {
-  if (STREAM) asm volatile("global_load_dwordx4 %0, %1, off nt" : "=v"(dst) : "v"(g) : "memory");
-  else asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(g) : "memory");
-}
-
 template <bool STREAM> __device__ __forceinline__ uint4 load16(const char* p);
 template <> __device__ __forceinline__ uint4 load16<false>(const char* p) {
   return *reinterpret_cast<const uint4*>(p);
