@@ -87,7 +87,20 @@ typedef struct {
   int32_t *err;          /* [1] sticky error bits                                 */
   int32_t max_cap;       /* HOST value: max_s cap[s]; sizes grids and workspace   */
   const int32_t *order;  /* [B] optional dispatch order, see bc_sort_by_length(); or NULL */
+  int32_t uniform_P;     /* HOST values, optional promise about the layout, 0 = none: see below */
+  int32_t uniform_cap;
 } bc_cache;
+
+/* Promise of a uniform layout (not in the paper: a latency aid for batches of equal prompt length,
+ * the shape of its evaluation rollouts).  With uniform_P > 0 the caller states that the slabs hold
+ * B * Hkv * uniform_cap rows, that uniform_cap == max_cap, and that (normally) every sequence has
+ * P[s] == uniform_P, cap[s] == uniform_cap and base[s] == s * uniform_cap.  The bf16 decode calls
+ * then request the prompt rows - which never change and are always resident - from those addresses
+ * while the tables are still on their way, about half a microsecond earlier.  Every sequence's
+ * tables are compared with the promise afterwards; where they differ (say after bc_cache_admit
+ * gave a slot another prompt length) the rows are simply requested again from the right place, so
+ * results never depend on the promise - only the addresses it implies must lie inside the slabs.
+ * uniform_P > 0 with uniform_cap != max_cap or uniform_P > uniform_cap is BC_ERR_ARG. */
 
 /* Note on strides: all sequences are streamed at once, each KV head from base + kvh * cap rows.
  * When cap * d * (bytes per element) is close to a multiple of 512 KiB the concurrent streams
@@ -295,7 +308,8 @@ int32_t bc_diag_stream_read(const void *src, size_t bytes, int32_t workgroups, u
  * plain-ALU kernel, 2 = the LDS/MFMA kernel or BC_ERR_SHAPE, 3 = automatic but ignoring
  * cache->order, 4 = automatic but with the default
  * cache policy for the K/V loads of large launches, 5 = automatic but always one workgroup per
- * (sequence, KV head) pair; 11..15 = timing probes that leave
+ * (sequence, KV head) pair, 6 = automatic but ignoring the uniform-layout promise; 11..15 = timing
+ * probes that leave
  * the LDS/MFMA kernel after a given stage (outputs are then meaningless). */
 void bc_set_decode_tuning(int32_t rows_per_workgroup, int32_t variant);
 

@@ -43,7 +43,8 @@ class bc_cache(C.Structure):
     _fields_ = [("k_slab", C.c_void_p), ("v_slab", C.c_void_p), ("base", C.c_void_p),
                 ("cap", C.c_void_p), ("P", C.c_void_p), ("c", C.c_void_p),
                 ("nb", C.c_void_p), ("w", C.c_void_p), ("err", C.c_void_p),
-                ("max_cap", C.c_int32), ("order", C.c_void_p)]
+                ("max_cap", C.c_int32), ("order", C.c_void_p),
+                ("uniform_P", C.c_int32), ("uniform_cap", C.c_int32)]
 
 
 class BcError(RuntimeError):
@@ -286,7 +287,13 @@ class Runtime:
         self.cache = bc_cache(self.k_slab.data_ptr(), self.v_slab.data_ptr(), self.base.data_ptr(),
                               self.cap.data_ptr(), self.P.data_ptr(), self.c.data_ptr(),
                               self.nb.data_ptr(), self.w.data_ptr(), self.err.data_ptr(),
-                              self.max_cap, None)
+                              self.max_cap, None, 0, 0)
+        # equal prompt lengths and capacities (slabs laid out back to back): tell the library, which
+        # may then request prompt rows before it has read the tables
+        if (self.P_host == self.P_host[0]).all() and (self.cap_host == self.cap_host[0]).all() \
+                and 0 < int(self.P_host[0]) <= int(self.cap_host[0]):
+            self.cache.uniform_P = int(self.P_host[0])
+            self.cache.uniform_cap = int(self.cap_host[0])
         self.order = None
         self.ws_bytes = int(bc_decode_workspace_bytes(self.shape, self.max_cap))
         self.ws = torch.empty(max(self.ws_bytes, 16), dtype=torch.uint8, device=device)

@@ -170,6 +170,8 @@ inline int32_t check_cache(const bc_cache* c) {
     return BC_ERR_ARG;
   if (!aligned16(c->k_slab) || !aligned16(c->v_slab)) return BC_ERR_ARG;
   if (c->max_cap < 1) return BC_ERR_ARG;
+  if (c->uniform_P < 0 || c->uniform_cap < 0) return BC_ERR_ARG;
+  if (c->uniform_P > 0 && (c->uniform_cap != c->max_cap || c->uniform_P > c->uniform_cap)) return BC_ERR_ARG;
   return BC_OK;
 }
 

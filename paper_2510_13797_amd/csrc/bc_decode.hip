@@ -57,6 +57,7 @@ struct DecodeParams {
   uint8_t* live;           // [B] cleared when the cap is reached
   int32_t beacon_row;  // the fused row is the beacon closing a full window (bk = new_k, bv = new_v)
   int32_t B;
+  int32_t spec_P, spec_cap;   // bc_cache::uniform_P, uniform_cap (0 = no promise)
   int32_t debug_stage; // experiments only: leave the kernel early (0 = run everything)
   int32_t Hq, Hkv, g;  // g = real group size
   int32_t Gp;          // padded group size of the partial layout
@@ -136,7 +137,10 @@ __device__ __forceinline__ void touch_kernel_arguments() {
 // slot: the sequence's index, or its rank in the dispatch order when there is one.  The grid
 // carries (chunk, KV head, slot) in its three dimensions, so that nothing has to be divided
 // before the tables can be requested; all of them are requested together.
-__device__ __forceinline__ PairInfo pair_info(const DecodeParams& p, int slot, int kvh, int chunk) {
+struct NoEarlyWork { __device__ __forceinline__ void operator()() const {} };
+template <typename F = NoEarlyWork>
+__device__ __forceinline__ PairInfo pair_info(const DecodeParams& p, int slot, int kvh, int chunk,
+                                              const F& while_tables_travel = F()) {
   PairInfo pi;
   int act, w;
   int s = slot;
@@ -148,12 +152,22 @@ __device__ __forceinline__ PairInfo pair_info(const DecodeParams& p, int slot, i
   }
   pi.s = s;
   pi.kvh = kvh;
-  pi.P = p.P[pi.s];
-  pi.nb = p.nb[pi.s];
-  w = p.w[pi.s];
-  pi.cap = p.cap[pi.s];
-  pi.base = p.base[pi.s];
-  pi.c = p.c[pi.s];
+  // The six table entries travel through the scalar cache, requested by hand: their counter is
+  // not the vector loads' one, so work started in the meantime (the first tile, when the caller
+  // has promised the slab geometry) does not have to be back before they are.
+  {
+    int32_t tP, tnb, tw, tcap, tc;
+    int64_t tbase;
+    asm volatile("s_load_dword %0, %1, 0x0" : "=s"(tP) : "s"(p.P + pi.s) : "memory");
+    asm volatile("s_load_dword %0, %1, 0x0" : "=s"(tnb) : "s"(p.nb + pi.s) : "memory");
+    asm volatile("s_load_dword %0, %1, 0x0" : "=s"(tw) : "s"(p.w + pi.s) : "memory");
+    asm volatile("s_load_dword %0, %1, 0x0" : "=s"(tcap) : "s"(p.cap + pi.s) : "memory");
+    asm volatile("s_load_dwordx2 %0, %1, 0x0" : "=s"(tbase) : "s"(p.base + pi.s) : "memory");
+    asm volatile("s_load_dword %0, %1, 0x0" : "=s"(tc) : "s"(p.c + pi.s) : "memory");
+    while_tables_travel();
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(tP), "+s"(tnb), "+s"(tw), "+s"(tcap), "+s"(tbase), "+s"(tc) : : "memory");
+    pi.P = tP; pi.nb = tnb; w = tw; pi.cap = tcap; pi.base = tbase; pi.c = tc;
+  }
   act = p.active ? p.active[pi.s] : 1;
   if (bad_order) {
     if (chunk == 0 && threadIdx.x == 0) atomicOr(p.err, BC_ERRBIT_STATE);
@@ -397,19 +411,48 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
   // that a pair's two workgroups are 8k apart in dispatch order (workgroups go to the XCDs in turn)
   const int vhalf = VS == 1 ? 0 : (int)blockIdx.z;
   if (VS != 1 && (int)blockIdx.y >= p.B) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r4 = lane / UPR, pos = lane & (UPR - 1);   // row within a 1 KB load, unit within the row
+  const int r4v = lane / VUPR, posv = lane & (VUPR - 1);   // the same for this workgroup's part of V
+  char* wk = lds + wave * (TILEB + VTILEB);
+  char* wv = wk + TILEB;
+  // Prompt rows never change and are always resident.  When the caller has promised the slab
+  // geometry (every sequence: P = spec_P, cap = spec_cap, base = index * spec_cap), a wave whose
+  // first tile lies inside the prompt requests it before the tables are back.
+  bool early_tile = false;
+  auto request_prompt_tile = [&]() {
+    if (p.spec_P > 0 && p.order == nullptr && p.max_chunks == 1 && (wave + 1) * kTileRows <= p.spec_P) {
+      const int s_ = VS == 1 ? (int)blockIdx.z : (int)blockIdx.y;
+      const int kvh_ = VS == 1 ? (int)blockIdx.y : (int)blockIdx.x;
+      const int64_t off_ = ((int64_t)s_ * p.spec_cap * p.Hkv + (int64_t)kvh_ * p.spec_cap) * ROWB;
+      const char* kb_ = p.k_slab + off_;
+      const char* vb_ = p.v_slab + off_ + vhalf * VROWB;
+#pragma unroll
+      for (int j = 0; j < NDMA; ++j) {
+        const int row = RPI * j + r4;
+        const int64_t goff = (int64_t)(wave * kTileRows + row) * ROWB + ((pos ^ tile_swz<D>(row)) << 4);
+        lds_dma16<KSTREAM>(kb_ + goff, wk + j * 1024);
+        if (j < VNDMA) {
+          const int vrow = VRPI * j + r4v;
+          const int64_t vgoff = (int64_t)(wave * kTileRows + vrow) * ROWB + ((posv ^ tile_swz<DV>(vrow)) << 4);
+          lds_dma16<VSTREAM>(vb_ + vgoff, wv + j * 1024);
+        }
+      }
+      early_tile = true;
+    }
+  };
   const PairInfo pi = VS == 1 ? pair_info(p, (int)blockIdx.z, (int)blockIdx.y, (int)blockIdx.x)
-                              : pair_info(p, (int)blockIdx.y, (int)blockIdx.x, 0);
-  if (!pi.live) return;
+                              : pair_info(p, (int)blockIdx.y, (int)blockIdx.x, 0, request_prompt_tile);
+  if (!pi.live) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); return; }
+  if (early_tile && (pi.P != p.spec_P || pi.cap != p.spec_cap || pi.base != (int64_t)pi.s * p.spec_cap))
+    early_tile = false;      // the promise does not hold here: the tile is requested again below
   if (PROBES && p.debug_stage == 2) { if (pi.L == 12345678) p.out[0] = 1.f; return; }
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, kb = lane >> 4;       // MFMA column / k-block of this lane
   const HalfSelectors sel = half_selectors();
   const int64_t stream_off = (pi.base * p.Hkv + (int64_t)pi.kvh * pi.cap) * ROWB;
   const char* kbase = p.k_slab + stream_off;
   const char* vbase = p.v_slab + stream_off + vhalf * VROWB;
-  char* wk = lds + wave * (TILEB + VTILEB);
-  char* wv = wk + TILEB;
 
   // B operand of the score product: Q^T, column n = query head, k = head-dim index.
   // The loads are written out by hand so that the compiler does not count them: it cannot tell
@@ -456,8 +499,6 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
   // flight from the start.  Afterwards: copy the register tile to LDS, request the next tile
   // into the freed registers, compute - one tile always in flight behind the one in use.
   const int ntiles = (pi.row_end - pi.row0 + kTileRows - 1) / kTileRows;
-  const int r4 = lane / UPR, pos = lane & (UPR - 1);   // row within a 1 KB load, unit within the row
-  const int r4v = lane / VUPR, posv = lane & (VUPR - 1);   // the same for this workgroup's part of V
   // (not initialised, and written at one place only, the top of the tile loop: the loads are
   // invisible to the compiler, so a register-to-register copy between a load and its wait - such
   // as one that joins two definitions - would copy what is not there yet)
@@ -472,7 +513,7 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
       load16_uncounted<VSTREAM>(vreg[j], vbase + (VS == 1 ? goff_ : (int64_t)vrow_ * ROWB + (posv << 4)));  \
     }                                                                         \
   }
-  if (wave < ntiles) {
+  if (wave < ntiles && !early_tile) {
     // ---- HBM -> LDS: NDMA + NDMA instructions, each RPI whole rows (1 KB), 16-byte units XOR-swizzled
     const int trow0 = pi.row0 + wave * kTileRows;
 #pragma unroll
@@ -1034,6 +1075,8 @@ static int32_t launch_attention(const bc_shape* shape, const bc_cache* cache, co
   p.max_chunks = pl.max_chunks;
   p.qscale = shape->scale * kLog2e;
   p.debug_stage = g_variant >= 10 ? g_variant - 10 : 0;
+  p.spec_P = g_variant == 6 ? 0 : cache->uniform_P;
+  p.spec_cap = cache->uniform_cap;
 
   const int pairs = shape->B * shape->Hkv;
   const dim3 grid(pl.max_chunks, shape->Hkv, shape->B);

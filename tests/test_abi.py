@@ -30,8 +30,9 @@ def test_struct_layouts_match_header():
     from paper_2510_13797_amd import bc
     assert C.sizeof(bc.bc_shape) == 24
     assert bc.bc_shape.scale.offset == 20
-    assert C.sizeof(bc.bc_cache) == 88 and bc.bc_cache.max_cap.offset == 72
+    assert C.sizeof(bc.bc_cache) == 96 and bc.bc_cache.max_cap.offset == 72
     assert bc.bc_cache.order.offset == 80
+    assert bc.bc_cache.uniform_P.offset == 88 and bc.bc_cache.uniform_cap.offset == 92
 
 
 def test_header_is_plain_c_and_agrees_with_the_binding(tmp_path):
@@ -49,9 +50,10 @@ def test_header_is_plain_c_and_agrees_with_the_binding(tmp_path):
     src.write_text(
         '#include <stdio.h>\n#include <stddef.h>\n#include "bc.h"\n'
         'int main(void) {\n'
-        '  printf("%zu %zu %zu %zu %zu %zu %zu\\n", sizeof(bc_shape), offsetof(bc_shape, scale),\n'
+        '  printf("%zu %zu %zu %zu %zu %zu %zu %zu %zu\\n", sizeof(bc_shape), offsetof(bc_shape, scale),\n'
         '         sizeof(bc_cache), offsetof(bc_cache, base), offsetof(bc_cache, err),\n'
-        '         offsetof(bc_cache, max_cap), offsetof(bc_cache, order));\n'
+        '         offsetof(bc_cache, max_cap), offsetof(bc_cache, order),\n'
+        '         offsetof(bc_cache, uniform_P), offsetof(bc_cache, uniform_cap));\n'
         '  return 0;\n}\n')
     exe = tmp_path / "layout"
     subprocess.check_call([cc, "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"),
@@ -59,7 +61,7 @@ def test_header_is_plain_c_and_agrees_with_the_binding(tmp_path):
     got = [int(x) for x in subprocess.check_output([str(exe)]).split()]
     want = [C.sizeof(bc.bc_shape), bc.bc_shape.scale.offset, C.sizeof(bc.bc_cache),
             bc.bc_cache.base.offset, bc.bc_cache.err.offset, bc.bc_cache.max_cap.offset,
-            bc.bc_cache.order.offset]
+            bc.bc_cache.order.offset, bc.bc_cache.uniform_P.offset, bc.bc_cache.uniform_cap.offset]
     assert got == want, (got, want)
 
 

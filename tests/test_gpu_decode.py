@@ -165,6 +165,27 @@ def test_fused_step_bf16_every_step(dev, c, P, d):
     rollout(wl, rt, oc, 150, steps, steps, use_step_call=True)
 
 
+@pytest.mark.parametrize("promise", ["as built", "none", "prompt too long", "prompt too short"])
+@pytest.mark.parametrize("Hkv,d", [(2, 128), (8, 128), (2, 64)])
+def test_uniform_layout_promise_is_only_a_hint(dev, promise, Hkv, d):
+    # equal prompt lengths and capacities: the binding states the layout and the kernel requests prompt
+    # rows before it has read the tables; a promise that names another prompt length must not change
+    # any result (the rows are requested again); Hkv = 8 takes the one-workgroup-per-pair kernel
+    B, P, G = 40, 100, 60
+    wl = W.Workload("promise", 97, B, 2 * Hkv, Hkv, d, "bf16", np.full(B, P, np.int32),
+                    np.full(B, G, np.int32), np.full(B, 8, np.int32))
+    cap = np.full(B, 176, np.int32)
+    rt, oc = make(wl, dev, cap)
+    assert rt.cache.uniform_P == P and rt.cache.uniform_cap == 176
+    if promise == "none":
+        rt.cache.uniform_P = rt.cache.uniform_cap = 0
+    elif promise == "prompt too long":
+        rt.cache.uniform_P = 160           # rows 100..159 are not all resident yet: unwritten slab rows
+    elif promise == "prompt too short":
+        rt.cache.uniform_P = 64
+    rollout(wl, rt, oc, G, (1, 2, 8, 9, 33, 60), (8, 60), use_step_call=True)
+
+
 @pytest.mark.parametrize("Hq,Hkv,dtype,d", [(1, 1, "bf16", 128), (4, 2, "bf16", 128), (3, 1, "bf16", 128),
                                              (10, 2, "bf16", 128), (7, 1, "bf16", 128), (16, 2, "bf16", 128),
                                              (8, 1, "f32", 64), (6, 2, "bf16", 64), (5, 1, "f32", 128),

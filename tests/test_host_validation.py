@@ -19,7 +19,7 @@ def shape(B=2, Hq=4, Hkv=1, d=64, dtype=bc.BC_F32, scale=0.125):
 
 def cache(**kw):
     f = dict(k_slab=PTR, v_slab=PTR, base=PTR, cap=PTR, P=PTR, c=PTR, nb=PTR, w=PTR, err=PTR,
-             max_cap=64, order=None)
+             max_cap=64, order=None, uniform_P=0, uniform_cap=0)
     f.update(kw)
     return bc.bc_cache(**f)
 
@@ -72,6 +72,11 @@ def test_a_missing_cache_table_is_an_argument_error_everywhere(field):
 def test_misaligned_slabs_and_empty_capacity_are_argument_errors():
     bc.load()
     for name, call in _cache_calls().items():
+        # the uniform-layout promise: capacity equal to max_cap, prompt not longer than it
+        assert call(shape(), cache(uniform_P=16, uniform_cap=32)) == bc.BC_ERR_ARG, name
+        assert call(shape(), cache(uniform_P=65, uniform_cap=64)) == bc.BC_ERR_ARG, name
+        assert call(shape(), cache(uniform_P=-1)) == bc.BC_ERR_ARG, name
+        assert call(shape(), cache(uniform_cap=-1)) == bc.BC_ERR_ARG, name
         assert call(shape(), cache(k_slab=ODD)) == bc.BC_ERR_ARG, name
         assert call(shape(), cache(v_slab=ODD)) == bc.BC_ERR_ARG, name
         assert call(shape(), cache(max_cap=0)) == bc.BC_ERR_ARG, name

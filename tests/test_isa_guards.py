@@ -4,7 +4,8 @@ The decode kernel issues its loads through hand-written instructions that the co
 track (so that it places no wait for them inside the tile loop); the waits are explicit.  That is
 only correct while the compiler never reads a destination register of such a load between the load
 and the next wait - e.g. through a register-to-register copy that joins two definitions.  This test
-compiles the file to assembly and checks exactly that, for every instantiation of the kernel.
+compiles the file to assembly and checks exactly that, for every instantiation of the kernel
+(and the same for the scalar loads of the table entries in the prologue of both decode kernels).
 """
 import os
 import re
@@ -48,7 +49,39 @@ def reads_of_inflight_registers(body):
     return found
 
 
+def reads_of_inflight_scalars(body):
+    """The same for the hand-written scalar table loads (s_load_dword[x2] ..., 0x0 from a pointer other
+    than the kernel-argument segment s[0:1]): reads of their destinations before the next
+    s_waitcnt lgkmcnt(0)."""
+    found, pending = [], set()
+    for line in body:
+        op = line.split()[0]
+        if pending and "lgkmcnt(0)" in line:
+            pending = set()
+            continue
+        if pending and not op.endswith(":") and not op.startswith("."):
+            operands = line[len(op):].split(",")
+            whole = op.startswith(("s_cmp", "s_cbranch", "s_bitcmp", "global_", "ds_write", "v_cmp"))
+            reads = line[len(op):] if whole else ",".join(operands[1:])
+            used = set(int(x) for x in re.findall(r"\bs(\d+)\b", reads))
+            for m in re.finditer(r"s\[(\d+):(\d+)\]", reads):
+                used.update(range(int(m.group(1)), int(m.group(2)) + 1))
+            if used & pending:
+                found.append(line)
+        m = re.match(r"s_load_dword(x2)? (?:s(\d+)|s\[(\d+):(\d+)\]), s\[(\d+):\d+\], 0x0$", line)
+        if m and m.group(5) != "0":
+            if m.group(2) is not None:
+                pending.add(int(m.group(2)))
+            else:
+                pending.update(range(int(m.group(3)), int(m.group(4)) + 1))
+    return found
+
+
 def test_checker_flags_a_copy_of_an_inflight_register():
+    bad_s = ["s_load_dword s7, s[4:5], 0x0", "s_add_i32 s9, s7, 1", "s_waitcnt lgkmcnt(0)"]
+    good_s = ["s_load_dword s7, s[4:5], 0x0", "s_add_i32 s7, s9, 1"[:0] + "s_add_i32 s9, s8, 1", "s_waitcnt lgkmcnt(0)",
+              "s_add_i32 s9, s7, 1"]
+    assert reads_of_inflight_scalars(bad_s) and not reads_of_inflight_scalars(good_s)
     bad = ["global_load_dwordx4 v[8:11], v[2:3], off", "v_mov_b32_e32 v20, v9", "s_waitcnt vmcnt(0)"]
     good = ["global_load_dwordx4 v[8:11], v[2:3], off", "v_mov_b32_e32 v9, v20", "s_waitcnt vmcnt(0)",
             "ds_write_b128 v1, v[8:11]"]
@@ -66,10 +99,14 @@ def test_decode_kernel_never_reads_a_register_whose_load_is_in_flight(tmp_path):
     subprocess.check_call([hipcc] + flags + ["-w", "-I", os.path.join(ROOT, "include"), "-S",
                                              "--cuda-device-only", src, "-o", out])
     text = open(out).read().split("\n")
-    starts = [i for i, l in enumerate(text) if re.match(r"^_ZN2bc17decode_lds_kernel\w+:", l)]
-    assert len(starts) >= 13
+    starts = [i for i, l in enumerate(text) if re.match(r"^_ZN2bc1[78]decode_(lds|valu)_kernel\w+:", l)]
+    assert len(starts) >= 13 + 20
     for s in starts:
         e = next(i for i in range(s, len(text)) if text[i].startswith(".Lfunc_end"))
         body = [l.strip() for l in text[s:e] if l.strip() and not l.strip().startswith(";")]
-        assert any(l.startswith("global_load_lds_dwordx4") for l in body)
-        assert not reads_of_inflight_registers(body), (text[s][:80], reads_of_inflight_registers(body)[:3])
+        if "decode_lds_kernel" in text[s]:
+            assert any(l.startswith("global_load_lds_dwordx4") for l in body)
+            assert not reads_of_inflight_registers(body), (text[s][:80], reads_of_inflight_registers(body)[:3])
+        # the six table entries of the prologue (both kernels)
+        assert sum(1 for l in body if re.match(r"s_load_dword(x2)? \S+ s\[(?!0:1)\d+:\d+\], 0x0$", l)) >= 6, text[s][:80]
+        assert not reads_of_inflight_scalars(body), (text[s][:80], reads_of_inflight_scalars(body)[:3])
