@@ -646,6 +646,7 @@ def main():
         "config": {"workload": "batch64 rollout: B=64, Hq=12, Hkv=2, d=128, bf16, P=256, G=4096, c=%s; "
                                "tokens %d..%d of the rollout" % (c if c > 0 else "inf", tok_first, t_end),
                    "layers_round_robin": NL, "hip_graph": graph is not None, "beacon_token_attention": bool(faithful),
+                   "uniform_layout_promise": bool(layers[0].cache.uniform_P > 0),
                    "step": "bc_decode_step for one layer: append_kv + decode_attn + compress_evict, one launch",
                    "kv_bytes_per_step_mean": int(np.mean(step_bytes))},
         "roofline": {"bound": "hbm", "kernel": "bc::decode_lds_kernel<false, 1, 128, 2, 12> (bc_decode_step: append + attention + eviction)",
