@@ -340,15 +340,12 @@ constexpr int kLdsBytes = kLdsWaves * 2 * kTileRows * 256;   // d = 128: 128 KB 
 constexpr int kLdsBytesSplit = kLdsWavesSplit * 3 * kTileRows * 128;   // K tile + half a V tile per wave: 144 KB
 constexpr int kLdsBytesMax = kLdsBytesSplit > kLdsBytes ? kLdsBytesSplit : kLdsBytes;
 
-typedef __attribute__((address_space(3))) void lds_void_t;
-typedef __attribute__((address_space(1))) const void global_void_t;
 typedef __attribute__((ext_vector_type(4))) short s16x4_t;
 typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
 
 // K/V rows are read exactly once per launch: they are loaded with the non-temporal cache policy
 // (the `nt` bit of the load instructions), which measured 5 % faster per step than the default
-// policy at config 2.  kStreamPolicy is that bit in the LDS-DMA load's cache-policy operand.
-constexpr int kStreamPolicy = 2;
+// policy at config 2.
 constexpr int kStreamMinWorkgroups = 48;
 
 template <bool STREAM> __device__ __forceinline__ uint4 load16(const char* p);
