@@ -106,6 +106,13 @@ def test_decode_kernel_never_reads_a_register_whose_load_is_in_flight(tmp_path):
         body = [l.strip() for l in text[s:e] if l.strip() and not l.strip().startswith(";")]
         if "decode_lds_kernel" in text[s]:
             assert any(l.startswith("global_load_lds_dwordx4") for l in body)
+            # M0 (the LDS address of a DMA load) is set by the hand-written sequence itself, right in
+            # front of every such load, and nothing else in the kernel touches it
+            for i, l in enumerate(body):
+                if l.startswith("global_load_lds"):
+                    assert body[i - 2].startswith("s_mov_b32 m0, s") and body[i - 1].startswith("s_nop"), body[i - 2:i + 1]
+                elif re.search(r"\bm0\b", l):
+                    assert l.startswith("s_mov_b32 m0, s"), l
             assert not reads_of_inflight_registers(body), (text[s][:80], reads_of_inflight_registers(body)[:3])
         # the six table entries of the prologue (both kernels)
         assert sum(1 for l in body if re.match(r"s_load_dword(x2)? \S+ s\[(?!0:1)\d+:\d+\], 0x0$", l)) >= 6, text[s][:80]
