@@ -308,7 +308,8 @@ int32_t bc_diag_stream_read(const void *src, size_t bytes, int32_t workgroups, u
  * plain-ALU kernel, 2 = the LDS/MFMA kernel or BC_ERR_SHAPE, 3 = automatic but ignoring
  * cache->order, 4 = automatic but with the default
  * cache policy for the K/V loads of large launches, 5 = automatic but always one workgroup per
- * (sequence, KV head) pair, 6 = automatic but ignoring the uniform-layout promise; 11..15 = timing
+ * (sequence, KV head) pair, 6 = automatic but ignoring the uniform-layout promise, 7 = automatic but
+ * never the four-wave workgroups of large batches with short caches; 11..15 = timing
  * probes that leave
  * the LDS/MFMA kernel after a given stage (outputs are then meaningless). */
 void bc_set_decode_tuning(int32_t rows_per_workgroup, int32_t variant);
