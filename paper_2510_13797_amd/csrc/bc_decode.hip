@@ -443,7 +443,11 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
   if (!pi.live) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); return; }
   if (early_tile && (pi.P != p.spec_P || pi.cap != p.spec_cap || pi.base != (int64_t)pi.s * p.spec_cap))
     early_tile = false;      // the promise does not hold here: the tile is requested again below
-  if (PROBES && p.debug_stage == 2) { if (pi.L == 12345678) p.out[0] = 1.f; return; }
+  if (PROBES && p.debug_stage == 2) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // (an early tile may be on its way to LDS)
+    if (pi.L == 12345678) p.out[0] = 1.f;
+    return;
+  }
 
   const int n = lane & 15, kb = lane >> 4;       // MFMA column / k-block of this lane
   const HalfSelectors sel = half_selectors();
@@ -685,7 +689,11 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
     }
   }
 
-  if (PROBES && (p.debug_stage == 3 || p.debug_stage == 4)) { if (m_run == 123.f) p.out[0] = l_run + O[0][0]; return; }
+  if (PROBES && (p.debug_stage == 3 || p.debug_stage == 4)) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // (the ticket's answer)
+    if (m_run == 123.f) p.out[0] = l_run + O[0][0];
+    return;
+  }
 #undef BC_LOAD_TILE_REGS
 #undef BC_TAKE_TICKET
   // denominators: sum the four k-blocks of each head
