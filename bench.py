@@ -428,7 +428,6 @@ def main():
                          "instead of handing the beacon K/V to the token step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-control", action="store_true", help="skip the uncompressed (c=inf) control measurement")
-    ap.add_argument("--rows-per-wg", type=int, default=0)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (--gpus 1); multi-GPU sharding is a design "
@@ -451,8 +450,6 @@ def main():
         return bench_copy(args)
     if args.workload == "readfloor":
         return bench_readfloor(args)
-    if args.rows_per_wg:
-        bc.bc_set_decode_tuning(args.rows_per_wg, 0)
 
     wl = workloads.batch64(c=args.c)
     NL = args.layers

@@ -13,7 +13,7 @@
  * General conventions
  *  - Every pointer is a DEVICE pointer owned by the caller unless the argument is
  *    documented as "host".  The library allocates no device memory and keeps no state
- *    between calls except the tuning override of bc_set_decode_tuning().
+ *    between calls: everything that steers a call travels in its arguments.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Every
  *    call except bc_tables_to_host() only enqueues work on that stream and returns.
  *  - Return value: host-detectable errors only (bad argument, unsupported shape,
@@ -89,7 +89,28 @@ typedef struct {
   const int32_t *order;  /* [B] optional dispatch order, see bc_sort_by_length(); or NULL */
   int32_t uniform_P;     /* HOST values, optional promise about the layout, 0 = none: see below */
   int32_t uniform_cap;
+  int32_t rows_per_workgroup; /* HOST value, 0 = automatic: see "Plan of the decode calls" below */
+  int32_t plan;               /* HOST value, 0 = automatic: BC_PLAN_* bits                      */
 } bc_cache;
+
+/* Plan of the decode calls (bc_decode_attn and the step calls).  Left at zero, the library picks
+ * kernel, workgroup shape and chunking from the shape and max_cap.  Tests and measurements can
+ * narrow that choice per call; no choice changes a result beyond the order of fp32 additions.
+ *  rows_per_workgroup > 0: rows of one (sequence, KV head) stream handled by one workgroup (rounded
+ *      up to the kernel's pass size and so that a sequence has at most 64 chunks); partial results
+ *      are folded by a second launch.  On a batch with 128 or more (sequence, KV head) pairs the
+ *      workspace of bc_decode_workspace_bytes() covers at most four chunks per sequence, beyond
+ *      that the calls return BC_ERR_WORKSPACE.  < 0 is BC_ERR_ARG.
+ *  plan: OR of the bits below; an unknown bit is BC_ERR_ARG. */
+#define BC_PLAN_PLAIN_ALU 1               /* bf16 shapes on the register/FMA kernel as well        */
+#define BC_PLAN_NEED_MATRIX_KERNEL 2      /* BC_ERR_SHAPE unless the LDS/MFMA kernel serves the shape */
+#define BC_PLAN_IGNORE_ORDER 4            /* dispatch in index order although cache->order is set  */
+#define BC_PLAN_CACHEABLE_LOADS 8         /* default cache policy for K/V loads of large launches  */
+#define BC_PLAN_ONE_WORKGROUP_PER_PAIR 16 /* never two workgroups (V column halves) per pair       */
+#define BC_PLAN_IGNORE_PROMISE 32         /* do not use uniform_P / uniform_cap                    */
+#define BC_PLAN_NO_SMALL_WORKGROUPS 64    /* never the four-wave workgroups of large, short batches */
+#define BC_PLAN_GENERAL_LOOP 128          /* short caches on the general tile loop as well         */
+#define BC_PLAN_ALL_BITS 255
 
 /* Promise of a uniform layout (not in the paper: a latency aid for batches of equal prompt length,
  * the shape of its evaluation rollouts).  With uniform_P > 0 the caller states that the slabs hold
@@ -147,9 +168,7 @@ int32_t bc_append_kv(const bc_shape *shape, const bc_cache *cache, const void *k
                      const void *v, const uint8_t *active, int32_t kind, void *stream);
 
 /* Bytes of workspace bc_decode_attn() and the step calls need for this shape and max_cap
- * (enough for the automatic plan; a chunk size forced by bc_set_decode_tuning() on a batch with
- * 128 or more (sequence, KV head) pairs may split a sequence into at most four chunks, beyond
- * that the calls return BC_ERR_WORKSPACE). */
+ * (enough for the automatic plan; for a forced chunk size see bc_cache::rows_per_workgroup). */
 size_t bc_decode_workspace_bytes(const bc_shape *shape, int32_t max_cap);
 
 /* Zero a freshly allocated workspace (it holds per-sequence counters that the library
@@ -234,7 +253,8 @@ int32_t bc_set_ratio(const bc_shape *shape, const bc_cache *cache, const int32_t
  * q: [total_rows, Hq, d]; k, v: [total_rows, Hkv, d] (kv_dtype must be BC_BF16);
  * out: [total_rows, Hq, d] fp32; lse (nullable): [total_rows, Hq] fp32, natural log of
  * the softmax denominator.  row_offsets: device [B+1] int64; P, c: device [B] int32;
- * max_rows: HOST value >= the longest trajectory (sizes the grid), < 2^26.  scale must be > 0 and finite (else BC_ERR_ARG). */
+ * max_rows: HOST value >= the longest trajectory (sizes the grid), < 2^26.  scale must be > 0 and finite (else BC_ERR_ARG).
+ * Supported: kv_dtype BC_BF16 with d = 128; anything else is BC_ERR_SHAPE. */
 int32_t bc_prefill_attn(const bc_shape *shape, const void *q, const void *k, const void *v,
                         const int64_t *row_offsets, const int32_t *P, const int32_t *c,
                         int32_t max_rows, float *out, float *lse, void *stream);
@@ -295,24 +315,6 @@ int32_t bc_tables_to_host(const bc_shape *shape, const bc_cache *cache, int32_t 
  * 0..B-1 sets the state bit and its workgroups do nothing.  B <= 4096, else BC_ERR_SHAPE. */
 int32_t bc_sort_by_length(const bc_shape *shape, const bc_cache *cache, const uint8_t *active,
                           int32_t *order, void *stream);
-
-/* Measurement aid (no operation of the paper): `workgroups` workgroups of 512 threads read
- * `bytes` bytes (a multiple of 16, 16-byte aligned, device) from `src` with coalesced streaming
- * loads and write one word each to sink[workgroups] (device, may be NULL).  With bytes == 0 it is
- * an empty kernel.  bench.py --workload readfloor times it at the decode step's size and grid. */
-int32_t bc_diag_stream_read(const void *src, size_t bytes, int32_t workgroups, uint32_t *sink,
-                            void *stream);
-
-/* Tuning override for experiments: rows of one (sequence, KV head) stream handled by one
- * workgroup of bc_decode_attn (0 = automatic), and kernel variant: 0 = automatic, 1 = always the
- * plain-ALU kernel, 2 = the LDS/MFMA kernel or BC_ERR_SHAPE, 3 = automatic but ignoring
- * cache->order, 4 = automatic but with the default
- * cache policy for the K/V loads of large launches, 5 = automatic but always one workgroup per
- * (sequence, KV head) pair, 6 = automatic but ignoring the uniform-layout promise, 7 = automatic but
- * never the four-wave workgroups of large batches with short caches; 11..15 = timing
- * probes that leave
- * the LDS/MFMA kernel after a given stage (outputs are then meaningless). */
-void bc_set_decode_tuning(int32_t rows_per_workgroup, int32_t variant);
 
 #ifdef __cplusplus
 }

@@ -17,21 +17,27 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libbc.so")
+DIAG_LIB_PATH = os.path.join(_HERE, "libbc_diag.so")     # measurement aids (include/bc_diag.h)
 
 BC_OK = 0
 BC_ERR_ARG, BC_ERR_SHAPE, BC_ERR_CAPACITY, BC_ERR_STATE, BC_ERR_WORKSPACE, BC_ERR_HIP = -1, -2, -3, -4, -5, -6
 BC_F32, BC_BF16 = 0, 1
 BC_ERRBIT_STATE, BC_ERRBIT_CAPACITY = 1, 2
 BC_ROW_TOKEN, BC_ROW_BEACON = 0, 1
+# bits of bc_cache.plan
+BC_PLAN_PLAIN_ALU, BC_PLAN_NEED_MATRIX_KERNEL, BC_PLAN_IGNORE_ORDER, BC_PLAN_CACHEABLE_LOADS = 1, 2, 4, 8
+BC_PLAN_ONE_WORKGROUP_PER_PAIR, BC_PLAN_IGNORE_PROMISE, BC_PLAN_NO_SMALL_WORKGROUPS = 16, 32, 64
+BC_PLAN_GENERAL_LOOP = 128
 
 EXPORTS = [
     "bc_status_str", "bc_version", "bc_cache_init", "bc_cache_admit", "bc_append_kv",
     "bc_decode_workspace_bytes", "bc_workspace_init", "bc_decode_attn",
     "bc_compress_evict", "bc_decode_step", "bc_beacon_step", "bc_decode_step_budget", "bc_set_ratio",
-    "bc_sort_by_length", "bc_diag_stream_read",
+    "bc_sort_by_length",
     "bc_prefill_attn", "bc_prefill_bwd_workspace_bytes", "bc_prefill_attn_bwd",
-    "bc_topk_kl_loss", "bc_topk_kl_loss_bwd", "bc_tables_to_host", "bc_set_decode_tuning",
+    "bc_topk_kl_loss", "bc_topk_kl_loss_bwd", "bc_tables_to_host",
 ]
+DIAG_EXPORTS = ["bc_diag_stream_read"]
 
 
 class bc_shape(C.Structure):
@@ -44,7 +50,8 @@ class bc_cache(C.Structure):
                 ("cap", C.c_void_p), ("P", C.c_void_p), ("c", C.c_void_p),
                 ("nb", C.c_void_p), ("w", C.c_void_p), ("err", C.c_void_p),
                 ("max_cap", C.c_int32), ("order", C.c_void_p),
-                ("uniform_P", C.c_int32), ("uniform_cap", C.c_int32)]
+                ("uniform_P", C.c_int32), ("uniform_cap", C.c_int32),
+                ("rows_per_workgroup", C.c_int32), ("plan", C.c_int32)]
 
 
 class BcError(RuntimeError):
@@ -74,8 +81,6 @@ def load():
     lib.bc_cache_init.argtypes = [sp, cp, vp, vp, vp, i64, vp]
     lib.bc_cache_admit.restype = i32
     lib.bc_cache_admit.argtypes = [sp, cp, vp, vp, vp, i64, vp, vp, vp, vp]
-    lib.bc_diag_stream_read.restype = i32
-    lib.bc_diag_stream_read.argtypes = [vp, sz, i32, vp, vp]
     lib.bc_sort_by_length.restype = i32
     lib.bc_sort_by_length.argtypes = [sp, cp, vp, vp, vp]
     lib.bc_append_kv.restype = i32
@@ -108,9 +113,27 @@ def load():
     lib.bc_topk_kl_loss_bwd.argtypes = [i64, i32, i32, vp, i32, vp, vp, vp, C.c_float, vp, vp]
     lib.bc_tables_to_host.restype = i32
     lib.bc_tables_to_host.argtypes = [sp, cp, vp, vp, vp, vp]
-    lib.bc_set_decode_tuning.restype = None
-    lib.bc_set_decode_tuning.argtypes = [i32, i32]
     _lib = lib
+    return lib
+
+
+_diag = None
+
+
+def load_diag():
+    """Load libbc_diag.so (measurement aids, see include/bc_diag.h); raises if it is missing."""
+    global _diag
+    if _diag is not None:
+        return _diag
+    if not os.path.exists(DIAG_LIB_PATH):
+        raise BcError("libbc_diag.so not built: run `python __graft_entry__.py` first")
+    lib = C.CDLL(DIAG_LIB_PATH)
+    for name in DIAG_EXPORTS:
+        if not hasattr(lib, name):
+            raise BcError("libbc_diag.so lacks symbol %s" % name)
+    lib.bc_diag_stream_read.restype = C.c_int32
+    lib.bc_diag_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+    _diag = lib
     return lib
 
 
@@ -173,8 +196,8 @@ def bc_decode_step_budget(shape, cache, k, v, q, out, beacon_k, beacon_v, budget
                                         budget, live, ws, ws_bytes, stream)
 
 
-def bc_diag_stream_read(src, nbytes, workgroups, sink, stream):
-    return load().bc_diag_stream_read(src, nbytes, workgroups, sink, stream)
+def bc_diag_stream_read(src, nbytes, workgroups, mode, sink, stream):
+    return load_diag().bc_diag_stream_read(src, nbytes, workgroups, mode, sink, stream)
 
 
 def bc_sort_by_length(shape, cache, active, order, stream):
@@ -214,10 +237,6 @@ def bc_topk_kl_loss_bwd(T, V, k, student_logits, logits_dtype, teacher_logits, t
 
 def bc_tables_to_host(shape, cache, nb_host, w_host, err_host, stream):
     return load().bc_tables_to_host(C.byref(shape), C.byref(cache), nb_host, w_host, err_host, stream)
-
-
-def bc_set_decode_tuning(rows_per_workgroup, variant=0):
-    load().bc_set_decode_tuning(rows_per_workgroup, variant)
 
 
 # ---------------------------------------------------------------------------
@@ -287,7 +306,7 @@ class Runtime:
         self.cache = bc_cache(self.k_slab.data_ptr(), self.v_slab.data_ptr(), self.base.data_ptr(),
                               self.cap.data_ptr(), self.P.data_ptr(), self.c.data_ptr(),
                               self.nb.data_ptr(), self.w.data_ptr(), self.err.data_ptr(),
-                              self.max_cap, None, 0, 0)
+                              self.max_cap, None, 0, 0, 0, 0)
         # equal prompt lengths and capacities (slabs laid out back to back): tell the library, which
         # may then request prompt rows before it has read the tables
         if (self.P_host == self.P_host[0]).all() and (self.cap_host == self.cap_host[0]).all() \

@@ -81,7 +81,15 @@ __device__ __forceinline__ void load16_uncounted(u32x4_t& dst, const char* g) {
   if (STREAM) asm volatile("global_load_dwordx4 %0, %1, off nt" : "=v"(dst) : "v"(g) : "memory");
   else asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(g) : "memory");
 }
-// (tests/test_isa_guards.py checks the generated code for reads of such a register before a wait)
+// The point from which such a register may be used: right behind the explicit wait that covers its
+// load.  Emits no instruction (the comment names the register for the check of the generated code:
+// nothing may touch it between its load and this point).  The register is an input only: an
+// in-out operand would make the mark a new definition, and the compiler joins the definitions of
+// several marks of one variable by register copies - some of them in front of the wait.
+template <typename R>
+__device__ __forceinline__ void landed(const R& reg) {
+  asm volatile("; landed %0" : : "v"(reg) : "memory");
+}
 
 // 16 bytes of a row -> floats
 __device__ __forceinline__ void unpack16(const uint4& r, float (&f)[4], float) {

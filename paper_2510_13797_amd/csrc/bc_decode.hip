@@ -58,7 +58,6 @@ struct DecodeParams {
   int32_t beacon_row;  // the fused row is the beacon closing a full window (bk = new_k, bv = new_v)
   int32_t B;
   int32_t spec_P, spec_cap;   // bc_cache::uniform_P, uniform_cap (0 = no promise)
-  int32_t debug_stage; // experiments only: leave the kernel early (0 = run everything)
   int32_t Hq, Hkv, g;  // g = real group size
   int32_t Gp;          // padded group size of the partial layout
   int32_t D;
@@ -145,8 +144,11 @@ __device__ __forceinline__ PairInfo pair_info(const DecodeParams& p, int slot, i
   int act, w;
   int s = slot;
   bool bad_order = false;
+  // (values that are the same for the whole workgroup are moved to scalar registers where the
+  // compiler cannot see that itself - anything it loads through the vector path - so that the
+  // conditions on them become real branches instead of lane masks)
   if (p.order) {
-    s = p.order[slot];
+    s = __builtin_amdgcn_readfirstlane(p.order[slot]);
     bad_order = (unsigned)s >= (unsigned)p.B;        // not written by bc_sort_by_length
     if (bad_order) s = 0;
   }
@@ -168,7 +170,7 @@ __device__ __forceinline__ PairInfo pair_info(const DecodeParams& p, int slot, i
     asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(tP), "+s"(tnb), "+s"(tw), "+s"(tcap), "+s"(tbase), "+s"(tc) : : "memory");
     pi.P = tP; pi.nb = tnb; w = tw; pi.cap = tcap; pi.base = tbase; pi.c = tc;
   }
-  act = p.active ? p.active[pi.s] : 1;
+  act = p.active ? __builtin_amdgcn_readfirstlane((int)p.active[pi.s]) : 1;
   if (bad_order) {
     if (chunk == 0 && threadIdx.x == 0) atomicOr(p.err, BC_ERRBIT_STATE);
     act = 0;
@@ -229,7 +231,7 @@ __device__ __forceinline__ PairInfo pair_info(const DecodeParams& p, int slot, i
       // the evaluation cap is tested on what this step's attention sees, whether or not the
       // append went through
       pi.update = append_ok || pi.evict_due ||
-                  (p.budget && pi.nb + pi.w_att >= p.budget[pi.s]);
+                  (p.budget && pi.nb + pi.w_att >= __builtin_amdgcn_readfirstlane(p.budget[pi.s]));
       if (pi.chunk < pi.nchunks) {
         pi.row0 = pi.chunk * rpc;
         pi.row_end = min(pi.L, pi.row0 + rpc);
@@ -238,6 +240,16 @@ __device__ __forceinline__ PairInfo pair_info(const DecodeParams& p, int slot, i
     }
   }
   if (p.part_n && chunk == 0 && threadIdx.x == 0) p.part_n[pi.s * p.Hkv + pi.kvh] = pi.nchunks;
+  // (uniform by construction; said explicitly for what went through vector arithmetic)
+  pi.L = __builtin_amdgcn_readfirstlane(pi.L);
+  pi.nchunks = __builtin_amdgcn_readfirstlane(pi.nchunks);
+  pi.row0 = __builtin_amdgcn_readfirstlane(pi.row0);
+  pi.row_end = __builtin_amdgcn_readfirstlane(pi.row_end);
+  pi.new_row = __builtin_amdgcn_readfirstlane(pi.new_row);
+  pi.live = __builtin_amdgcn_readfirstlane((int)pi.live) != 0;
+  pi.update = __builtin_amdgcn_readfirstlane((int)pi.update) != 0;
+  pi.evict_due = __builtin_amdgcn_readfirstlane((int)pi.evict_due) != 0;
+  pi.store_new_row = __builtin_amdgcn_readfirstlane((int)pi.store_new_row) != 0;
   return pi;
 }
 
@@ -372,7 +384,6 @@ template <> __device__ __forceinline__ int tile_swz<64>(int row) {
   return (((row >> 1) & 1) << 1) | (((row >> 3) & 1) << 2);
 }
 
-// PROBES: honour the early exits of the timing probes (tuning variants 11..15).
 // STREAM: 1 = load K and V with the non-temporal policy (large launches; small ones are
 // latency-bound and about a microsecond faster with the default policy, 0); 2 = V only: with two
 // workgroups per pair and long caches the K lines, which the partner reads a little later, are
@@ -385,7 +396,28 @@ template <> __device__ __forceinline__ int tile_swz<64>(int row) {
 // multiple of 8: the K rows then come from HBM once.
 // NW: waves per workgroup, 8 or (two workgroups per pair, short caches: every wave then has one or
 // two tiles, and twelve waves finish a sequence of up to 384 rows in one pass) 12.
-template <bool PROBES, int STREAM, int D, int VS, int NW>
+// A wait for the wave's vector-memory counter with a count known at compile time (the
+// instruction takes an immediate).
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N <= 40, "counts used by the decode kernel");
+  if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  else if constexpr (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+  else if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+  else if constexpr (N == 12) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+  else if constexpr (N == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+  else if constexpr (N == 20) asm volatile("s_waitcnt vmcnt(20)" ::: "memory");
+  else if constexpr (N == 24) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
+  else static_assert(N < 0, "add the count");
+}
+
+// SHORT: every wave has at most two tiles (the caller's max_cap is at most 2 * NW * 32 rows, one
+// chunk per pair, no dispatch order).  The code is then a straight line: query and appended row
+// are requested first (their addresses do not need the tables), then the K part of the first
+// tile, its V part, and the second tile's K and V parts into registers - everything in flight
+// from the start, in the order it is needed - and every stage waits only for what it is about to
+// read: scores and softmax of a tile run while its V rows are still on their way, so that behind
+// the last byte only one value product is left.
+template <int STREAM, int D, int VS, int NW, bool SHORT = false>
 __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   constexpr bool KSTREAM = STREAM == 1, VSTREAM = STREAM >= 1;
@@ -403,90 +435,111 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
   constexpr int NJ = DV / 16;              // 16-column blocks of the output held here: 8 or 4
   constexpr int TILEB = kTileRows * ROWB;  // one K (or V) tile: 8 or 4 KB
   touch_kernel_arguments();
-  if (PROBES && p.debug_stage == 1) return;
   // grid: VS = 1: (chunk, KV head, slot); VS = 2: (KV head, slot, V half), the slots padded so
   // that a pair's two workgroups are 8k apart in dispatch order (workgroups go to the XCDs in turn)
   const int vhalf = VS == 1 ? 0 : (int)blockIdx.z;
-  if (VS != 1 && (int)blockIdx.y >= p.B) return;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int slot = VS == 1 ? (int)blockIdx.z : (int)blockIdx.y;
+  const int kvh0 = VS == 1 ? (int)blockIdx.y : (int)blockIdx.x;
+  if (VS != 1 && slot >= p.B) return;
+  // (the wave's number as a scalar: conditions on it become real branches, not lane masks)
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int r4 = lane / UPR, pos = lane & (UPR - 1);   // row within a 1 KB load, unit within the row
   const int r4v = lane / VUPR, posv = lane & (VUPR - 1);   // the same for this workgroup's part of V
+  const int n = lane & 15, kb = lane >> 4;       // MFMA column / k-block of this lane
   char* wk = lds + wave * (TILEB + VTILEB);
   char* wv = wk + TILEB;
+
+  // B operand of the score product: Q^T, column n = query head, k = head-dim index.
+  // The loads are written out by hand so that the compiler does not count them: it cannot tell
+  // the order in which they and the LDS-DMA loads complete, and would put a wait for ALL
+  // outstanding loads - the next tile's among them - in front of the first use in every pass of
+  // the tile loop.  They are older than any tile load the wave waits for.
+  bf16x8_t qb[NI];
+  auto request_query = [&](int s_) {
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      __attribute__((ext_vector_type(4))) uint32_t r = {0u, 0u, 0u, 0u};
+      if (n < p.g) {
+        const char* src = p.q + ((int64_t)(s_ * p.Hq + kvh0 * p.g + n) * D + 32 * i + 8 * kb) * 2;
+        asm volatile("global_load_dwordx4 %0, %1, off" : "+v"(r) : "v"(src) : "memory");
+      }
+      qb[i] = __builtin_bit_cast(bf16x8_t, r);
+    }
+  };
+  // Fused append: lanes 0..UPR-1 carry the new K row, the next VUPR lanes this workgroup's part of
+  // the new V row (16 bytes each); loaded by hand like the query, for the same reason.  The
+  // instruction is issued whether or not a row is appended (the other lanes, and all lanes of a
+  // plain attention call, read the head of the query tensor instead): the waits below count it.
+  u32x4_t newrow_v;
+  auto request_new_row = [&](int s_) {
+    const char* src = p.q + ((lane & 7) << 4);      // (128 bytes: inside the smallest query tensor)
+    if (p.new_k != nullptr && lane < UPR + VUPR) {
+      if constexpr (VS == 1)
+        src = (lane < UPR ? p.new_k : p.new_v) + (int64_t)(s_ * p.Hkv + kvh0) * ROWB + ((lane & (UPR - 1)) << 4);
+      else
+        src = lane < UPR
+            ? p.new_k + (int64_t)(s_ * p.Hkv + kvh0) * ROWB + (lane << 4)
+            : p.new_v + (int64_t)(s_ * p.Hkv + kvh0) * ROWB + vhalf * VROWB + ((lane - UPR) << 4);
+    }
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(newrow_v) : "v"(src) : "memory");
+  };
+  // HBM -> LDS: the K part of a tile (NDMA instructions, each RPI whole rows = 1 KB), then this
+  // workgroup's V part, 16-byte units XOR-swizzled by the row.  Rows beyond `last_row` are read
+  // from `last_row` instead (they are masked later; the loads stay inside the resident rows).
+  auto request_tile_dma = [&](const char* kb_, const char* vb_, int trow0, int last_row) {
+#pragma unroll
+    for (int j = 0; j < NDMA; ++j) {
+      const int row = RPI * j + r4;
+      const int grow = min(trow0 + row, last_row);
+      lds_dma16<KSTREAM>(kb_ + (int64_t)grow * ROWB + ((pos ^ tile_swz<D>(row)) << 4), wk + j * 1024);
+    }
+#pragma unroll
+    for (int j = 0; j < VNDMA; ++j) {
+      const int vrow = VRPI * j + r4v;
+      const int vgrow = min(trow0 + vrow, last_row);
+      lds_dma16<VSTREAM>(vb_ + (int64_t)vgrow * ROWB + ((posv ^ tile_swz<DV>(vrow)) << 4), wv + j * 1024);
+    }
+  };
+  if constexpr (SHORT) {            // the sequence is the slot: nothing here needs the tables
+    request_query(slot);
+    request_new_row(slot);
+  }
   // Prompt rows never change and are always resident.  When the caller has promised the slab
   // geometry (every sequence: P = spec_P, cap = spec_cap, base = index * spec_cap), a wave whose
   // first tile lies inside the prompt requests it before the tables are back.
   bool early_tile = false;
   auto request_prompt_tile = [&]() {
     if (p.spec_P > 0 && p.order == nullptr && p.max_chunks == 1 && (wave + 1) * kTileRows <= p.spec_P) {
-      const int s_ = VS == 1 ? (int)blockIdx.z : (int)blockIdx.y;
-      const int kvh_ = VS == 1 ? (int)blockIdx.y : (int)blockIdx.x;
-      const int64_t off_ = ((int64_t)s_ * p.spec_cap * p.Hkv + (int64_t)kvh_ * p.spec_cap) * ROWB;
-      const char* kb_ = p.k_slab + off_;
-      const char* vb_ = p.v_slab + off_ + vhalf * VROWB;
-#pragma unroll
-      for (int j = 0; j < NDMA; ++j) {
-        const int row = RPI * j + r4;
-        const int64_t goff = (int64_t)(wave * kTileRows + row) * ROWB + ((pos ^ tile_swz<D>(row)) << 4);
-        lds_dma16<KSTREAM>(kb_ + goff, wk + j * 1024);
-        if (j < VNDMA) {
-          const int vrow = VRPI * j + r4v;
-          const int64_t vgoff = (int64_t)(wave * kTileRows + vrow) * ROWB + ((posv ^ tile_swz<DV>(vrow)) << 4);
-          lds_dma16<VSTREAM>(vb_ + vgoff, wv + j * 1024);
-        }
-      }
+      const int64_t off_ = ((int64_t)slot * p.spec_cap * p.Hkv + (int64_t)kvh0 * p.spec_cap) * ROWB;
+      request_tile_dma(p.k_slab + off_, p.v_slab + off_ + vhalf * VROWB, wave * kTileRows, p.spec_P - 1);
       early_tile = true;
     }
   };
-  const PairInfo pi = VS == 1 ? pair_info(p, (int)blockIdx.z, (int)blockIdx.y, (int)blockIdx.x)
-                              : pair_info(p, (int)blockIdx.y, (int)blockIdx.x, 0, request_prompt_tile);
-  if (!pi.live) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); return; }
+  const PairInfo pi = VS == 1 && !SHORT ? pair_info(p, slot, kvh0, (int)blockIdx.x)
+                                        : pair_info(p, slot, kvh0, 0, request_prompt_tile);
+  // Tiles wave, wave + NW, ... of the chunk belong to this wave.
+  const int ntiles = (pi.row_end - pi.row0 + kTileRows - 1) / kTileRows;
+  bool nothing_to_do = !pi.live;
+  if constexpr (SHORT) {
+    // more rows than the caller's max_cap allows: no wave of the sequence goes on (none takes
+    // a ticket, so its tables and the counters stay as they were)
+    if (ntiles > 2 * NW) {
+      if (pi.kvh == 0 && vhalf == 0 && tid == 0) atomicOr(p.err, BC_ERRBIT_STATE);
+      nothing_to_do = true;
+    }
+  }
+  if (nothing_to_do) { wait_vmcnt<0>(); return; }
   if (early_tile && (pi.P != p.spec_P || pi.cap != p.spec_cap || pi.base != (int64_t)pi.s * p.spec_cap))
     early_tile = false;      // the promise does not hold here: the tile is requested again below
-  if (PROBES && p.debug_stage == 2) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // (an early tile may be on its way to LDS)
-    if (pi.L == 12345678) p.out[0] = 1.f;
-    return;
-  }
 
-  const int n = lane & 15, kb = lane >> 4;       // MFMA column / k-block of this lane
   const HalfSelectors sel = half_selectors();
   const int64_t stream_off = (pi.base * p.Hkv + (int64_t)pi.kvh * pi.cap) * ROWB;
   const char* kbase = p.k_slab + stream_off;
   const char* vbase = p.v_slab + stream_off + vhalf * VROWB;
-
-  // B operand of the score product: Q^T, column n = query head, k = head-dim index.
-  // The loads are written out by hand so that the compiler does not count them: it cannot tell
-  // the order in which they and the LDS-DMA loads complete, and would put a wait for ALL
-  // outstanding loads - the next tile's among them - in front of the first use in every pass of
-  // the tile loop.  They are the oldest loads of the wave: every wait for a first tile below (or
-  // the explicit one of a wave without tiles) covers them.
-  bf16x8_t qb[NI];
-#pragma unroll
-  for (int i = 0; i < NI; ++i) {
-    __attribute__((ext_vector_type(4))) uint32_t r = {0u, 0u, 0u, 0u};
-    if (n < p.g) {
-      const char* src = p.q + ((int64_t)(pi.s * p.Hq + pi.kvh * p.g + n) * D + 32 * i + 8 * kb) * 2;
-      asm volatile("global_load_dwordx4 %0, %1, off" : "+v"(r) : "v"(src) : "memory");
-    }
-    qb[i] = __builtin_bit_cast(bf16x8_t, r);
+  if constexpr (!SHORT) {           // the sequence may come from the dispatch order: after the tables
+    request_query(pi.s);
+    request_new_row(pi.s);
   }
-
-  // fused append: lanes 0..UPR-1 carry the new K row, the next VUPR lanes this workgroup's part
-  // of the new V row (16 bytes each)
-  // (loaded by hand like the query above, for the same reason)
-  u32x4_t newrow_v = u32x4_t{0u, 0u, 0u, 0u};
-  if (pi.new_row >= 0 && lane < UPR + VUPR) {
-    const char* src;
-    if constexpr (VS == 1)
-      src = (lane < UPR ? p.new_k : p.new_v) + (int64_t)(pi.s * p.Hkv + pi.kvh) * ROWB + ((lane & (UPR - 1)) << 4);
-    else
-      src = lane < UPR
-          ? p.new_k + (int64_t)(pi.s * p.Hkv + pi.kvh) * ROWB + (lane << 4)
-          : p.new_v + (int64_t)(pi.s * p.Hkv + pi.kvh) * ROWB + vhalf * VROWB + ((lane - UPR) << 4);
-    asm volatile("global_load_dwordx4 %0, %1, off" : "+v"(newrow_v) : "v"(src) : "memory");
-  }
-  const uint4 newrow = make_uint4(newrow_v.x, newrow_v.y, newrow_v.z, newrow_v.w);
   // rows the tile loads may touch: the resident rows that are already in the slab
   const int last_slab_row = max((pi.new_row >= 0 ? pi.new_row : pi.L) - 1, 0);
 
@@ -495,119 +548,101 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
   for (int j = 0; j < NJ; ++j) O[j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
   float m_run = kNegBig, l_run = 0.f;
 
-  // Tiles wave, wave + 8, ... of the chunk belong to this wave.  The first goes from HBM to
-  // LDS by LDS-DMA; the second is requested at the same time into registers, so both are in
-  // flight from the start.  Afterwards: copy the register tile to LDS, request the next tile
-  // into the freed registers, compute - one tile always in flight behind the one in use.
-  const int ntiles = (pi.row_end - pi.row0 + kTileRows - 1) / kTileRows;
-  // (not initialised, and written at one place only, the top of the tile loop: the loads are
-  // invisible to the compiler, so a register-to-register copy between a load and its wait - such
-  // as one that joins two definitions - would copy what is not there yet)
+  // A wave's first tile goes from HBM to LDS by LDS-DMA; the second is requested at the same
+  // time into registers, so both are in flight from the start.  Afterwards: copy the register
+  // tile to LDS, request the next tile into the freed registers, compute - one tile always in
+  // flight behind the one in use.
+  // (not initialised, and written at one place only: the loads are invisible to the compiler, so
+  // a register-to-register copy between a load and its wait - such as one that joins two
+  // definitions - would copy what is not there yet)
   u32x4_t kreg[NDMA], vreg[VNDMA];
-#define BC_LOAD_TILE_REGS(TROW0)                                              \
-  _Pragma("unroll") for (int j = 0; j < NDMA; ++j) {                          \
-    const int grow_ = min((TROW0) + RPI * j + r4, last_slab_row);             \
-    const int64_t goff_ = (int64_t)grow_ * ROWB + (pos << 4);                 \
-    load16_uncounted<KSTREAM>(kreg[j], kbase + goff_);                        \
-    if (j < VNDMA) {                                                          \
-      const int vrow_ = min((TROW0) + VRPI * j + r4v, last_slab_row);         \
-      load16_uncounted<VSTREAM>(vreg[j], vbase + (VS == 1 ? goff_ : (int64_t)vrow_ * ROWB + (posv << 4)));  \
-    }                                                                         \
-  }
-  if (wave < ntiles && !early_tile) {
-    // ---- HBM -> LDS: NDMA + NDMA instructions, each RPI whole rows (1 KB), 16-byte units XOR-swizzled
-    const int trow0 = pi.row0 + wave * kTileRows;
+  auto request_tile_regs = [&](int trow0) {
+#pragma unroll
+    for (int j = 0; j < NDMA; ++j) {
+      const int grow = min(trow0 + RPI * j + r4, last_slab_row);
+      load16_uncounted<KSTREAM>(kreg[j], kbase + (int64_t)grow * ROWB + (pos << 4));
+    }
+#pragma unroll
+    for (int j = 0; j < VNDMA; ++j) {
+      const int vrow = min(trow0 + VRPI * j + r4v, last_slab_row);
+      load16_uncounted<VSTREAM>(vreg[j], vbase + (int64_t)vrow * ROWB + (posv << 4));
+    }
+  };
+  auto k_regs_to_lds = [&]() {
 #pragma unroll
     for (int j = 0; j < NDMA; ++j) {
       const int row = RPI * j + r4;
-      const int grow = min(trow0 + row, last_slab_row);     // stay inside the slab rows
-      const int64_t goff = (int64_t)grow * ROWB + ((pos ^ tile_swz<D>(row)) << 4);
-      lds_dma16<KSTREAM>(kbase + goff, wk + j * 1024);
-      if (j < VNDMA) {
-        const int vrow = VRPI * j + r4v;
-        const int vgrow = min(trow0 + vrow, last_slab_row);
-        const int64_t vgoff = VS == 1 ? goff : (int64_t)vgrow * ROWB + ((posv ^ tile_swz<DV>(vrow)) << 4);
-        lds_dma16<VSTREAM>(vbase + vgoff, wv + j * 1024);
-      }
+      *reinterpret_cast<u32x4_t*>(wk + row * ROWB + ((pos ^ tile_swz<D>(row)) << 4)) = kreg[j];
     }
-  }
+  };
+  auto v_regs_to_lds = [&]() {
+#pragma unroll
+    for (int j = 0; j < VNDMA; ++j) {
+      const int vrow = VRPI * j + r4v;
+      *reinterpret_cast<u32x4_t*>(wv + vrow * VROWB + ((posv ^ tile_swz<DV>(vrow)) << 4)) = vreg[j];
+    }
+  };
+  auto query_landed = [&]() {
+#pragma unroll
+    for (int i = 0; i < NI; ++i) landed(qb[i]);
+    landed(newrow_v);
+  };
+  auto k_regs_landed = [&]() {
+#pragma unroll
+    for (int j = 0; j < NDMA; ++j) landed(kreg[j]);
+  };
+  auto v_regs_landed = [&]() {
+#pragma unroll
+    for (int j = 0; j < VNDMA; ++j) landed(vreg[j]);
+  };
+  if (wave < ntiles && !early_tile)
+    request_tile_dma(kbase, vbase, pi.row0 + wave * kTileRows, last_slab_row);
+
   // Fused step: every wave of every workgroup of the sequence takes a ticket as soon as its last
   // load from the slab has landed (the tables were read at the start); whoever draws the last one
   // may write the beacon row and update the tables.  The answer is only looked at after the wave
   // merge, so the atomic's round trip (about a microsecond) hides behind the remaining compute.
   int ticket = -1;
-#define BC_TAKE_TICKET()                                                                    \
-  if (pi.update && lane == 0) {                                                             \
-    const int one_ = 1;                                                                     \
-    asm volatile("global_atomic_add %0, %1, %2, off sc0"                                    \
-                 : "=v"(ticket) : "v"(p.tickets + pi.s * kTicketStride), "v"(one_) : "memory"); \
-  }
-  if (wave >= ntiles) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the query loads, before their registers are reused
-    BC_TAKE_TICKET()
-  }
-  for (int tile = wave; tile < ntiles; tile += NW) {
-    const int trow0 = pi.row0 + tile * kTileRows;
-    if (tile != wave) {
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // the register tile has arrived
-#pragma unroll
-      for (int j = 0; j < NDMA; ++j) {
-        const int row = RPI * j + r4;
-        const int o = row * ROWB + ((pos ^ tile_swz<D>(row)) << 4);
-        *reinterpret_cast<u32x4_t*>(wk + o) = kreg[j];
-        if (j < VNDMA) {
-          const int vrow = VRPI * j + r4v;
-          *reinterpret_cast<u32x4_t*>(wv + (VS == 1 ? o : vrow * VROWB + ((posv ^ tile_swz<DV>(vrow)) << 4))) = vreg[j];
-        }
-      }
+  auto take_ticket = [&]() {
+    if (pi.update && lane == 0) {
+      const int one_ = 1;
+      asm volatile("global_atomic_add %0, %1, %2, off sc0"
+                   : "=v"(ticket) : "v"(p.tickets + pi.s * kTicketStride), "v"(one_) : "memory");
     }
-    // the next tile of this wave goes to registers while this one is in use
-    if (tile + NW < ntiles) { BC_LOAD_TILE_REGS(trow0 + NW * kTileRows) }
-    if (tile == wave) {
-      // the LDS-DMA loads have landed once at most the register loads behind them are pending
-      if (wave + NW >= ntiles) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      else if (NDMA + VNDMA == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-      else if (NDMA + VNDMA == 12) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
-      else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+  };
+  // The appended row is not in the slab yet: place it in the tile (K part before the scores, V
+  // part before the value product), clear the V rows behind it, store it for later steps (unless
+  // this step's eviction drops it at once).  Only the sequence's last tile can hold it.
+  auto patch_k_row = [&](int trow0) {
+    const int ra = pi.new_row - trow0;
+    if (ra >= 0 && ra < kTileRows && lane < UPR)
+      *reinterpret_cast<u32x4_t*>(wk + ra * ROWB + ((lane ^ tile_swz<D>(ra)) << 4)) = newrow_v;
+  };
+  auto patch_v_row_and_store = [&](int trow0) {
+    const int ra = pi.new_row - trow0;
+    if (ra < 0 || ra >= kTileRows) return;
+    if (lane >= UPR && lane < UPR + VUPR) {
+      const int u = lane - UPR;
+      *reinterpret_cast<u32x4_t*>(wv + ra * VROWB + ((u ^ tile_swz<DV>(ra)) << 4)) = newrow_v;
+      if (pi.store_new_row)
+        *reinterpret_cast<u32x4_t*>(const_cast<char*>(vbase) + (int64_t)pi.new_row * ROWB + (u << 4)) = newrow_v;
+    } else if (lane < UPR) {
+      if (pi.store_new_row && vhalf == 0)
+        *reinterpret_cast<u32x4_t*>(const_cast<char*>(kbase) + (int64_t)pi.new_row * ROWB + (lane << 4)) = newrow_v;
     }
-    if (PROBES && p.debug_stage == 3) { if (tile + NW >= ntiles) { BC_TAKE_TICKET() } continue; }
+    for (int rr = ra + 1 + r4v; rr < kTileRows; rr += VRPI)
+      *reinterpret_cast<uint4*>(wv + rr * VROWB + (posv << 4)) = make_uint4(0u, 0u, 0u, 0u);
+  };
 
-    if (pi.new_row >= trow0 && pi.new_row < trow0 + kTileRows) {
-      // the appended row is not in the slab yet: place it in the tile, store it for later
-      // steps (unless this step's eviction drops it at once), clear the V rows behind it
-      const int ra = pi.new_row - trow0;
-      if constexpr (VS == 1) {
-        if (lane < 2 * UPR) {
-          char* tile = lane < UPR ? wk : wv;
-          const int u = lane & (UPR - 1);
-          *reinterpret_cast<uint4*>(tile + ra * ROWB + ((u ^ tile_swz<D>(ra)) << 4)) = newrow;
-          if (pi.store_new_row) {
-            char* slab = const_cast<char*>(lane < UPR ? kbase : vbase);
-            *reinterpret_cast<uint4*>(slab + (int64_t)pi.new_row * ROWB + (u << 4)) = newrow;
-          }
-        }
-      } else {
-        if (lane < UPR) {
-          *reinterpret_cast<uint4*>(wk + ra * ROWB + ((lane ^ tile_swz<D>(ra)) << 4)) = newrow;
-          if (pi.store_new_row && vhalf == 0)
-            *reinterpret_cast<uint4*>(const_cast<char*>(kbase) + (int64_t)pi.new_row * ROWB + (lane << 4)) = newrow;
-        } else if (lane < UPR + VUPR) {
-          const int u = lane - UPR;
-          *reinterpret_cast<uint4*>(wv + ra * VROWB + ((u ^ tile_swz<DV>(ra)) << 4)) = newrow;
-          if (pi.store_new_row)
-            *reinterpret_cast<uint4*>(const_cast<char*>(vbase) + (int64_t)pi.new_row * ROWB + (u << 4)) = newrow;
-        }
-      }
-      for (int rr = ra + 1 + r4v; rr < kTileRows; rr += VRPI)
-        *reinterpret_cast<uint4*>(wv + rr * VROWB + (posv << 4)) = make_uint4(0u, 0u, 0u, 0u);
-    }
-    // this wave's last tile is in LDS (a register tile has been waited for by its copy above) and
-    // the appended row, whose load the compiler waits for just above, is out of the way: nothing
-    // between here and the end of the kernel waits for memory, so the ticket's answer can stay out
-    if (tile + NW >= ntiles) { BC_TAKE_TICKET() }
-
-    // ---- scores, transposed: S^T[key][head] = K . Q^T.  Row m of sub-tile t is key
-    //      8*(m/4) + 4*t + m%4, so that a lane ends up with 8 consecutive keys of one head.
+  // ---- scores, transposed: S^T[key][head] = K . Q^T.  Row m of sub-tile t is key
+  //      8*(m/4) + 4*t + m%4, so that a lane ends up with 8 consecutive keys of one head:
+  //      lane (n, kb) holds head n, keys trow0 + 8*kb + e, e = 4*t + r.
+  // ---- softmax: the scores stay unscaled; the softmax scale (>= 0) enters through one fused
+  //      multiply-add per key, p = 2^(s*qs - m).  Only a sequence's last tile has rows beyond its
+  //      end; the tests for them sit behind a branch that is uniform over the wave.  The weights
+  //      leave as p = hi + lo with both parts bf16: the p.V product keeps ~16 bits of p.
+  bf16x8_t phi, plo;
+  auto scores_and_softmax = [&](int trow0, bool first) {
     f32x4_t S[2];
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
@@ -621,10 +656,6 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
         S[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qb[i], S[t], 0, 0, 0);
       }
     }
-    // lane (n, kb) now holds head n, keys trow0 + 8*kb + e, e = 4*t + r.  The scores stay
-    // unscaled: the softmax scale (>= 0) enters through one fused multiply-add per key,
-    // p = 2^(s*qs - m).  Only a sequence's last tile has rows beyond its end; the tests for
-    // them sit behind a branch that is uniform over the wave.
     const bool partial = trow0 + kTileRows > pi.row_end;
     const int nvalid = pi.row_end - trow0 - 8 * kb;        // keys e < nvalid of this lane exist
     float sv[8];
@@ -646,7 +677,6 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
       for (int e = 0; e < 8; ++e) pe[e] = e < nvalid ? pe[e] : 0.f;
     }
     const float psum = ((pe[0] + pe[1]) + (pe[2] + pe[3])) + ((pe[4] + pe[5]) + (pe[6] + pe[7]));
-    // p = hi + lo with both parts bf16: the p.V product keeps ~16 bits of p
     uint32_t hi[4], lo[4];
 #pragma unroll
     for (int e = 0; e < 8; e += 2) {
@@ -655,7 +685,7 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
       lo[e >> 1] = pack2_bf16(minus_half(pe[e], hp, sel.low), minus_half(pe[e + 1], hp, sel.high));
     }
     // a wave's first tile finds empty accumulators: nothing to rescale
-    if (tile != wave) {
+    if (!first) {
       const float alpha = fast_exp2(m_run - m_new);
       l_run *= alpha;
 #pragma unroll
@@ -663,39 +693,104 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
     }
     m_run = m_new;
     l_run += psum;
-    const bf16x8_t phi = __builtin_bit_cast(bf16x8_t, make_uint4(hi[0], hi[1], hi[2], hi[3]));
-    const bf16x8_t plo = __builtin_bit_cast(bf16x8_t, make_uint4(lo[0], lo[1], lo[2], lo[3]));
-
-    // ---- O^T[dcol][head] += V^T . P^T ; V^T comes from the transposing LDS read: lane r of a
-    //      16-lane block points at 4 consecutive dcols of key 8*kb + r/4 (+4 for the 2nd read)
-    {
-      const int r = lane & 15;
-      const int key0 = 8 * kb + (r >> 2);
+    phi = __builtin_bit_cast(bf16x8_t, make_uint4(hi[0], hi[1], hi[2], hi[3]));
+    plo = __builtin_bit_cast(bf16x8_t, make_uint4(lo[0], lo[1], lo[2], lo[3]));
+  };
+  // ---- O^T[dcol][head] += V^T . P^T ; V^T comes from the transposing LDS read: lane r of a
+  //      16-lane block points at 4 consecutive dcols of key 8*kb + r/4 (+4 for the 2nd read)
+  auto value_product = [&]() {
+    const int r = lane & 15;
+    const int key0 = 8 * kb + (r >> 2);
 #pragma unroll
-      for (int j = 0; j < NJ; ++j) {
-        const int u = 2 * j + ((r & 3) >> 1);
-        const int sub = (r & 1) << 3;
-        const int rowa = key0, rowb = key0 + 4;
-        const s16x4_t a0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (lds_s16x4_t*)(wv + rowa * VROWB + ((u ^ tile_swz<DV>(rowa)) << 4) + sub));
-        const s16x4_t a1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (lds_s16x4_t*)(wv + rowb * VROWB + ((u ^ tile_swz<DV>(rowb)) << 4) + sub));
-        typedef __attribute__((ext_vector_type(8))) short s16x8_t;
-        const s16x8_t a = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
-        const bf16x8_t av = __builtin_bit_cast(bf16x8_t, a);
-        O[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, phi, O[j], 0, 0, 0);
-        O[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, plo, O[j], 0, 0, 0);
+    for (int j = 0; j < NJ; ++j) {
+      const int u = 2 * j + ((r & 3) >> 1);
+      const int sub = (r & 1) << 3;
+      const int rowa = key0, rowb = key0 + 4;
+      const s16x4_t a0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (lds_s16x4_t*)(wv + rowa * VROWB + ((u ^ tile_swz<DV>(rowa)) << 4) + sub));
+      const s16x4_t a1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (lds_s16x4_t*)(wv + rowb * VROWB + ((u ^ tile_swz<DV>(rowb)) << 4) + sub));
+      typedef __attribute__((ext_vector_type(8))) short s16x8_t;
+      const s16x8_t a = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
+      const bf16x8_t av = __builtin_bit_cast(bf16x8_t, a);
+      O[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, phi, O[j], 0, 0, 0);
+      O[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, plo, O[j], 0, 0, 0);
+    }
+  };
+
+  if constexpr (SHORT) {
+    // Loads in flight, oldest first: query (NI), appended row (1), K of the first tile (NDMA),
+    // its V part (VNDMA) and, with a second tile, its K (NDMA) and V (VNDMA) into registers.
+    const int trowA = wave * kTileRows, trowB = trowA + NW * kTileRows;
+    if (wave >= ntiles) {
+      wait_vmcnt<0>();          // query and row loads, before their registers are reused
+      query_landed();
+      take_ticket();
+    } else if (wave + NW < ntiles) {
+      request_tile_regs(trowB);
+      wait_vmcnt<VNDMA + NDMA + VNDMA>();          // K of the first tile is in LDS
+      query_landed();
+      scores_and_softmax(trowA, true);
+      wait_vmcnt<NDMA + VNDMA>();                  // ... and its V part
+      value_product();
+      wait_vmcnt<VNDMA>();                         // K of the second tile is in registers
+      k_regs_landed();
+      k_regs_to_lds();
+      patch_k_row(trowB);
+      scores_and_softmax(trowB, false);
+      wait_vmcnt<0>();
+      v_regs_landed();
+      v_regs_to_lds();
+      patch_v_row_and_store(trowB);
+      take_ticket();
+      value_product();
+    } else {
+      wait_vmcnt<VNDMA>();
+      query_landed();
+      patch_k_row(trowA);
+      scores_and_softmax(trowA, true);
+      wait_vmcnt<0>();
+      patch_v_row_and_store(trowA);
+      take_ticket();
+      value_product();
+    }
+  } else {
+    if (wave >= ntiles) {
+      wait_vmcnt<0>();          // the query loads, before their registers are reused
+      query_landed();
+      take_ticket();
+    } else {
+      for (int tile = wave;; tile += NW) {
+        const int trow0 = pi.row0 + tile * kTileRows;
+        if (tile + NW < ntiles) {
+          // the next tile of this wave goes to registers while this one is in use; the tile in
+          // use has landed once at most those loads are pending
+          request_tile_regs(trow0 + NW * kTileRows);
+          wait_vmcnt<NDMA + VNDMA>();
+          query_landed();
+          scores_and_softmax(trow0, tile == wave);
+          value_product();
+          wait_vmcnt<0>();
+          k_regs_landed();
+          v_regs_landed();
+          k_regs_to_lds();
+          v_regs_to_lds();
+        } else {
+          // this wave's last tile: nothing between here and the end of the kernel waits for
+          // memory, so the ticket's answer can stay out
+          wait_vmcnt<0>();
+          query_landed();
+          patch_k_row(trow0);
+          patch_v_row_and_store(trow0);
+          take_ticket();
+          scores_and_softmax(trow0, tile == wave);
+          value_product();
+          break;
+        }
       }
     }
   }
 
-  if (PROBES && (p.debug_stage == 3 || p.debug_stage == 4)) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // (the ticket's answer)
-    if (m_run == 123.f) p.out[0] = l_run + O[0][0];
-    return;
-  }
-#undef BC_LOAD_TILE_REGS
-#undef BC_TAKE_TICKET
   // denominators: sum the four k-blocks of each head
   l_run = rows_allreduce_sum(l_run);
 
@@ -720,8 +815,9 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
   merge_waves_and_store4<NW, DV, D, APITCH>(p, pi, s_m, s_l, s_acc, WSTRIDE, vhalf * DV);
 
   // ---- the wave that drew the sequence's last ticket writes the beacon row and updates the tables
-  if (!pi.update || (PROBES && p.debug_stage == 5)) return;
-  asm volatile("s_waitcnt vmcnt(0)" : "+v"(ticket) : : "memory");     // the ticket has arrived
+  if (!pi.update) return;
+  wait_vmcnt<0>();     // the ticket has arrived
+  landed(ticket);
   if (__builtin_amdgcn_readfirstlane(ticket) != p.Hkv * pi.nchunks * VS * NW - 1) return;
   if (pi.evict_due) {
     const int n16 = p.Hkv * UPR;                   // 16-byte units of one K (or V) entry
@@ -931,9 +1027,6 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeParams p) {
   }
 }
 
-static int g_rows_per_wg = 0;
-static int g_variant = 0;
-
 struct DecodePlan {
   bool lds;           // LDS/MFMA kernel (bf16, d = 128) or the VALU kernel
   int Gp;             // padded group size
@@ -949,9 +1042,9 @@ static size_t align256(size_t x) { return (x + 255) / 256 * 256; }
 
 constexpr int kPlanForSizing = -1;    // rows_override value: size the workspace (see below)
 
-static DecodePlan make_plan(const bc_shape* sh, int max_cap, int rows_override, int variant) {
+static DecodePlan make_plan(const bc_shape* sh, int max_cap, int rows_override, int plan_bits) {
   DecodePlan pl;
-  pl.lds = sh->kv_dtype == BC_BF16 && variant != 1;
+  pl.lds = sh->kv_dtype == BC_BF16 && !(plan_bits & BC_PLAN_PLAIN_ALU);
   if (pl.lds) {
     pl.Gp = 8;
     pl.rows_per_pass = kLdsWaves * kTileRows;
@@ -1014,20 +1107,22 @@ static int32_t enable_big_lds() {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return BC_ERR_HIP;
   if (done[dev].load(std::memory_order_acquire)) return BC_OK;
-  const void* kernels[14] = {reinterpret_cast<const void*>(decode_lds_kernel<false, 1, 128, 1, 4>),
-                             reinterpret_cast<const void*>(decode_lds_kernel<false, 0, 128, 1, 8>),
-                             reinterpret_cast<const void*>(decode_lds_kernel<false, 1, 128, 1, 8>),
-                             reinterpret_cast<const void*>(decode_lds_kernel<true, 0, 128, 1, 8>),
-                             reinterpret_cast<const void*>(decode_lds_kernel<true, 1, 128, 1, 8>),
-                             reinterpret_cast<const void*>(decode_lds_kernel<false, 0, 64, 1, 8>),
-                             reinterpret_cast<const void*>(decode_lds_kernel<false, 1, 64, 1, 8>),
-                             reinterpret_cast<const void*>(decode_lds_kernel<false, 0, 128, 2, 8>),
-                             reinterpret_cast<const void*>(decode_lds_kernel<false, 1, 128, 2, 8>),
-                             reinterpret_cast<const void*>(decode_lds_kernel<false, 2, 128, 2, 8>),
-                             reinterpret_cast<const void*>(decode_lds_kernel<false, 0, 128, 2, 12>),
-                             reinterpret_cast<const void*>(decode_lds_kernel<false, 1, 128, 2, 12>),
-                             reinterpret_cast<const void*>(decode_lds_kernel<true, 1, 128, 2, 8>),
-                             reinterpret_cast<const void*>(decode_lds_kernel<true, 1, 128, 2, 12>)};
+  const void* kernels[] = {reinterpret_cast<const void*>(decode_lds_kernel<1, 128, 1, 4>),
+                           reinterpret_cast<const void*>(decode_lds_kernel<0, 128, 1, 8>),
+                           reinterpret_cast<const void*>(decode_lds_kernel<1, 128, 1, 8>),
+                           reinterpret_cast<const void*>(decode_lds_kernel<0, 128, 1, 8, true>),
+                           reinterpret_cast<const void*>(decode_lds_kernel<1, 128, 1, 8, true>),
+                           reinterpret_cast<const void*>(decode_lds_kernel<0, 64, 1, 8>),
+                           reinterpret_cast<const void*>(decode_lds_kernel<1, 64, 1, 8>),
+                           reinterpret_cast<const void*>(decode_lds_kernel<0, 64, 1, 8, true>),
+                           reinterpret_cast<const void*>(decode_lds_kernel<1, 64, 1, 8, true>),
+                           reinterpret_cast<const void*>(decode_lds_kernel<0, 128, 2, 8>),
+                           reinterpret_cast<const void*>(decode_lds_kernel<1, 128, 2, 8>),
+                           reinterpret_cast<const void*>(decode_lds_kernel<2, 128, 2, 8>),
+                           reinterpret_cast<const void*>(decode_lds_kernel<0, 128, 2, 12>),
+                           reinterpret_cast<const void*>(decode_lds_kernel<1, 128, 2, 12>),
+                           reinterpret_cast<const void*>(decode_lds_kernel<0, 128, 2, 12, true>),
+                           reinterpret_cast<const void*>(decode_lds_kernel<1, 128, 2, 12, true>)};
   bool ok = true;
   for (const void* kfn : kernels)
     ok = ok && hipFuncSetAttribute(kfn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytesMax) ==
@@ -1072,7 +1167,8 @@ static int32_t launch_attention(const bc_shape* shape, const bc_cache* cache, co
   p.B = shape->B;
   // Batches that need more than one round of workgroups follow the caller's dispatch order
   // (bc_sort_by_length), if there is one; with fewer workgroups everything starts at once.
-  p.order = (cache->order && pl.max_chunks == 1 && shape->B * shape->Hkv > kLptMinPairs && g_variant != 3)
+  p.order = (cache->order && pl.max_chunks == 1 && shape->B * shape->Hkv > kLptMinPairs &&
+             !(cache->plan & BC_PLAN_IGNORE_ORDER))
                 ? cache->order : nullptr;
   p.Hq = shape->Hq; p.Hkv = shape->Hkv; p.g = shape->Hq / shape->Hkv;
   p.Gp = pl.Gp;
@@ -1080,8 +1176,7 @@ static int32_t launch_attention(const bc_shape* shape, const bc_cache* cache, co
   p.rows_per_wg = pl.R;
   p.max_chunks = pl.max_chunks;
   p.qscale = shape->scale * kLog2e;
-  p.debug_stage = g_variant >= 10 ? g_variant - 10 : 0;
-  p.spec_P = g_variant == 6 ? 0 : cache->uniform_P;
+  p.spec_P = (cache->plan & BC_PLAN_IGNORE_PROMISE) ? 0 : cache->uniform_P;
   p.spec_cap = cache->uniform_cap;
 
   const int pairs = shape->B * shape->Hkv;
@@ -1090,41 +1185,50 @@ static int32_t launch_attention(const bc_shape* shape, const bc_cache* cache, co
     const int32_t st = enable_big_lds();
     if (st != BC_OK) return st;
     // launches that cannot saturate the memory system are latency-bound: default cache policy
-    const bool stream = (long)pairs * pl.max_chunks >= kStreamMinWorkgroups && g_variant != 4;
+    const bool cacheable = (cache->plan & BC_PLAN_CACHEABLE_LOADS) != 0;
+    const bool general = (cache->plan & BC_PLAN_GENERAL_LOOP) != 0;
+    const bool stream = (long)pairs * pl.max_chunks >= kStreamMinWorkgroups && !cacheable;
     // two workgroups per pair (each one half of the V columns) while that still fits the chip
     int slots = shape->B;                   // padded until the pairs are a multiple of 8
     while ((slots * shape->Hkv) & 7) ++slots;
     const bool vsplit = shape->d == 128 && pl.max_chunks == 1 && 2 * slots * shape->Hkv <= kLptMinPairs &&
-                        g_variant != 5;
+                        !(cache->plan & BC_PLAN_ONE_WORKGROUP_PER_PAIR);
     if (vsplit) {
       // K lines are read by both workgroups of a pair: streamed while the batch's K is small
       // enough for the partner's request to find the line still on its way or in the L2
       // (measured up to about 48 MB), cacheable beyond
-      const bool stream2 = 2L * pairs >= kStreamMinWorkgroups && g_variant != 4;
+      const bool stream2 = 2L * pairs >= kStreamMinWorkgroups && !cacheable;
       const bool small_k = (int64_t)pairs * cache->max_cap * 256 <= (48LL << 20);
       // short caches: twelve waves (most sequences then need one pass); long ones: eight
       const bool w12 = cache->max_cap <= kSplitWaves12MaxCap;
-      auto kfn = p.debug_stage ? (w12 ? decode_lds_kernel<true, 1, 128, 2, 12> : decode_lds_kernel<true, 1, 128, 2, 8>)
-                 : !stream2    ? (w12 ? decode_lds_kernel<false, 0, 128, 2, 12> : decode_lds_kernel<false, 0, 128, 2, 8>)
-                 : small_k     ? (w12 ? decode_lds_kernel<false, 1, 128, 2, 12> : decode_lds_kernel<false, 1, 128, 2, 8>)
-                               : decode_lds_kernel<false, 2, 128, 2, 8>;
+      // at most two tiles per wave: the straight-line form of the kernel
+      const bool two = w12 && cache->max_cap <= 2 * kLdsWavesSplit * kTileRows && !general;
+      auto kfn = two ? (stream2 ? decode_lds_kernel<1, 128, 2, 12, true> : decode_lds_kernel<0, 128, 2, 12, true>)
+                 : !stream2 ? (w12 ? decode_lds_kernel<0, 128, 2, 12> : decode_lds_kernel<0, 128, 2, 8>)
+                 : small_k ? (w12 ? decode_lds_kernel<1, 128, 2, 12> : decode_lds_kernel<1, 128, 2, 8>)
+                           : decode_lds_kernel<2, 128, 2, 8>;
       const int nw = w12 ? kLdsWavesSplit : kLdsWaves;
       kfn<<<dim3(shape->Hkv, slots, 2), nw * 64, nw * 3 * kTileRows * 128, hs>>>(p);
     } else if (shape->d == 128) {
-      auto kfn = p.debug_stage
-                     ? (stream ? decode_lds_kernel<true, 1, 128, 1, 8> : decode_lds_kernel<true, 0, 128, 1, 8>)
-                     : (stream ? decode_lds_kernel<false, 1, 128, 1, 8> : decode_lds_kernel<false, 0, 128, 1, 8>);
+      auto kfn = stream ? decode_lds_kernel<1, 128, 1, 8> : decode_lds_kernel<0, 128, 1, 8>;
       // More pairs than the chip holds workgroups, and short caches: workgroups of four waves, two
       // per compute unit (64 KB of LDS each), so that one's start and end phases - tables, first
       // bytes, merge, store - overlap with the other's streaming.  Measured at 512 pairs of 512
       // rows: 28.2 -> 25.4 us; with long ragged sequences (2048 pairs of up to 2700 rows) the longest
       // streams set the pace and eight waves are faster (54.5 against 62.5 us).
       const bool four = pairs > kLptMinPairs && cache->max_cap <= kSplitWaves12MaxCap && stream &&
-                        !p.debug_stage && g_variant != 7;
-      if (four) decode_lds_kernel<false, 1, 128, 1, 4><<<grid, 4 * 64, kLdsBytes / 2, hs>>>(p);
+                        !(cache->plan & BC_PLAN_NO_SMALL_WORKGROUPS);
+      const bool two = pl.max_chunks == 1 && p.order == nullptr && !general &&
+                       cache->max_cap <= 2 * kLdsWaves * kTileRows;
+      if (four) decode_lds_kernel<1, 128, 1, 4><<<grid, 4 * 64, kLdsBytes / 2, hs>>>(p);
+      else if (two && stream) decode_lds_kernel<1, 128, 1, 8, true><<<grid, kLdsWaves * 64, kLdsBytes, hs>>>(p);
+      else if (two) decode_lds_kernel<0, 128, 1, 8, true><<<grid, kLdsWaves * 64, kLdsBytes, hs>>>(p);
       else kfn<<<grid, kLdsWaves * 64, kLdsBytes, hs>>>(p);
     } else {
-      auto kfn = stream ? decode_lds_kernel<false, 1, 64, 1, 8> : decode_lds_kernel<false, 0, 64, 1, 8>;
+      const bool two = pl.max_chunks == 1 && p.order == nullptr && !general &&
+                       cache->max_cap <= 2 * kLdsWaves * kTileRows;
+      auto kfn = two ? (stream ? decode_lds_kernel<1, 64, 1, 8, true> : decode_lds_kernel<0, 64, 1, 8, true>)
+                     : (stream ? decode_lds_kernel<1, 64, 1, 8> : decode_lds_kernel<0, 64, 1, 8>);
       kfn<<<grid, kLdsWaves * 64, kLdsBytes / 2, hs>>>(p);
     }
   } else if (shape->kv_dtype == BC_BF16) {
@@ -1148,8 +1252,9 @@ static int32_t check_attention_args(const bc_shape* shape, const bc_cache* cache
   if (!q || !out || !aligned16(q) || !aligned16(out)) return BC_ERR_ARG;
   if (shape->B > 65535 || shape->Hkv > 65535) return BC_ERR_SHAPE;      // grid dimensions
   if (!nonnegative_finite(shape->scale)) return BC_ERR_ARG;   // the kernels take maxima of unscaled scores
-  *pl = make_plan(shape, cache->max_cap, g_rows_per_wg, g_variant);
-  if (g_variant == 2 && !pl->lds) return BC_ERR_SHAPE;
+  if (cache->rows_per_workgroup < 0 || (cache->plan & ~BC_PLAN_ALL_BITS)) return BC_ERR_ARG;
+  *pl = make_plan(shape, cache->max_cap, cache->rows_per_workgroup, cache->plan);
+  if ((cache->plan & BC_PLAN_NEED_MATRIX_KERNEL) && !pl->lds) return BC_ERR_SHAPE;
   if (!workspace || !aligned16(workspace) || workspace_bytes < pl->total()) return BC_ERR_WORKSPACE;
   return BC_OK;
 }
@@ -1162,11 +1267,6 @@ int32_t launch_budget_apply(const bc_shape* shape, uint8_t* live, int32_t* mark,
 }  // namespace bc
 
 using namespace bc;
-
-extern "C" void bc_set_decode_tuning(int32_t rows_per_workgroup, int32_t variant) {
-  g_rows_per_wg = rows_per_workgroup > 0 ? rows_per_workgroup : 0;
-  g_variant = variant;
-}
 
 extern "C" int32_t bc_sort_by_length(const bc_shape* shape, const bc_cache* cache,
                                      const uint8_t* active, int32_t* order, void* stream) {
@@ -1187,7 +1287,7 @@ extern "C" size_t bc_decode_workspace_bytes(const bc_shape* shape, int32_t max_c
   if (check_shape(shape) != BC_OK || max_cap < 1) return 0;
   // sized for the largest number of chunks the automatic plan can select, for either kernel
   const DecodePlan a = make_plan(shape, max_cap, kPlanForSizing, 0),
-                   b = make_plan(shape, max_cap, kPlanForSizing, 1);
+                   b = make_plan(shape, max_cap, kPlanForSizing, BC_PLAN_PLAIN_ALU);
   return a.total() > b.total() ? a.total() : b.total();
 }
 

@@ -5,8 +5,8 @@ import re
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _declared():
-    text = open(os.path.join(ROOT, "include", "bc.h")).read()
+def _declared(header="bc.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(bc_[a-z_]+)\s*\(", text)))
 
@@ -23,6 +23,12 @@ def test_header_symbols_are_exported_and_bound():
     assert sorted(bc.EXPORTS) == names
     assert bc.bc_version() >= 100
     assert bc.bc_status_str(0) == "ok" and "shape" in bc.bc_status_str(-2)
+    # the measurement aids live in a library of their own, not in the product library
+    diag = bc.load_diag()
+    dnames = _declared("bc_diag.h")
+    assert dnames == sorted(bc.DIAG_EXPORTS)
+    for n in dnames:
+        assert hasattr(diag, n) and hasattr(bc, n) and not hasattr(lib, n), n
 
 
 def test_struct_layouts_match_header():
@@ -30,9 +36,10 @@ def test_struct_layouts_match_header():
     from paper_2510_13797_amd import bc
     assert C.sizeof(bc.bc_shape) == 24
     assert bc.bc_shape.scale.offset == 20
-    assert C.sizeof(bc.bc_cache) == 96 and bc.bc_cache.max_cap.offset == 72
+    assert C.sizeof(bc.bc_cache) == 104 and bc.bc_cache.max_cap.offset == 72
     assert bc.bc_cache.order.offset == 80
     assert bc.bc_cache.uniform_P.offset == 88 and bc.bc_cache.uniform_cap.offset == 92
+    assert bc.bc_cache.rows_per_workgroup.offset == 96 and bc.bc_cache.plan.offset == 100
 
 
 def test_header_is_plain_c_and_agrees_with_the_binding(tmp_path):
@@ -48,12 +55,13 @@ def test_header_is_plain_c_and_agrees_with_the_binding(tmp_path):
         pytest.skip("no host C compiler")
     src = tmp_path / "layout.c"
     src.write_text(
-        '#include <stdio.h>\n#include <stddef.h>\n#include "bc.h"\n'
+        '#include <stdio.h>\n#include <stddef.h>\n#include "bc.h"\n#include "bc_diag.h"\n'
         'int main(void) {\n'
-        '  printf("%zu %zu %zu %zu %zu %zu %zu %zu %zu\\n", sizeof(bc_shape), offsetof(bc_shape, scale),\n'
+        '  printf("%zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu\\n", sizeof(bc_shape), offsetof(bc_shape, scale),\n'
         '         sizeof(bc_cache), offsetof(bc_cache, base), offsetof(bc_cache, err),\n'
         '         offsetof(bc_cache, max_cap), offsetof(bc_cache, order),\n'
-        '         offsetof(bc_cache, uniform_P), offsetof(bc_cache, uniform_cap));\n'
+        '         offsetof(bc_cache, uniform_P), offsetof(bc_cache, uniform_cap),\n'
+        '         offsetof(bc_cache, rows_per_workgroup), offsetof(bc_cache, plan));\n'
         '  return 0;\n}\n')
     exe = tmp_path / "layout"
     subprocess.check_call([cc, "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"),
@@ -61,7 +69,8 @@ def test_header_is_plain_c_and_agrees_with_the_binding(tmp_path):
     got = [int(x) for x in subprocess.check_output([str(exe)]).split()]
     want = [C.sizeof(bc.bc_shape), bc.bc_shape.scale.offset, C.sizeof(bc.bc_cache),
             bc.bc_cache.base.offset, bc.bc_cache.err.offset, bc.bc_cache.max_cap.offset,
-            bc.bc_cache.order.offset, bc.bc_cache.uniform_P.offset, bc.bc_cache.uniform_cap.offset]
+            bc.bc_cache.order.offset, bc.bc_cache.uniform_P.offset, bc.bc_cache.uniform_cap.offset,
+            bc.bc_cache.rows_per_workgroup.offset, bc.bc_cache.plan.offset]
     assert got == want, (got, want)
 
 

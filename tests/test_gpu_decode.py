@@ -303,12 +303,12 @@ def test_longest_first_dispatch_large_ragged_batch(dev, B, Hq, Hkv, dtype, d):
     for act in (None, active):
         rt.out.fill_(-3.0)
         a = rt.decode_attn(q, active=act).cpu().numpy().copy()
-        bc.bc_set_decode_tuning(0, 3)
+        rt.cache.plan = bc.BC_PLAN_IGNORE_ORDER          # the same call in index order
         try:
             rt.out.fill_(-3.0)
             b = rt.decode_attn(q, active=act).cpu().numpy().copy()
         finally:
-            bc.bc_set_decode_tuning(0, 0)
+            rt.cache.plan = 0
         assert np.array_equal(a, b)
         seqs = [s for s in range(B) if act is None or act[s]]
         check_attention(a, q, oc, wl, seqs, 99)
@@ -478,11 +478,11 @@ def test_deterministic_and_split_invariant(dev):
     a = rt.decode_attn(q).clone()
     b = rt.decode_attn(q).clone()
     assert torch.equal(a, b)                               # fixed merge order
+    rt.cache.rows_per_workgroup = 512                   # a forced chunk size, for this call only
     try:
-        bc.bc_set_decode_tuning(512, 0)
         c = rt.decode_attn(q).clone()
     finally:
-        bc.bc_set_decode_tuning(0, 0)
+        rt.cache.rows_per_workgroup = 0
     assert float((a - c).abs().max()) < 1e-5               # independent of the split factor
     assert not torch.equal(a, torch.zeros_like(a))
 

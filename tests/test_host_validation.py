@@ -19,7 +19,7 @@ def shape(B=2, Hq=4, Hkv=1, d=64, dtype=bc.BC_F32, scale=0.125):
 
 def cache(**kw):
     f = dict(k_slab=PTR, v_slab=PTR, base=PTR, cap=PTR, P=PTR, c=PTR, nb=PTR, w=PTR, err=PTR,
-             max_cap=64, order=None, uniform_P=0, uniform_cap=0)
+             max_cap=64, order=None, uniform_P=0, uniform_cap=0, rows_per_workgroup=0, plan=0)
     f.update(kw)
     return bc.bc_cache(**f)
 
@@ -121,14 +121,22 @@ def test_decode_entry_points_check_their_own_pointers_and_the_workspace():
                                     None) == bc.BC_ERR_ARG
 
 
-def test_forced_matrix_kernel_rejects_fp32_shapes():
-    # tuning variant 2 asks for the bf16 matrix-core kernel; an fp32 cache cannot run on it
-    s, c = shape(dtype=bc.BC_F32), cache()
-    try:
-        bc.bc_set_decode_tuning(0, 2)
-        assert bc.bc_decode_attn(s, c, PTR, PTR, None, PTR, 1 << 30, None) == bc.BC_ERR_SHAPE
-    finally:
-        bc.bc_set_decode_tuning(0, 0)
+def test_plan_fields_are_checked_per_call():
+    # the plan travels with the call: asking for the bf16 matrix-core kernel on an fp32 cache is a
+    # shape error, an unknown plan bit or a negative chunk size an argument error
+    s = shape(dtype=bc.BC_F32)
+    need = cache(plan=bc.BC_PLAN_NEED_MATRIX_KERNEL)
+    assert bc.bc_decode_attn(s, need, PTR, PTR, None, PTR, 1 << 30, None) == bc.BC_ERR_SHAPE
+    assert bc.bc_decode_attn(s, cache(plan=1 << 20), PTR, PTR, None, PTR, 1 << 30, None) == bc.BC_ERR_ARG
+    assert bc.bc_decode_attn(s, cache(rows_per_workgroup=-1), PTR, PTR, None, PTR, 1 << 30,
+                             None) == bc.BC_ERR_ARG
+    assert bc.bc_decode_step(s, cache(plan=1 << 20), PTR, PTR, PTR, PTR, None, None, None, PTR, 1 << 30,
+                             None) == bc.BC_ERR_ARG
+    # a forced chunk size on a large batch may need more workspace than the sizing call promises
+    big = shape(B=128, Hq=4, Hkv=1, d=128, dtype=bc.BC_BF16)
+    need_ws = bc.bc_decode_workspace_bytes(big, 4096)
+    many = cache(max_cap=4096, rows_per_workgroup=256)       # 16 chunks per sequence
+    assert bc.bc_decode_attn(big, many, PTR, PTR, None, PTR, need_ws, None) == bc.BC_ERR_WORKSPACE
 
 
 def test_cache_maintenance_entry_points():
@@ -204,11 +212,16 @@ def test_distillation_and_diagnostic_entry_points():
     assert grad(dz=None) == bc.BC_ERR_ARG
     assert grad(dz=PTR, z=PTR) == bc.BC_ERR_ARG    # in-place gradients are not supported
 
-    assert bc.bc_diag_stream_read(PTR, 1 << 20, 0, PTR, None) == bc.BC_ERR_ARG
-    assert bc.bc_diag_stream_read(PTR, 1 << 20, 65537, PTR, None) == bc.BC_ERR_ARG
-    assert bc.bc_diag_stream_read(PTR, (1 << 20) + 8, 256, PTR, None) == bc.BC_ERR_ARG
-    assert bc.bc_diag_stream_read(ODD, 1 << 20, 256, PTR, None) == bc.BC_ERR_ARG
-    assert bc.bc_diag_stream_read(None, 1 << 20, 256, PTR, None) == bc.BC_ERR_ARG
+
+
+def test_measurement_aid_checks_its_arguments():
+    assert bc.bc_diag_stream_read(PTR, 1 << 20, 0, 0, PTR, None) == bc.BC_ERR_ARG
+    assert bc.bc_diag_stream_read(PTR, 1 << 20, 65537, 0, PTR, None) == bc.BC_ERR_ARG
+    assert bc.bc_diag_stream_read(PTR, (1 << 20) + 8, 256, 0, PTR, None) == bc.BC_ERR_ARG
+    assert bc.bc_diag_stream_read(PTR, (1 << 20) + 16, 256, 1, PTR, None) == bc.BC_ERR_ARG
+    assert bc.bc_diag_stream_read(ODD, 1 << 20, 256, 0, PTR, None) == bc.BC_ERR_ARG
+    assert bc.bc_diag_stream_read(None, 1 << 20, 256, 0, PTR, None) == bc.BC_ERR_ARG
+    assert bc.bc_diag_stream_read(PTR, 1 << 20, 256, 2, PTR, None) == bc.BC_ERR_ARG
 
 
 def test_every_status_has_its_own_text():
