@@ -176,6 +176,15 @@ size_t bc_decode_workspace_bytes(const bc_shape *shape, int32_t max_cap);
  * allocated zero-filled needs no call.  Enqueues a fill kernel, no memset node. */
 int32_t bc_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
 
+/* Which kernel, grid and chunking the decode calls use for this shape and cache (HOST fields of
+ * `cache` only: max_cap, order, the layout promise, rows_per_workgroup, plan; nothing on the
+ * device is read).  Writes a NUL-terminated line to text[text_bytes] (HOST memory), cut short if
+ * it does not fit; the kernel's name is spelled as profilers print it.  For logs and for
+ * benchmarks that report which kernel they timed.  Same status codes as bc_decode_attn for a bad
+ * shape, cache or plan; text == NULL or text_bytes == 0 is BC_ERR_ARG. */
+int32_t bc_decode_plan_describe(const bc_shape *shape, const bc_cache *cache, char *text,
+                                size_t text_bytes);
+
 /* Single-token grouped-query attention over the resident entries (Sec. 2, Sec. 3.1:
  * generation proceeds as in a vanilla Transformer over what is in the cache):
  *   out[s,h,:] = sum_j softmax_j(scale * q[s,h,:] . K_j[kvh,:]) V_j[kvh,:],

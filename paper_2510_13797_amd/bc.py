@@ -31,7 +31,7 @@ BC_PLAN_GENERAL_LOOP = 128
 
 EXPORTS = [
     "bc_status_str", "bc_version", "bc_cache_init", "bc_cache_admit", "bc_append_kv",
-    "bc_decode_workspace_bytes", "bc_workspace_init", "bc_decode_attn",
+    "bc_decode_workspace_bytes", "bc_workspace_init", "bc_decode_plan_describe", "bc_decode_attn",
     "bc_compress_evict", "bc_decode_step", "bc_beacon_step", "bc_decode_step_budget", "bc_set_ratio",
     "bc_sort_by_length",
     "bc_prefill_attn", "bc_prefill_bwd_workspace_bytes", "bc_prefill_attn_bwd",
@@ -89,6 +89,8 @@ def load():
     lib.bc_decode_workspace_bytes.argtypes = [sp, i32]
     lib.bc_workspace_init.restype = i32
     lib.bc_workspace_init.argtypes = [vp, sz, vp]
+    lib.bc_decode_plan_describe.restype = i32
+    lib.bc_decode_plan_describe.argtypes = [sp, cp, C.c_char_p, sz]
     lib.bc_decode_attn.restype = i32
     lib.bc_decode_attn.argtypes = [sp, cp, vp, vp, vp, vp, sz, vp]
     lib.bc_compress_evict.restype = i32
@@ -170,6 +172,13 @@ def bc_decode_workspace_bytes(shape, max_cap):
 
 def bc_workspace_init(ws, nbytes, stream):
     return load().bc_workspace_init(ws, nbytes, stream)
+
+
+def bc_decode_plan_describe(shape, cache):
+    """-> (status, text): the kernel, grid and chunking the decode calls use for this shape and cache."""
+    buf = C.create_string_buffer(512)
+    st = load().bc_decode_plan_describe(C.byref(shape), C.byref(cache), buf, len(buf))
+    return st, buf.value.decode()
 
 
 def bc_decode_attn(shape, cache, q, out, active, ws, ws_bytes, stream):

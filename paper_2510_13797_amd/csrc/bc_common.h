@@ -73,6 +73,24 @@ __device__ __forceinline__ void lds_dma16(const char* g, const char* lds_dst) {
                  : : "s"(a), "v"(g) : "memory");
 }
 
+// The same with the address given as a base in scalar registers plus a 32-bit byte offset per lane
+// and the LDS address as a number: no 64-bit vector arithmetic and no pointer conversion per
+// instruction, which is what the issue rate of a tile's loads is bound by otherwise.
+template <bool STREAM>
+__device__ __forceinline__ void lds_dma16_s(uint32_t lane_offset, uint64_t base, uint32_t lds_addr) {
+  if (STREAM)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt"
+                 : : "s"(lds_addr), "v"(lane_offset), "s"(base) : "memory");
+  else
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 : : "s"(lds_addr), "v"(lane_offset), "s"(base) : "memory");
+}
+// The number an LDS pointer stands for (uniform over the wave).
+__device__ __forceinline__ uint32_t lds_address(const char* lds_ptr) {
+  return __builtin_amdgcn_readfirstlane(
+      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)lds_ptr);
+}
+
 // A 16-byte load into registers that the compiler does not count either (same reason).  The value
 // is there only after an explicit wait: nothing may read the result before it.
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
@@ -80,6 +98,11 @@ template <bool STREAM>
 __device__ __forceinline__ void load16_uncounted(u32x4_t& dst, const char* g) {
   if (STREAM) asm volatile("global_load_dwordx4 %0, %1, off nt" : "=v"(dst) : "v"(g) : "memory");
   else asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(g) : "memory");
+}
+template <bool STREAM>
+__device__ __forceinline__ void load16_uncounted_s(u32x4_t& dst, uint32_t lane_offset, uint64_t base) {
+  if (STREAM) asm volatile("global_load_dwordx4 %0, %1, %2 nt" : "=v"(dst) : "v"(lane_offset), "s"(base) : "memory");
+  else asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(dst) : "v"(lane_offset), "s"(base) : "memory");
 }
 // The point from which such a register may be used: right behind the explicit wait that covers its
 // load.  Emits no instruction (the comment names the register for the check of the generated code:

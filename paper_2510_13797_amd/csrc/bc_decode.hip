@@ -20,6 +20,9 @@
 //  * decode_valu_kernel (fp32): rows held in registers, 16 bytes per lane, plain
 //    FMA dot products completed by a DPP all-reduce.
 #include <atomic>
+#include <cstdint>
+#include <cstdio>
+#include <type_traits>
 #include "bc_common.h"
 
 namespace bc {
@@ -329,7 +332,7 @@ __device__ __forceinline__ void merge_waves_and_store4(const DecodeParams& p, co
       o += ow[wv] * a;
     }
     if (pi.nchunks == 1) {
-      const float inv = 1.0f / lsum;
+      const float inv = __builtin_amdgcn_rcpf(lsum);      // (one rounding error of the hardware reciprocal)
       __builtin_nontemporal_store(o * inv, reinterpret_cast<f32x4_t*>(outp + h * DOUT + x));
     } else {
       __builtin_nontemporal_store(o, reinterpret_cast<f32x4_t*>(po + h * D + x));
@@ -484,21 +487,43 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
     asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(newrow_v) : "v"(src) : "memory");
   };
   // HBM -> LDS: the K part of a tile (NDMA instructions, each RPI whole rows = 1 KB), then this
-  // workgroup's V part, 16-byte units XOR-swizzled by the row.  Rows beyond `last_row` are read
-  // from `last_row` instead (they are masked later; the loads stay inside the resident rows).
-  auto request_tile_dma = [&](const char* kb_, const char* vb_, int trow0, int last_row) {
+  // workgroup's V part, 16-byte units XOR-swizzled by the row.  Addresses are a base in scalar
+  // registers plus a 32-bit offset per lane.  CLAMP: rows beyond `last_row` are read from
+  // `last_row` instead (they are masked later; the loads stay inside the resident rows); without
+  // it the tile's rows must all exist, and the lane offsets do not depend on the tile.
+  const uint32_t wk_lds = lds_address(lds) + wave * (TILEB + VTILEB), wv_lds = wk_lds + TILEB;
+  auto request_tile_dma = [&](auto clamp, uint64_t kb_, uint64_t vb_, int trow0, int last_row) {
+    constexpr bool CLAMP = decltype(clamp)::value;
 #pragma unroll
     for (int j = 0; j < NDMA; ++j) {
       const int row = RPI * j + r4;
-      const int grow = min(trow0 + row, last_row);
-      lds_dma16<KSTREAM>(kb_ + (int64_t)grow * ROWB + ((pos ^ tile_swz<D>(row)) << 4), wk + j * 1024);
+      const uint32_t unit = (uint32_t)(pos ^ tile_swz<D>(row)) << 4;
+      if constexpr (CLAMP)
+        lds_dma16_s<KSTREAM>((uint32_t)min(trow0 + row, last_row) * ROWB + unit, kb_, wk_lds + j * 1024);
+      else
+        lds_dma16_s<KSTREAM>((uint32_t)r4 * ROWB + unit, kb_ + (uint64_t)(trow0 + RPI * j) * ROWB, wk_lds + j * 1024);
     }
 #pragma unroll
     for (int j = 0; j < VNDMA; ++j) {
       const int vrow = VRPI * j + r4v;
-      const int vgrow = min(trow0 + vrow, last_row);
-      lds_dma16<VSTREAM>(vb_ + (int64_t)vgrow * ROWB + ((posv ^ tile_swz<DV>(vrow)) << 4), wv + j * 1024);
+      const uint32_t unit = (uint32_t)(posv ^ tile_swz<DV>(vrow)) << 4;
+      if constexpr (CLAMP)
+        lds_dma16_s<VSTREAM>((uint32_t)min(trow0 + vrow, last_row) * ROWB + unit, vb_, wv_lds + j * 1024);
+      else
+        lds_dma16_s<VSTREAM>((uint32_t)r4v * ROWB + unit, vb_ + (uint64_t)(trow0 + VRPI * j) * ROWB, wv_lds + j * 1024);
     }
+  };
+  // (not initialised, and written by request_tile_regs only: the loads are invisible to the
+  // compiler, so a register-to-register copy between a load and its wait would copy what is not
+  // there yet; the check of the generated code looks for exactly that)
+  u32x4_t kreg[NDMA], vreg[VNDMA];
+  auto request_tile_regs = [&](uint64_t kb_, uint64_t vb_, int trow0, int last_row) {
+#pragma unroll
+    for (int j = 0; j < NDMA; ++j)
+      load16_uncounted_s<KSTREAM>(kreg[j], (uint32_t)min(trow0 + RPI * j + r4, last_row) * ROWB + (pos << 4), kb_);
+#pragma unroll
+    for (int j = 0; j < VNDMA; ++j)
+      load16_uncounted_s<VSTREAM>(vreg[j], (uint32_t)min(trow0 + VRPI * j + r4v, last_row) * ROWB + (posv << 4), vb_);
   };
   if constexpr (SHORT) {            // the sequence is the slot: nothing here needs the tables
     request_query(slot);
@@ -506,17 +531,21 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
   }
   // Prompt rows never change and are always resident.  When the caller has promised the slab
   // geometry (every sequence: P = spec_P, cap = spec_cap, base = index * spec_cap), a wave whose
-  // first tile lies inside the prompt requests it before the tables are back.
+  // first tile lies inside the prompt requests it before the tables are back; whatever the
+  // tables say afterwards decides: if the geometry is another, the tile is requested again.
+  // (Requesting the tiles behind the prompt early as well, under a promised number of resident
+  // rows, was measured: with everything asked for at once the step is 2 % slower.)
   bool early_tile = false;
-  auto request_prompt_tile = [&]() {
+  auto request_early_tiles = [&]() {
     if (p.spec_P > 0 && p.order == nullptr && p.max_chunks == 1 && (wave + 1) * kTileRows <= p.spec_P) {
       const int64_t off_ = ((int64_t)slot * p.spec_cap * p.Hkv + (int64_t)kvh0 * p.spec_cap) * ROWB;
-      request_tile_dma(p.k_slab + off_, p.v_slab + off_ + vhalf * VROWB, wave * kTileRows, p.spec_P - 1);
+      request_tile_dma(std::false_type{}, (uint64_t)(p.k_slab + off_), (uint64_t)(p.v_slab + off_ + vhalf * VROWB),
+                       wave * kTileRows, 0);
       early_tile = true;
     }
   };
   const PairInfo pi = VS == 1 && !SHORT ? pair_info(p, slot, kvh0, (int)blockIdx.x)
-                                        : pair_info(p, slot, kvh0, 0, request_prompt_tile);
+                                        : pair_info(p, slot, kvh0, 0, request_early_tiles);
   // Tiles wave, wave + NW, ... of the chunk belong to this wave.
   const int ntiles = (pi.row_end - pi.row0 + kTileRows - 1) / kTileRows;
   bool nothing_to_do = !pi.live;
@@ -529,6 +558,8 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
     }
   }
   if (nothing_to_do) { wait_vmcnt<0>(); return; }
+  // rows the tile loads may touch: the resident rows that are already in the slab
+  const int last_slab_row = max((pi.new_row >= 0 ? pi.new_row : pi.L) - 1, 0);
   if (early_tile && (pi.P != p.spec_P || pi.cap != p.spec_cap || pi.base != (int64_t)pi.s * p.spec_cap))
     early_tile = false;      // the promise does not hold here: the tile is requested again below
 
@@ -536,12 +567,11 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
   const int64_t stream_off = (pi.base * p.Hkv + (int64_t)pi.kvh * pi.cap) * ROWB;
   const char* kbase = p.k_slab + stream_off;
   const char* vbase = p.v_slab + stream_off + vhalf * VROWB;
+  const uint64_t kbase_s = (uint64_t)kbase, vbase_s = (uint64_t)vbase;      // (uniform: scalar registers)
   if constexpr (!SHORT) {           // the sequence may come from the dispatch order: after the tables
     request_query(pi.s);
     request_new_row(pi.s);
   }
-  // rows the tile loads may touch: the resident rows that are already in the slab
-  const int last_slab_row = max((pi.new_row >= 0 ? pi.new_row : pi.L) - 1, 0);
 
   f32x4_t O[NJ];
 #pragma unroll
@@ -552,22 +582,6 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
   // time into registers, so both are in flight from the start.  Afterwards: copy the register
   // tile to LDS, request the next tile into the freed registers, compute - one tile always in
   // flight behind the one in use.
-  // (not initialised, and written at one place only: the loads are invisible to the compiler, so
-  // a register-to-register copy between a load and its wait - such as one that joins two
-  // definitions - would copy what is not there yet)
-  u32x4_t kreg[NDMA], vreg[VNDMA];
-  auto request_tile_regs = [&](int trow0) {
-#pragma unroll
-    for (int j = 0; j < NDMA; ++j) {
-      const int grow = min(trow0 + RPI * j + r4, last_slab_row);
-      load16_uncounted<KSTREAM>(kreg[j], kbase + (int64_t)grow * ROWB + (pos << 4));
-    }
-#pragma unroll
-    for (int j = 0; j < VNDMA; ++j) {
-      const int vrow = min(trow0 + VRPI * j + r4v, last_slab_row);
-      load16_uncounted<VSTREAM>(vreg[j], vbase + (int64_t)vrow * ROWB + (posv << 4));
-    }
-  };
   auto k_regs_to_lds = [&]() {
 #pragma unroll
     for (int j = 0; j < NDMA; ++j) {
@@ -595,8 +609,11 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
 #pragma unroll
     for (int j = 0; j < VNDMA; ++j) landed(vreg[j]);
   };
-  if (wave < ntiles && !early_tile)
-    request_tile_dma(kbase, vbase, pi.row0 + wave * kTileRows, last_slab_row);
+  if (wave < ntiles && !early_tile) {
+    const int trow0 = pi.row0 + wave * kTileRows;
+    if (trow0 + kTileRows <= last_slab_row + 1) request_tile_dma(std::false_type{}, kbase_s, vbase_s, trow0, 0);
+    else request_tile_dma(std::true_type{}, kbase_s, vbase_s, trow0, last_slab_row);
+  }
 
   // Fused step: every wave of every workgroup of the sequence takes a ticket as soon as its last
   // load from the slab has landed (the tables were read at the start); whoever draws the last one
@@ -727,7 +744,7 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
       query_landed();
       take_ticket();
     } else if (wave + NW < ntiles) {
-      request_tile_regs(trowB);
+      request_tile_regs(kbase_s, vbase_s, trowB, last_slab_row);
       wait_vmcnt<VNDMA + NDMA + VNDMA>();          // K of the first tile is in LDS
       query_landed();
       scores_and_softmax(trowA, true);
@@ -765,7 +782,7 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
         if (tile + NW < ntiles) {
           // the next tile of this wave goes to registers while this one is in use; the tile in
           // use has landed once at most those loads are pending
-          request_tile_regs(trow0 + NW * kTileRows);
+          request_tile_regs(kbase_s, vbase_s, trow0 + NW * kTileRows, last_slab_row);
           wait_vmcnt<NDMA + VNDMA>();
           query_landed();
           scores_and_softmax(trow0, tile == wave);
@@ -1100,6 +1117,71 @@ static void launch_valu(const DecodeParams& p, int G, dim3 grid, hipStream_t st)
   }
 }
 
+// Which instantiation of the LDS/MFMA kernel serves a call, with its launch shape.  `name` is the
+// kernel's name as profilers print it.
+struct LdsLaunch {
+  void (*fn)(DecodeParams);
+  const char* name;
+  dim3 grid;
+  int threads;
+  int lds_bytes;
+};
+#define BC_LDS_KERNEL(...) decode_lds_kernel<__VA_ARGS__>, "bc::decode_lds_kernel<" #__VA_ARGS__ ">"
+
+static LdsLaunch pick_lds_kernel(const bc_shape* shape, const bc_cache* cache, const DecodePlan& pl,
+                                 bool ordered) {
+  const int pairs = shape->B * shape->Hkv;
+  const dim3 grid(pl.max_chunks, shape->Hkv, shape->B);
+  // launches that cannot saturate the memory system are latency-bound: default cache policy
+  const bool cacheable = (cache->plan & BC_PLAN_CACHEABLE_LOADS) != 0;
+  const bool general = (cache->plan & BC_PLAN_GENERAL_LOOP) != 0;
+  const bool stream = (long)pairs * pl.max_chunks >= kStreamMinWorkgroups && !cacheable;
+  // at most two tiles per wave of an eight-wave workgroup: the straight-line form of the kernel
+  const bool two8 = pl.max_chunks == 1 && !ordered && !general && cache->max_cap <= 2 * kLdsWaves * kTileRows;
+  // two workgroups per pair (each one half of the V columns) while that still fits the chip
+  int slots = shape->B;                   // padded until the pairs are a multiple of 8
+  while ((slots * shape->Hkv) & 7) ++slots;
+  const bool vsplit = shape->d == 128 && pl.max_chunks == 1 && 2 * slots * shape->Hkv <= kLptMinPairs &&
+                      !(cache->plan & BC_PLAN_ONE_WORKGROUP_PER_PAIR);
+  if (vsplit) {
+    // K lines are read by both workgroups of a pair: streamed while the batch's K is small
+    // enough for the partner's request to find the line still on its way or in the L2
+    // (measured up to about 48 MB), cacheable beyond
+    const bool stream2 = 2L * pairs >= kStreamMinWorkgroups && !cacheable;
+    const bool small_k = (int64_t)pairs * cache->max_cap * 256 <= (48LL << 20);
+    // short caches: twelve waves (most sequences then need one pass); long ones: eight
+    const bool w12 = cache->max_cap <= kSplitWaves12MaxCap;
+    const bool two12 = w12 && cache->max_cap <= 2 * kLdsWavesSplit * kTileRows && !general;
+    const dim3 g2(shape->Hkv, slots, 2);
+    const int t12 = kLdsWavesSplit * 64, l12 = kLdsBytesSplit, t8 = kLdsWaves * 64, l8 = kLdsWaves * 3 * kTileRows * 128;
+    if (two12) return stream2 ? LdsLaunch{BC_LDS_KERNEL(1, 128, 2, 12, true), g2, t12, l12}
+                              : LdsLaunch{BC_LDS_KERNEL(0, 128, 2, 12, true), g2, t12, l12};
+    if (!stream2) return w12 ? LdsLaunch{BC_LDS_KERNEL(0, 128, 2, 12), g2, t12, l12}
+                             : LdsLaunch{BC_LDS_KERNEL(0, 128, 2, 8), g2, t8, l8};
+    if (small_k) return w12 ? LdsLaunch{BC_LDS_KERNEL(1, 128, 2, 12), g2, t12, l12}
+                            : LdsLaunch{BC_LDS_KERNEL(1, 128, 2, 8), g2, t8, l8};
+    return LdsLaunch{BC_LDS_KERNEL(2, 128, 2, 8), g2, t8, l8};
+  }
+  if (shape->d == 128) {
+    // More pairs than the chip holds workgroups, and short caches: workgroups of four waves, two
+    // per compute unit (64 KB of LDS each), so that one's start and end phases - tables, first
+    // bytes, merge, store - overlap with the other's streaming.  Measured at 512 pairs of 512
+    // rows: 28.2 -> 25.4 us; with long ragged sequences (512 pairs of up to 2700 rows) the longest
+    // streams set the pace and eight waves are faster (54.5 against 62.5 us).
+    const bool four = pairs > kLptMinPairs && cache->max_cap <= kSplitWaves12MaxCap && stream &&
+                      !(cache->plan & BC_PLAN_NO_SMALL_WORKGROUPS);
+    if (four) return LdsLaunch{BC_LDS_KERNEL(1, 128, 1, 4), grid, 4 * 64, kLdsBytes / 2};
+    if (two8) return stream ? LdsLaunch{BC_LDS_KERNEL(1, 128, 1, 8, true), grid, kLdsWaves * 64, kLdsBytes}
+                            : LdsLaunch{BC_LDS_KERNEL(0, 128, 1, 8, true), grid, kLdsWaves * 64, kLdsBytes};
+    return stream ? LdsLaunch{BC_LDS_KERNEL(1, 128, 1, 8), grid, kLdsWaves * 64, kLdsBytes}
+                  : LdsLaunch{BC_LDS_KERNEL(0, 128, 1, 8), grid, kLdsWaves * 64, kLdsBytes};
+  }
+  if (two8) return stream ? LdsLaunch{BC_LDS_KERNEL(1, 64, 1, 8, true), grid, kLdsWaves * 64, kLdsBytes / 2}
+                          : LdsLaunch{BC_LDS_KERNEL(0, 64, 1, 8, true), grid, kLdsWaves * 64, kLdsBytes / 2};
+  return stream ? LdsLaunch{BC_LDS_KERNEL(1, 64, 1, 8), grid, kLdsWaves * 64, kLdsBytes / 2}
+                : LdsLaunch{BC_LDS_KERNEL(0, 64, 1, 8), grid, kLdsWaves * 64, kLdsBytes / 2};
+}
+
 // The LDS kernel needs 128 KB of dynamic LDS: opt in once per device.  Two host threads that get
 // here together both set the (same) attributes; the flag only saves the later calls.
 static int32_t enable_big_lds() {
@@ -1139,6 +1221,13 @@ __global__ void fill_zero_kernel(uint32_t* p, int64_t n) {
     p[i] = 0u;
 }
 
+// Batches that need more than one round of workgroups follow the caller's dispatch order
+// (bc_sort_by_length), if there is one; with fewer workgroups everything starts at once.
+static bool follows_order(const bc_shape* shape, const bc_cache* cache, const DecodePlan& pl) {
+  return cache->order && pl.max_chunks == 1 && shape->B * shape->Hkv > kLptMinPairs &&
+         !(cache->plan & BC_PLAN_IGNORE_ORDER);
+}
+
 // Attention launch shared by bc_decode_attn (k = beacon_k = NULL) and the fused bc_decode_step.
 static int32_t launch_attention(const bc_shape* shape, const bc_cache* cache, const DecodePlan& pl,
                                 const void* q, float* out, const uint8_t* active, void* workspace,
@@ -1165,11 +1254,7 @@ static int32_t launch_attention(const bc_shape* shape, const bc_cache* cache, co
   p.budget = budget; p.live = live;
   p.beacon_row = beacon_row ? 1 : 0;
   p.B = shape->B;
-  // Batches that need more than one round of workgroups follow the caller's dispatch order
-  // (bc_sort_by_length), if there is one; with fewer workgroups everything starts at once.
-  p.order = (cache->order && pl.max_chunks == 1 && shape->B * shape->Hkv > kLptMinPairs &&
-             !(cache->plan & BC_PLAN_IGNORE_ORDER))
-                ? cache->order : nullptr;
+  p.order = follows_order(shape, cache, pl) ? cache->order : nullptr;
   p.Hq = shape->Hq; p.Hkv = shape->Hkv; p.g = shape->Hq / shape->Hkv;
   p.Gp = pl.Gp;
   p.D = shape->d;
@@ -1184,53 +1269,8 @@ static int32_t launch_attention(const bc_shape* shape, const bc_cache* cache, co
   if (pl.lds) {
     const int32_t st = enable_big_lds();
     if (st != BC_OK) return st;
-    // launches that cannot saturate the memory system are latency-bound: default cache policy
-    const bool cacheable = (cache->plan & BC_PLAN_CACHEABLE_LOADS) != 0;
-    const bool general = (cache->plan & BC_PLAN_GENERAL_LOOP) != 0;
-    const bool stream = (long)pairs * pl.max_chunks >= kStreamMinWorkgroups && !cacheable;
-    // two workgroups per pair (each one half of the V columns) while that still fits the chip
-    int slots = shape->B;                   // padded until the pairs are a multiple of 8
-    while ((slots * shape->Hkv) & 7) ++slots;
-    const bool vsplit = shape->d == 128 && pl.max_chunks == 1 && 2 * slots * shape->Hkv <= kLptMinPairs &&
-                        !(cache->plan & BC_PLAN_ONE_WORKGROUP_PER_PAIR);
-    if (vsplit) {
-      // K lines are read by both workgroups of a pair: streamed while the batch's K is small
-      // enough for the partner's request to find the line still on its way or in the L2
-      // (measured up to about 48 MB), cacheable beyond
-      const bool stream2 = 2L * pairs >= kStreamMinWorkgroups && !cacheable;
-      const bool small_k = (int64_t)pairs * cache->max_cap * 256 <= (48LL << 20);
-      // short caches: twelve waves (most sequences then need one pass); long ones: eight
-      const bool w12 = cache->max_cap <= kSplitWaves12MaxCap;
-      // at most two tiles per wave: the straight-line form of the kernel
-      const bool two = w12 && cache->max_cap <= 2 * kLdsWavesSplit * kTileRows && !general;
-      auto kfn = two ? (stream2 ? decode_lds_kernel<1, 128, 2, 12, true> : decode_lds_kernel<0, 128, 2, 12, true>)
-                 : !stream2 ? (w12 ? decode_lds_kernel<0, 128, 2, 12> : decode_lds_kernel<0, 128, 2, 8>)
-                 : small_k ? (w12 ? decode_lds_kernel<1, 128, 2, 12> : decode_lds_kernel<1, 128, 2, 8>)
-                           : decode_lds_kernel<2, 128, 2, 8>;
-      const int nw = w12 ? kLdsWavesSplit : kLdsWaves;
-      kfn<<<dim3(shape->Hkv, slots, 2), nw * 64, nw * 3 * kTileRows * 128, hs>>>(p);
-    } else if (shape->d == 128) {
-      auto kfn = stream ? decode_lds_kernel<1, 128, 1, 8> : decode_lds_kernel<0, 128, 1, 8>;
-      // More pairs than the chip holds workgroups, and short caches: workgroups of four waves, two
-      // per compute unit (64 KB of LDS each), so that one's start and end phases - tables, first
-      // bytes, merge, store - overlap with the other's streaming.  Measured at 512 pairs of 512
-      // rows: 28.2 -> 25.4 us; with long ragged sequences (2048 pairs of up to 2700 rows) the longest
-      // streams set the pace and eight waves are faster (54.5 against 62.5 us).
-      const bool four = pairs > kLptMinPairs && cache->max_cap <= kSplitWaves12MaxCap && stream &&
-                        !(cache->plan & BC_PLAN_NO_SMALL_WORKGROUPS);
-      const bool two = pl.max_chunks == 1 && p.order == nullptr && !general &&
-                       cache->max_cap <= 2 * kLdsWaves * kTileRows;
-      if (four) decode_lds_kernel<1, 128, 1, 4><<<grid, 4 * 64, kLdsBytes / 2, hs>>>(p);
-      else if (two && stream) decode_lds_kernel<1, 128, 1, 8, true><<<grid, kLdsWaves * 64, kLdsBytes, hs>>>(p);
-      else if (two) decode_lds_kernel<0, 128, 1, 8, true><<<grid, kLdsWaves * 64, kLdsBytes, hs>>>(p);
-      else kfn<<<grid, kLdsWaves * 64, kLdsBytes, hs>>>(p);
-    } else {
-      const bool two = pl.max_chunks == 1 && p.order == nullptr && !general &&
-                       cache->max_cap <= 2 * kLdsWaves * kTileRows;
-      auto kfn = two ? (stream ? decode_lds_kernel<1, 64, 1, 8, true> : decode_lds_kernel<0, 64, 1, 8, true>)
-                     : (stream ? decode_lds_kernel<1, 64, 1, 8> : decode_lds_kernel<0, 64, 1, 8>);
-      kfn<<<grid, kLdsWaves * 64, kLdsBytes / 2, hs>>>(p);
-    }
+    const LdsLaunch k = pick_lds_kernel(shape, cache, pl, p.order != nullptr);
+    k.fn<<<k.grid, k.threads, k.lds_bytes, hs>>>(p);
   } else if (shape->kv_dtype == BC_BF16) {
     if (shape->d == 128) launch_valu<bf16_t, 128>(p, pl.Gp, grid, hs);
     else launch_valu<bf16_t, 64>(p, pl.Gp, grid, hs);
@@ -1301,6 +1341,30 @@ extern "C" int32_t bc_workspace_init(void* workspace, size_t workspace_bytes, vo
   return launch_status();
 }
 
+extern "C" int32_t bc_decode_plan_describe(const bc_shape* shape, const bc_cache* cache, char* text,
+                                           size_t text_bytes) {
+  if (!text || text_bytes == 0) return BC_ERR_ARG;
+  text[0] = 0;
+  int32_t st = check_shape(shape);
+  if (st != BC_OK) return st;
+  st = check_cache(cache);
+  if (st != BC_OK) return st;
+  if (cache->rows_per_workgroup < 0 || (cache->plan & ~BC_PLAN_ALL_BITS)) return BC_ERR_ARG;
+  const DecodePlan pl = make_plan(shape, cache->max_cap, cache->rows_per_workgroup, cache->plan);
+  if ((cache->plan & BC_PLAN_NEED_MATRIX_KERNEL) && !pl.lds) return BC_ERR_SHAPE;
+  if (pl.lds) {
+    const LdsLaunch k = pick_lds_kernel(shape, cache, pl, follows_order(shape, cache, pl));
+    snprintf(text, text_bytes, "%s grid=(%u,%u,%u) threads=%d lds=%d chunks=%d%s", k.name, k.grid.x,
+             k.grid.y, k.grid.z, k.threads, k.lds_bytes, pl.max_chunks,
+             pl.max_chunks > 1 ? " + bc::decode_merge_kernel" : "");
+  } else {
+    snprintf(text, text_bytes, "bc::decode_valu_kernel<%s, %d, %d, 8> grid=(%d,%d,%d) threads=256 chunks=%d%s",
+             shape->kv_dtype == BC_BF16 ? "bc::bf16_t" : "float", shape->d, pl.Gp, pl.max_chunks,
+             shape->Hkv, shape->B, pl.max_chunks, pl.max_chunks > 1 ? " + bc::decode_merge_kernel" : "");
+  }
+  return BC_OK;
+}
+
 extern "C" int32_t bc_decode_attn(const bc_shape* shape, const bc_cache* cache, const void* q,
                                   float* out, const uint8_t* active, void* workspace,
                                   size_t workspace_bytes, void* stream) {
@@ -1311,26 +1375,34 @@ extern "C" int32_t bc_decode_attn(const bc_shape* shape, const bc_cache* cache, 
                           nullptr, as_stream(stream));
 }
 
-extern "C" int32_t bc_decode_step(const bc_shape* shape, const bc_cache* cache, const void* k,
-                                  const void* v, const void* q, float* out, const void* beacon_k,
-                                  const void* beacon_v, const uint8_t* active, void* workspace,
-                                  size_t workspace_bytes, void* stream) {
-  DecodePlan pl;
-  int32_t st = check_attention_args(shape, cache, q, out, workspace, workspace_bytes, &pl);
-  if (st != BC_OK) return st;
+// bc_decode_step behind its argument checks (shared with the allocation-free form)
+static int32_t decode_step_checked(const bc_shape* shape, const bc_cache* cache, const DecodePlan& pl,
+                                   const void* k, const void* v, const void* q, float* out,
+                                   const void* beacon_k, const void* beacon_v, const uint8_t* active,
+                                   void* workspace, void* stream) {
   if (!k || !v || !aligned16(k) || !aligned16(v)) return BC_ERR_ARG;
   if ((beacon_k == nullptr) != (beacon_v == nullptr)) return BC_ERR_ARG;
   if (beacon_k && (!aligned16(beacon_k) || !aligned16(beacon_v))) return BC_ERR_ARG;
   if (pl.lds)     // one launch: append, attention and eviction fused
     return launch_attention(shape, cache, pl, q, out, active, workspace, k, v, beacon_k, beacon_v,
                             as_stream(stream));
-  st = bc_append_kv(shape, cache, k, v, active, BC_ROW_TOKEN, stream);
+  int32_t st = bc_append_kv(shape, cache, k, v, active, BC_ROW_TOKEN, stream);
   if (st != BC_OK) return st;
   st = launch_attention(shape, cache, pl, q, out, active, workspace, nullptr, nullptr, nullptr,
                         nullptr, as_stream(stream));
   if (st != BC_OK) return st;
   if (beacon_k) st = bc_compress_evict(shape, cache, beacon_k, beacon_v, active, 1, stream);
   return st;
+}
+
+extern "C" int32_t bc_decode_step(const bc_shape* shape, const bc_cache* cache, const void* k,
+                                  const void* v, const void* q, float* out, const void* beacon_k,
+                                  const void* beacon_v, const uint8_t* active, void* workspace,
+                                  size_t workspace_bytes, void* stream) {
+  DecodePlan pl;
+  const int32_t st = check_attention_args(shape, cache, q, out, workspace, workspace_bytes, &pl);
+  if (st != BC_OK) return st;
+  return decode_step_checked(shape, cache, pl, k, v, q, out, beacon_k, beacon_v, active, workspace, stream);
 }
 
 extern "C" int32_t bc_beacon_step(const bc_shape* shape, const bc_cache* cache, const void* k,

@@ -48,3 +48,23 @@ def test_stored_traffic_figures_are_read_from_the_profiles():
     assert bench.stored_value("prefill_fwd_traffic_bytes") >= fwd_alg
     assert bench.stored_value("distill_bwd_traffic_bytes") >= 2 * 4096 * 151936 * 2
     assert bench.stored_value("no_such_key") is None
+
+
+def test_tables_and_rows_of_a_state_follow_the_closed_forms():
+    wl = W.ragged256()
+    t = np.minimum(int(wl.extra["T"]), wl.G)
+    nb, w = bench.tables_at(wl, t)
+    rows = bench.rows_seen(wl, t)
+    for s in range(0, wl.B, 17):
+        P, c, ts = int(wl.P[s]), int(wl.c[s]), int(t[s])
+        assert (int(nb[s]), int(w[s])) == (ts // c, ts % c)
+        assert int(rows[s]) == OR.len_at_attention(P, c, ts)
+        # the state after t tokens is what the attention of step t + 1 sees, minus the new row
+        assert int(wl.P[s]) + int(nb[s]) + int(w[s]) == OR.len_after_step(P, c, ts)
+    wl0 = W.batch64(c=0)
+    nb0, w0 = bench.tables_at(wl0, 100)
+    assert nb0[0] == 0 and w0[0] == 100 and bench.rows_seen(wl0, 100)[0] == 356
+
+
+def test_host_cores_is_bounded():
+    assert 1 <= bench.host_cores() <= 16

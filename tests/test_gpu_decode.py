@@ -66,11 +66,13 @@ def check_attention(o, q, oc, wl, seqs=None, t=None):
 
 
 def rollout(wl, rt, oc, steps, attn_steps, slab_steps, table_every=1, tail_form=False,
-            use_step_call=False, seq_sample=None, beacon_call=False):
+            use_step_call=False, seq_sample=None, beacon_call=False, before_step=None):
     """Alg. 1 for `steps` decode steps; sequences whose generation is over stay resident."""
     attn_steps, slab_steps = set(attn_steps), set(slab_steps)
     worst = 0.0
     for t in range(1, steps + 1):
+        if before_step is not None:
+            before_step(t)
         active = (wl.G >= t).astype(np.uint8)
         act = None if active.all() else active
         k, v = wl.step_kv(t)
@@ -184,6 +186,28 @@ def test_uniform_layout_promise_is_only_a_hint(dev, promise, Hkv, d):
     elif promise == "prompt too short":
         rt.cache.uniform_P = 64
     rollout(wl, rt, oc, G, (1, 2, 8, 9, 33, 60), (8, 60), use_step_call=True)
+
+
+@pytest.mark.parametrize("B,Hkv,d,P", [(12, 2, 128, 410), (40, 4, 128, 270), (12, 2, 64, 270)])
+def test_second_tiles_of_the_straight_line_kernel(dev, B, Hkv, d, P):
+    # short caches run on the straight-line form of the kernel, where a wave has at most two tiles:
+    # 24 pairs, d = 128: two twelve-wave workgroups per pair, second tiles from row 384; 160 pairs,
+    # and d = 64: eight waves, second tiles from row 256.  The rollout crosses those rows, with the
+    # appended row in a first tile, in a second tile and on a tile boundary.
+    G, c = 70, 8
+    wl = W.Workload("twotiles", 98, B, 2 * Hkv, Hkv, d, "bf16", np.full(B, P, np.int32),
+                    np.where(np.arange(B) % 3 == 2, 40, G).astype(np.int32), np.full(B, c, np.int32))
+    rt, oc = make(wl, dev, np.full(B, P + G // c + c + 1, np.int32))       # one capacity: uniform layout
+    st, text = _bc().bc_decode_plan_describe(rt.shape, rt.cache)
+    assert st == 0 and "true>" in text, text          # the straight-line kernel serves these shapes
+    rollout(wl, rt, oc, G, range(1, G + 1), (8, 40, G), use_step_call=True)
+    q = wl.step_q(G + 1)
+    check_attention(rt.decode_attn(q).cpu().numpy(), q, oc, wl, None, "attn")
+    # the same rows on the general tile loop
+    rt.cache.plan = _bc().BC_PLAN_GENERAL_LOOP
+    st, text = _bc().bc_decode_plan_describe(rt.shape, rt.cache)
+    assert st == 0 and "true>" not in text, text
+    check_attention(rt.decode_attn(q).cpu().numpy(), q, oc, wl, None, "attn, general loop")
 
 
 @pytest.mark.parametrize("Hq,Hkv,dtype,d", [(1, 1, "bf16", 128), (4, 2, "bf16", 128), (3, 1, "bf16", 128),

@@ -136,11 +136,15 @@ def reads_of_inflight_registers(body):
                 return [(target, learned(vcc_if_taken))] + [(j, learned(-1 - vcc_if_taken)) for j in nxt]
             return [(j, state) for j in nxt] + [(target, state)]
         # ordinary instruction: hazards first
-        touched = _registers(line[len(op):])
+        is_hand_load = hand[i] and op.startswith(("global_load", "global_atomic")) and not op.startswith("global_load_lds")
+        # (a hand-written load may be issued again to the registers of one that is still
+        # outstanding - an early request repeated with other addresses: loads return in order, the
+        # later one wins - so only its address operands count as touched)
+        touched = _registers(",".join(line[len(op):].split(",")[1:]) if is_hand_load else line[len(op):])
         for reg, k in out_regs:
             if reg in touched:
                 found.add((body[k], line))
-        if hand[i] and op.startswith(("global_load", "global_atomic")) and not op.startswith("global_load_lds"):
+        if is_hand_load:
             dst = set()
             m = re.match(r"global_load_\w+ (v\[\d+:\d+\]|v\d+),", line)
             if m:
