@@ -220,6 +220,22 @@ int32_t bc_decode_step(const bc_shape *shape, const bc_cache *cache, const void 
                        const void *beacon_v, const uint8_t *active, void *workspace,
                        size_t workspace_bytes, void *stream);
 
+/* bc_decode_step for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
+ * and semantics as bc_decode_step without the workspace: the counters and partial results live in
+ * a fixed array of BC_NOALLOC_SCRATCH_BYTES in device memory that belongs to the library (one copy
+ * per GPU it runs on, held until the process ends).  The call allocates and frees nothing.  Its
+ * plan must fit the array: B * 128 bytes of counters, plus - only for batches of fewer than 128
+ * (sequence, KV head) pairs whose sequences are split into chunks, or a forced chunk size - the
+ * partial results of bc_decode_workspace_bytes(); a call that needs more returns BC_ERR_WORKSPACE
+ * and launches nothing.  Every call on one GPU uses the same array (the counters are cleared at
+ * the start of each call): calls that overlap in time on one GPU, on whatever streams, race -
+ * serialise them, or give the overlapping ones a workspace of their own through bc_decode_step. */
+#define BC_NOALLOC_SCRATCH_BYTES (4u << 20)
+int32_t bc_decode_step_noalloc(const bc_shape *shape, const bc_cache *cache, const void *k,
+                               const void *v, const void *q, float *out, const void *beacon_k,
+                               const void *beacon_v, const uint8_t *active, void *stream);
+
 /* The beacon's own step in one launch (Alg. 1: encode the beacon, then drop the window; Sec. 3.1):
  * the same as bc_append_kv(kind = BC_ROW_BEACON) + bc_decode_attn + bc_compress_evict(NULL, NULL)
  * on the sequences whose window is full.  k, v: the beacon token's K/V rows [B, Hkv, d]; q: its

@@ -32,7 +32,7 @@ BC_PLAN_GENERAL_LOOP = 128
 EXPORTS = [
     "bc_status_str", "bc_version", "bc_cache_init", "bc_cache_admit", "bc_append_kv",
     "bc_decode_workspace_bytes", "bc_workspace_init", "bc_decode_plan_describe", "bc_decode_attn",
-    "bc_compress_evict", "bc_decode_step", "bc_beacon_step", "bc_decode_step_budget", "bc_set_ratio",
+    "bc_compress_evict", "bc_decode_step", "bc_decode_step_noalloc", "bc_beacon_step", "bc_decode_step_budget", "bc_set_ratio",
     "bc_sort_by_length",
     "bc_prefill_attn", "bc_prefill_bwd_workspace_bytes", "bc_prefill_attn_bwd",
     "bc_topk_kl_loss", "bc_topk_kl_loss_bwd", "bc_tables_to_host",
@@ -97,6 +97,8 @@ def load():
     lib.bc_compress_evict.argtypes = [sp, cp, vp, vp, vp, i32, vp]
     lib.bc_decode_step.restype = i32
     lib.bc_decode_step.argtypes = [sp, cp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.bc_decode_step_noalloc.restype = i32
+    lib.bc_decode_step_noalloc.argtypes = [sp, cp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.bc_beacon_step.restype = i32
     lib.bc_beacon_step.argtypes = [sp, cp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.bc_decode_step_budget.restype = i32
@@ -193,6 +195,11 @@ def bc_compress_evict(shape, cache, beacon_k, beacon_v, active, require_full_win
 def bc_decode_step(shape, cache, k, v, q, out, beacon_k, beacon_v, active, ws, ws_bytes, stream):
     return load().bc_decode_step(C.byref(shape), C.byref(cache), k, v, q, out, beacon_k, beacon_v,
                                  active, ws, ws_bytes, stream)
+
+
+def bc_decode_step_noalloc(shape, cache, k, v, q, out, beacon_k, beacon_v, active, stream):
+    return load().bc_decode_step_noalloc(C.byref(shape), C.byref(cache), k, v, q, out, beacon_k, beacon_v,
+                                         active, stream)
 
 
 def bc_beacon_step(shape, cache, k, v, q, out, active, ws, ws_bytes, stream):
@@ -406,6 +413,16 @@ class Runtime:
         _check(bc_decode_step(self.shape, self.cache, _ptr(k), _ptr(v), _ptr(q), _ptr(out),
                               _ptr(bk), _ptr(bv), _ptr(a), _ptr(self.ws), self.ws_bytes,
                               _stream_ptr()))
+        return out
+
+    def decode_step_noalloc(self, k, v, q, bk=None, bv=None, active=None, out=None):
+        """bc_decode_step on the library's own scratch array instead of this object's workspace."""
+        k, v, q, a = self.dev(k), self.dev(v), self.dev(q), self.mask(active)
+        bk = None if bk is None else self.dev(bk)
+        bv = None if bv is None else self.dev(bv)
+        out = self.out if out is None else out
+        _check(bc_decode_step_noalloc(self.shape, self.cache, _ptr(k), _ptr(v), _ptr(q), _ptr(out),
+                                      _ptr(bk), _ptr(bv), _ptr(a), _stream_ptr()))
         return out
 
     def beacon_step(self, k, v, q, active=None, out=None):

@@ -1405,6 +1405,60 @@ extern "C" int32_t bc_decode_step(const bc_shape* shape, const bc_cache* cache, 
   return decode_step_checked(shape, cache, pl, k, v, q, out, beacon_k, beacon_v, active, workspace, stream);
 }
 
+// ---------------------------------------------------------------------------
+// bc_decode_step for callers that cannot allocate: the workspace is a fixed array in device memory
+// ---------------------------------------------------------------------------
+namespace bc {
+constexpr size_t kScratchBytes = BC_NOALLOC_SCRATCH_BYTES;
+// One copy per GPU the library runs on, at an address of its own, held until the process ends.
+// (In host code the array's name is only a handle: its device address comes from
+// hipGetSymbolAddress, once per device, below.)
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+static int32_t scratch_of_current_device(unsigned char** ptr) {
+  static unsigned char* address[64];
+  static std::atomic<bool> known[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return BC_ERR_HIP;
+  if (!known[dev].load(std::memory_order_acquire)) {
+    void* a = nullptr;
+    if (hipGetSymbolAddress(&a, HIP_SYMBOL(scratch)) != hipSuccess || a == nullptr) return BC_ERR_HIP;
+    address[dev] = static_cast<unsigned char*>(a);      // (two threads racing here store the same value)
+    known[dev].store(true, std::memory_order_release);
+  }
+  *ptr = address[dev];
+  return BC_OK;
+}
+}  // namespace bc
+
+extern "C" int32_t bc_decode_step_noalloc(const bc_shape* shape, const bc_cache* cache, const void* k,
+                                          const void* v, const void* q, float* out, const void* beacon_k,
+                                          const void* beacon_v, const uint8_t* active, void* stream) {
+  // the checks of bc_decode_step (the workspace is checked below, against the scratch array)
+  DecodePlan pl;
+  int32_t st = check_attention_args(shape, cache, q, out, reinterpret_cast<void*>(uintptr_t(256)), SIZE_MAX, &pl);
+  if (st != BC_OK) return st;
+  if (!k || !v || !aligned16(k) || !aligned16(v)) return BC_ERR_ARG;
+  if ((beacon_k == nullptr) != (beacon_v == nullptr)) return BC_ERR_ARG;
+  if (beacon_k && (!aligned16(beacon_k) || !aligned16(beacon_v))) return BC_ERR_ARG;
+  // what this call's plan touches: the per-sequence counters, and the partial results only when
+  // sequences are split into chunks
+  const size_t need = pl.tickets_bytes + (pl.max_chunks > 1 ? pl.total() - pl.tickets_bytes : 0);
+  if (need > kScratchBytes) return BC_ERR_WORKSPACE;
+  unsigned char* ws = nullptr;
+  st = scratch_of_current_device(&ws);
+  if (st != BC_OK) return st;
+  // Every call on this GPU shares the array and finds what the last one left: the counters must
+  // start at zero (a fill kernel, not a memset node: callers may be capturing a graph).
+  const int64_t n = (int64_t)(pl.tickets_bytes / 4);
+  const int64_t blocks = (n + 255) / 256;
+  fill_zero_kernel<<<(int)(blocks < 1024 ? blocks : 1024), 256, 0, as_stream(stream)>>>(
+      reinterpret_cast<uint32_t*>(ws), n);
+  st = launch_status();
+  if (st != BC_OK) return st;
+  return decode_step_checked(shape, cache, pl, k, v, q, out, beacon_k, beacon_v, active, ws, stream);
+}
+
 extern "C" int32_t bc_beacon_step(const bc_shape* shape, const bc_cache* cache, const void* k,
                                   const void* v, const void* q, float* out, const uint8_t* active,
                                   void* workspace, size_t workspace_bytes, void* stream) {

@@ -228,3 +228,19 @@ def test_every_status_has_its_own_text():
     texts = [bc.bc_status_str(s) for s in range(0, -7, -1)]
     assert len(set(texts)) == 7 and all(texts)
     assert bc.bc_status_str(-99) not in texts[:1]
+
+
+def test_noalloc_step_rejects_what_does_not_fit_its_scratch_array():
+    # the allocation-free step checks its arguments like bc_decode_step and its plan against the
+    # fixed scratch array, before anything is launched or any device is asked for
+    s, c = shape(), cache()
+    call = lambda s, c, k=PTR: bc.bc_decode_step_noalloc(s, c, k, PTR, PTR, PTR, None, None, None, None)
+    assert call(shape(B=0), c) == bc.BC_ERR_SHAPE
+    assert call(s, cache(k_slab=None)) == bc.BC_ERR_ARG
+    assert call(s, c, k=None) == bc.BC_ERR_ARG
+    assert bc.bc_decode_step_noalloc(s, c, PTR, PTR, PTR, PTR, PTR, None, None, None) == bc.BC_ERR_ARG
+    # 1024 pairs in 32 forced chunks each: 128 MB of partial results against 4 MiB of scratch
+    big = shape(B=128, Hq=64, Hkv=8, d=128, dtype=bc.BC_BF16)
+    assert call(big, cache(max_cap=4096, rows_per_workgroup=128)) == bc.BC_ERR_WORKSPACE
+    # more counters than the array holds (128 bytes per sequence)
+    assert call(shape(B=40000, Hq=1, Hkv=1, d=128, dtype=bc.BC_BF16), cache(max_cap=64)) == bc.BC_ERR_WORKSPACE
