@@ -70,6 +70,7 @@ def rollout(wl, rt, oc, steps, attn_steps, slab_steps, table_every=1, tail_form=
     """Alg. 1 for `steps` decode steps; sequences whose generation is over stay resident."""
     attn_steps, slab_steps = set(attn_steps), set(slab_steps)
     worst = 0.0
+    q_any = None
     for t in range(1, steps + 1):
         if before_step is not None:
             before_step(t)
@@ -77,7 +78,14 @@ def rollout(wl, rt, oc, steps, attn_steps, slab_steps, table_every=1, tail_form=
         act = None if active.all() else active
         k, v = wl.step_kv(t)
         need_attn = t in attn_steps
-        q = wl.step_q(t) if (need_attn or use_step_call) else None
+        if need_attn:
+            q = wl.step_q(t)
+        elif use_step_call or beacon_call:
+            # the step calls need a query; where the output is not compared any will do (drawing one
+            # per step is most of the host time of a long rollout)
+            q = q_any = wl.step_q(1) if q_any is None else q_any
+        else:
+            q = None
         bk, bv = wl.beacon_kv(t)
         if beacon_call:
             # token step without eviction, then the beacon's own step (bc_beacon_step): beacon row
@@ -87,7 +95,7 @@ def rollout(wl, rt, oc, steps, attn_steps, slab_steps, table_every=1, tail_form=
             if need_attn:
                 seqs = [s for s in (range(wl.B) if seq_sample is None else seq_sample) if active[s]]
                 worst = max(worst, check_attention(o.cpu().numpy(), q, oc, wl, seqs, t))
-            qb = wl.beacon_q(t)
+            qb = wl.beacon_q(t) if need_attn else q
             ob = rt.beacon_step(bk, bv, qb, active=act)
             oc.append(bk, bv, active=act, beacon=True)
             due = [s for s in range(wl.B) if active[s] and oc.c[s] > 0 and oc.w[s] == oc.c[s] + 1]
@@ -390,7 +398,8 @@ def test_config2_batch64_full_rollout(dev, c):
     print("batch64 c=%d worst %.3g" % (c, worst))
 
 
-def test_config3_ragged_snapshot(dev):
+@pytest.mark.parametrize("mode", ["attention", "fused step in dispatch order"])
+def test_config3_ragged_snapshot(dev, mode):
     wl = W.ragged256()
     T = wl.extra["T"]
     rt, oc = make(wl, dev)
@@ -398,6 +407,29 @@ def test_config3_ragged_snapshot(dev):
     # snapshot at attention time of step T
     active = (wl.G >= T).astype(np.uint8)
     k, v = wl.step_kv(T)
+    q = wl.step_q(T)
+    if mode != "attention":
+        # the way this state is timed: bc_decode_step (append + attention + eviction in one launch)
+        # with the dispatch order of bc_sort_by_length attached; sequences that are over stay out
+        bk, bv = wl.beacon_kv(T)
+        rt.sort_by_length(active=active)
+        st, text = _bc().bc_decode_plan_describe(rt.shape, rt.cache)
+        assert st == 0 and "decode_lds_kernel" in text and "chunks=1" in text, text
+        rt.out.fill_(-5.0)
+        o = rt.decode_step(k, v, q, bk, bv, active=active).cpu().numpy()
+        oc.append(k, v, active=active)
+        live = [s for s in range(wl.B) if active[s]]
+        worst = check_attention(o, q, oc, wl, live, T)
+        assert all(np.all(o[s] == -5.0) for s in range(wl.B) if not active[s])
+        oc.compress_evict(bk, bv, active=active)
+        nb, w = check_tables(rt, oc, T)
+        for s in live:
+            assert (int(nb[s]), int(w[s])) == OR.tables_after_step(int(wl.c[s]), T)
+        check_slabs(rt, oc, None, T)
+        order = rt.order.cpu().numpy()
+        assert sorted(order.tolist()) == list(range(wl.B))
+        print("ragged fused T=%d worst %.3g" % (T, worst))
+        return
     rt.append_kv(k, v, active=active)
     oc.append(k, v, active=active)
     nb, w = check_tables(rt, oc, T)
@@ -408,21 +440,31 @@ def test_config3_ragged_snapshot(dev):
         else:
             assert (int(nb[s]), int(w[s])) == OR.tables_after_step(int(wl.c[s]), t_s)
     check_slabs(rt, oc, None, T)
-    q = wl.step_q(T)
     o = rt.decode_attn(q).cpu().numpy()          # all sequences, finished ones included
     worst = check_attention(o, q, oc, wl, None, T)
     print("ragged T=%d sumL=%d worst %.3g" % (T, sum(oc.L(s) for s in range(wl.B)), worst))
 
 
-def test_config4_long_peaked(dev):
+@pytest.mark.parametrize("mode", ["separate calls", "step with supplied beacon", "step and beacon step"])
+def test_config4_long_peaked(dev, mode):
+    # the whole 32768-token rollout, by the three separate calls, by the fused step that is handed
+    # the beacon (the form the benchmark times) and by the fused step followed by the beacon
+    # token's own step (bc_beacon_step)
     wl = W.long_reasoning()
     rt, oc = make(wl, dev)
     rng = np.random.default_rng(9)
-    # steps whose window holds a x4 key: the 64th written row falls on a token
+    # steps whose window holds a x4 key: the 64th written row falls on a token (rows are counted
+    # in write order: 512 prompt rows, then 32 tokens and one beacon per window)
+    peaked = [t for t in range(1, 32769) if (512 + (t - 1) + (t - 1) // 32) % 64 == 63]
+    assert len(peaked) > 400
     sample = sorted(set([1, 31, 32, 33, 63, 64, 65, 4096, 32767, 32768])
-                    | set(int(x) for x in rng.integers(1, 32769, size=20)))
+                    | set(int(x) for x in rng.integers(1, 32769, size=20))
+                    | set(peaked[:2] + [peaked[len(peaked) // 2], peaked[-1], peaked[-1] + 1, peaked[-1] + 5]))
+    sample = [t for t in sample if t <= 32768]
     seqs = [0, 7, 31]
-    worst = rollout(wl, rt, oc, 32768, sample, (32, 33, 32768), table_every=1024, seq_sample=seqs)
+    worst = rollout(wl, rt, oc, 32768, sample, (32, 33, 32768), table_every=1024, seq_sample=seqs,
+                    use_step_call=(mode == "step with supplied beacon"),
+                    beacon_call=(mode == "step and beacon step"))
     nb, w, _ = rt.tables()
     assert int(nb[0]) == 1024 and int(w[0]) == 0
     q = wl.step_q(40000)

@@ -81,6 +81,19 @@ def test_config5_full_size(dev):
     for b in range(pw.B):
         rows = sorted(set(int(x) for x in rng.integers(0, 8688, size=120)))
         worst = max(worst, _check_rows(pw, qkv, off, out, lse, b, rows))
+    # every row of four (trajectory, query head) slices: first and last trajectory, heads of both
+    # KV heads, first and last head of a group
+    g = pw.Hq // pw.Hkv
+    for b, h in ((0, 0), (0, pw.Hq - 1), (pw.B - 1, g - 1), (7, g)):
+        q, k, v = qkv[b]
+        kvh = h // g
+        ref, ref_lse = OA.masked_prefill_attention(q[:, h:h + 1], k[:, kvh:kvh + 1], v[:, kvh:kvh + 1],
+                                                   int(pw.P[b]), int(pw.c[b]), pw.scale)
+        got = out[off[b]:off[b + 1], h:h + 1]
+        err = float(np.abs(got - ref).max())
+        lerr = float(np.abs(lse[off[b]:off[b + 1], h:h + 1] - ref_lse).max())
+        assert err <= TOL and lerr <= 1e-3, (b, h, err, lerr)
+        worst = max(worst, err)
     print("config5 worst", worst)
 
 
