@@ -548,13 +548,16 @@ def decode_record(wl, what, K, W, us_step, us_step_wall, step_bytes, extra_cfg, 
 
 
 def run_replayed(db, K, W, replays, first_token, tokens_per_step=None):
-    """Warm up W layer-steps eagerly, capture [restore tables, K layer-steps] as one graph, replay
-    it `replays` times.  Every replay starts from the same tables (a small kernel at the head of
-    the graph puts them back), so every replay does the same K steps.  Returns timing and the
-    token index of each timed layer-step."""
+    """Warm up W layer-steps eagerly, then time the unit [restore tables, K layer-steps]: a small
+    kernel at its head puts the tables back, so every execution of the unit does the same K
+    steps.  One graph holds several units back to back (about 256 launches: the pause between two
+    graph launches is then a small part of it) and is replayed until the unit has run at least
+    `replays` times.  Returns timing per unit and the token index of each timed layer-step."""
     import torch
     stream = torch.cuda.Stream()
     NL = db.NL
+    units = max(1, 256 // (K + 1))
+    launches = (replays + units - 1) // units
     tok = (lambda i: first_token + i // NL) if first_token is not None else (lambda i: None)
     with torch.cuda.stream(stream):
         for i in range(W):
@@ -564,19 +567,21 @@ def run_replayed(db, K, W, replays, first_token, tokens_per_step=None):
         stream.synchronize()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=stream):
-            db.restore()
-            for i in range(W, W + K):
-                db.step(i, tok(i))
+            for _ in range(units):
+                db.restore()
+                for i in range(W, W + K):
+                    db.step(i, tok(i))
         for _ in range(3):                      # untimed: the first replay of a graph pays for its upload
             graph.replay()
         stream.synchronize()
     after = db.tab.clone()
-    us_ev, us_wall, us_min, us_med = replay_timed(stream, graph, replays)
+    us_ev, us_wall, us_min, us_med = replay_timed(stream, graph, launches)
     assert torch.equal(after, db.tab), "a replay did not end in the state of the one before"
     db.check()
     tokens = [first_token + i // NL for i in range(W, W + K)] if first_token is not None else []
-    return {"us_replay_mean": us_ev, "us_replay_wall": us_wall, "us_replay_min": us_min,
-            "us_replay_median": us_med, "tokens": tokens, "stream": stream}
+    return {"us_replay_mean": us_ev / units, "us_replay_wall": us_wall / units, "us_replay_min": us_min / units,
+            "us_replay_median": us_med / units, "tokens": tokens, "stream": stream,
+            "units_run": launches * units, "units_per_graph": units}
 
 
 def bench_decode(args, pool, ncores):
@@ -675,12 +680,13 @@ def bench_decode(args, pool, ncores):
         n = len(step_bytes)
         rec = decode_record(wl, what + "; tokens %d..%d of the rollout" % (r["tokens"][0], r["tokens"][-1]), K, W,
                             r["us_replay_mean"] / n, r["us_replay_wall"] / n, step_bytes,
-                            {"layers_round_robin": NL, "hip_graph": True, "replays": args.replays,
+                            {"layers_round_robin": NL, "hip_graph": True, "replays": r["units_run"],
+                             "units_per_graph": r["units_per_graph"],
                              "beacon_token_attention": bool(args.beacon_attn),
                              "uniform_layout_promise": bool(db.layers[0].cache.uniform_P > 0)},
-                            {"method": "HIP events around %d replays of one graph [restore tables, %d steps]; "
-                                       "per launch = replay / %d (the restore kernel's share included)"
-                                       % (args.replays, K, n),
+                            {"method": "HIP events around %d executions of the unit [restore tables, %d steps], %d units "
+                                       "per graph; per launch = unit / %d (the restore kernel's share included)"
+                                       % (r["units_run"], K, r["units_per_graph"], n),
                              "min_launch_us": round(r["us_replay_min"] / n, 3),
                              "median_launch_us": round(r["us_replay_median"] / n, 3)},
                             db.kernel(), stored_traffic())
@@ -735,8 +741,10 @@ def bench_long(args, pool, ncores):
                                                                         int(rows_seen(wl, r["tokens"][0])[0]),
                                                                         int(rows_seen(wl, r["tokens"][-1])[0])),
                         K, W, r["us_replay_mean"] / K, r["us_replay_wall"] / K, step_bytes,
-                        {"layers_round_robin": NL, "hip_graph": True, "replays": args.replays},
-                        {"method": "HIP events around %d replays of one graph [restore tables, %d steps]" % (args.replays, K),
+                        {"layers_round_robin": NL, "hip_graph": True, "replays": r["units_run"],
+                         "units_per_graph": r["units_per_graph"]},
+                        {"method": "HIP events around %d executions of the unit [restore tables, %d steps], %d units per graph"
+                                   % (r["units_run"], K, r["units_per_graph"]),
                          "min_launch_us": round(r["us_replay_min"] / K, 3),
                          "median_launch_us": round(r["us_replay_median"] / K, 3)},
                         db.kernel(), stored_profile("decode_long_c32_hbm_traffic.txt"))
@@ -775,9 +783,11 @@ def bench_ragged(args, pool, ncores):
                             "c in {2,4,8,16,32}; the %d steps that end at the snapshot T=%d (resident rows %d..%d, %d in all)"
                             % (K, T, int(Ls.min()), int(Ls.max()), int(Ls.sum())),
                         K, W, r["us_replay_mean"] / K, r["us_replay_wall"] / K, step_bytes,
-                        {"layers_round_robin": NL, "hip_graph": True, "replays": args.replays,
+                        {"layers_round_robin": NL, "hip_graph": True, "replays": r["units_run"],
+                         "units_per_graph": r["units_per_graph"],
                          "dispatch_order": "bc_sort_by_length, once before the capture" if not args.no_sort else "index order"},
-                        {"method": "HIP events around %d replays of one graph [restore tables, %d steps]" % (args.replays, K),
+                        {"method": "HIP events around %d executions of the unit [restore tables, %d steps], %d units per graph"
+                                   % (r["units_run"], K, r["units_per_graph"]),
                          "min_launch_us": round(r["us_replay_min"] / K, 3),
                          "median_launch_us": round(r["us_replay_median"] / K, 3)},
                         db.kernel(), stored_profile("decode_ragged256_hbm_traffic.txt"))
@@ -797,7 +807,7 @@ def main():
     ap.add_argument("--steps", type=int, default=-1)
     ap.add_argument("--warmup", type=int, default=-1)
     ap.add_argument("--replays", type=int, default=200,
-                    help="replays of the captured graph of the timed steps (decode workloads with --steps)")
+                    help="executions of the timed steps (decode workloads with --steps), at least")
     ap.add_argument("--layers", type=int, default=16, help="cache instances visited round-robin")
     ap.add_argument("--c", type=int, default=16, help="compression ratio (0: uncompressed control)")
     ap.add_argument("--beacon-attn", action="store_true",
