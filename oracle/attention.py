@@ -165,3 +165,57 @@ def masked_prefill_attention_bwd(q, k, v, do, P: int, c: int, scale):
         dq[:, h, :] = scale * (ds @ k[:, kvh, :])
         dk[:, kvh, :] += scale * (ds.T @ q[:, h, :])
     return dq, dk, dv
+
+
+def rows_seeing(j: int, S: int, P: int, c: int) -> np.ndarray:
+    """Rows r of an S-row trajectory that attend to row j (the column of the mask, from the
+    same rule as `visible`): the prompt and the beacons are seen by every later row, a response
+    token by the later rows of its own window, the closing beacon included."""
+    if j < P or c <= 0 or is_beacon_row(j, P, c):
+        return np.arange(j, S)
+    end = P + ((j - P) // (c + 1) + 1) * (c + 1) - 1          # the window's beacon row
+    return np.arange(j, min(end, S - 1) + 1)
+
+
+def masked_prefill_attention_bwd_at(q, k, v, do, P: int, c: int, scale, rows, keys):
+    """The gradients of `masked_prefill_attention_bwd` at chosen places of a trajectory too long
+    for its dense S x S form: dq of `rows`, dk and dv of `keys`, every entry from its own sum
+    over the visible pairs (same formulas: a = softmax row, ds = a * (da - sum(do * o)),
+    dq[r] = scale * sum_j ds[r, j] k[j], dk[j] = scale * sum_r ds[r, j] q[r],
+    dv[j] = sum_r a[r, j] do[r], the last two also summed over the query heads of a group).
+    Returns (dq [len(rows), Hq, d], dk [len(keys), Hkv, d], dv [len(keys), Hkv, d]) in fp64."""
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    do = np.asarray(do, dtype=np.float64)
+    S, Hq, d = q.shape
+    Hkv = k.shape[1]
+    g = Hq // Hkv
+
+    def row_terms(r, h):
+        """(visible keys, a[r, vis], ds[r, vis]) of query row r, head h."""
+        vis = visible_row(r, P, c)
+        kvh = h // g
+        s = scale * (k[vis, kvh, :] @ q[r, h])
+        a = np.exp(s - s.max())
+        a /= a.sum()
+        o = a @ v[vis, kvh, :]
+        da = v[vis, kvh, :] @ do[r, h]
+        return vis, a, a * (da - do[r, h] @ o)
+
+    dq = np.zeros((len(rows), Hq, d))
+    for n, r in enumerate(rows):
+        for h in range(Hq):
+            vis, _, ds = row_terms(r, h)
+            dq[n, h] = scale * (ds @ k[vis, h // g, :])
+    dk = np.zeros((len(keys), Hkv, d))
+    dv = np.zeros((len(keys), Hkv, d))
+    for n, j in enumerate(keys):
+        for r in rows_seeing(j, S, P, c):
+            for h in range(Hq):
+                vis, a, ds = row_terms(int(r), h)
+                at = int(np.searchsorted(vis, j))
+                assert vis[at] == j
+                dk[n, h // g] += scale * ds[at] * q[r, h]
+                dv[n, h // g] += a[at] * do[r, h]
+    return dq, dk, dv

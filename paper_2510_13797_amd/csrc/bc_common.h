@@ -212,4 +212,29 @@ inline int32_t launch_status() {
   return hipGetLastError() == hipSuccess ? BC_OK : BC_ERR_HIP;
 }
 
+// Row offsets divided by the window stride c + 1 (Fig. 2: c tokens and their beacon), for
+// offsets below 2^26.  The multiplier is floor(2^32 / stride) + 1, so the product's high word
+// overestimates offset / stride by less than offset / 2^32 < 1/64: it is the quotient, or one
+// more - and never more while rows * stride fits in 32 bits, which `exact` records (uniform, so
+// the correction is skipped by a scalar branch at the paper's ratios).  Ratios beyond any row
+// count behave like 2^26: no window ever closes.
+struct WindowStride {
+  int c, stride;
+  uint32_t magic;
+  bool exact;
+};
+__device__ __forceinline__ WindowStride window_stride(int c_table, int rows) {
+  WindowStride ws;
+  ws.c = min(c_table, 1 << 26);
+  ws.stride = ws.c + 1;
+  ws.magic = ws.c > 0 ? (uint32_t)(0x100000000ull / (uint32_t)ws.stride) + 1u : 0u;
+  ws.exact = (uint64_t)(uint32_t)max(rows, 0) * (uint32_t)max(ws.stride, 1) < 0x100000000ull;
+  return ws;
+}
+__device__ __forceinline__ uint32_t window_of(const WindowStride& ws, uint32_t offset) {
+  uint32_t q = __umulhi(offset, ws.magic);
+  if (!ws.exact) q -= (q * (uint32_t)ws.stride > offset) ? 1u : 0u;
+  return q;
+}
+
 }  // namespace bc

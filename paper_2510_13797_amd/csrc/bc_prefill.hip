@@ -77,14 +77,14 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
   const int r0 = qt * kPfBM;
   if (r0 >= S) return;
   const int r1 = min(r0 + kPfBM - 1, S - 1);
-  const int P = p.P[b], c = p.c[b];
-  const int cp1 = c + 1;
-  const uint32_t magic = c > 0 ? (uint32_t)(0x100000000ull / (uint32_t)cp1) + 1u : 0u;   // n/(c+1), n < 2^26
+  const int P = p.P[b];
+  const WindowStride ws = window_stride(p.c[b], S);
+  const int c = ws.c, cp1 = ws.stride;
 
   // compacted key list of this tile
   int nA = 0, nB = 0, band_start = 0;
   if (c > 0 && r0 >= P) {
-    const int m0 = (int)__umulhi((uint32_t)(r0 - P), magic);
+    const int m0 = (int)window_of(ws, (uint32_t)(r0 - P));
     nA = P; nB = m0; band_start = P + m0 * cp1;
   }
   const int nC = r1 - band_start + 1;
@@ -151,7 +151,7 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
       qb[h][i] = __builtin_bit_cast(bf16x8_t, x);
     }
   }
-  const int win_r = (c > 0 && r >= P) ? (int)__umulhi((uint32_t)(r - P), magic) : -1;
+  const int win_r = (c > 0 && r >= P) ? (int)window_of(ws, (uint32_t)(r - P)) : -1;
 
   f32x4_t O[HPW][8];
   float m_run[HPW], l_run[HPW], grow_at[HPW];
@@ -184,7 +184,7 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
           bool see = j < P || c <= 0;
           if (!see) {
             const uint32_t u = (uint32_t)(j - P);
-            const uint32_t qd = __umulhi(u, magic);
+            const uint32_t qd = window_of(ws, u);
             see = (int)(u - qd * (uint32_t)cp1) == c || (int)qd == win_r;
           }
           vis[e] = vis[e] && j <= r && see;

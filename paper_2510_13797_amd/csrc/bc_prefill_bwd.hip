@@ -142,13 +142,13 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dq_kernel(BwdPar
   const int r0 = qt * kBwBM;
   if (r0 >= S) return;
   const int r1 = min(r0 + kBwBM - 1, S - 1);
-  const int P = p.P[b], c = p.c[b];
-  const int cp1 = c + 1;
-  const uint32_t magic = c > 0 ? (uint32_t)(0x100000000ull / (uint32_t)cp1) + 1u : 0u;
+  const int P = p.P[b];
+  const WindowStride ws = window_stride(p.c[b], S);
+  const int c = ws.c, cp1 = ws.stride;
 
   int nA = 0, nB = 0, band_start = 0;
   if (c > 0 && r0 >= P) {
-    const int m0 = (int)__umulhi((uint32_t)(r0 - P), magic);
+    const int m0 = (int)window_of(ws, (uint32_t)(r0 - P));
     nA = P; nB = m0; band_start = P + m0 * cp1;
   }
   const int nC = r1 - band_start + 1;
@@ -231,7 +231,7 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dq_kernel(BwdPar
       st[1] = delta[h];
     }
   }
-  const int win_r = (c > 0 && r >= P) ? (int)__umulhi((uint32_t)(r - P), magic) : -1;
+  const int win_r = (c > 0 && r >= P) ? (int)window_of(ws, (uint32_t)(r - P)) : -1;
 
   f32x4_t dQ[kDqHeads][8];
 #pragma unroll
@@ -267,7 +267,7 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dq_kernel(BwdPar
           bool see = j < P || c <= 0;
           if (!see) {
             const uint32_t u = (uint32_t)(j - P);
-            const uint32_t qd = __umulhi(u, magic);
+            const uint32_t qd = window_of(ws, u);
             see = (int)(u - qd * (uint32_t)cp1) == c || (int)qd == win_r;
           }
           vis[e] = vis[e] && j <= r && see;
@@ -337,14 +337,14 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dkv_kernel(BwdPa
   const int kvh = blockIdx.x % p.Hkv, b = blockIdx.x / p.Hkv;
   const int64_t off0 = p.row_off[b];
   const int S = (int)(p.row_off[b + 1] - off0);
-  const int P0 = p.P[b], c = p.c[b];
-  const int cp1 = c + 1;
-  const uint32_t magic = c > 0 ? (uint32_t)(0x100000000ull / (uint32_t)cp1) + 1u : 0u;
+  const int P0 = p.P[b];
+  const WindowStride ws = window_stride(p.c[b], S);
+  const int c = ws.c, cp1 = ws.stride;
   // key blocks of this (trajectory, KV head): prompt keys | gathered beacons | response rows.
   // Without compression every row behaves like a prompt row (plain causal).
   const int Pk = c > 0 ? min(P0, S) : S;                        // keys treated as dense-causal
   const int nresp = S - Pk;                                     // response rows (tokens and beacons)
-  const int nbeac = c > 0 ? (int)__umulhi((uint32_t)nresp, magic) : 0;   // complete windows
+  const int nbeac = c > 0 ? (int)window_of(ws, (uint32_t)nresp) : 0;   // complete windows
   const int NPB = (Pk + kBwBM - 1) / kBwBM, NBB = (nbeac + kBwBM - 1) / kBwBM;
   const int NLB = (nresp + kBwBM - 1) / kBwBM;
   // The dense blocks (prompt keys, beacons) stream every later row of every head; each is cut
@@ -387,11 +387,11 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dkv_kernel(BwdPa
     jkey = j0 + 16 * wave + n; key_ok = jkey < S;
     if (key_ok) {                              // beacon rows belong to the beacon blocks
       const uint32_t u = (uint32_t)(jkey - Pk);
-      const uint32_t qd = __umulhi(u, magic);
+      const uint32_t qd = window_of(ws, u);
       if ((int)(u - qd * (uint32_t)cp1) == c) key_ok = false;
     }
     const int jl = min(j0 + kBwBM - 1, S - 1);
-    const int wl = (int)__umulhi((uint32_t)(jl - Pk), magic);
+    const int wl = (int)window_of(ws, (uint32_t)(jl - Pk));
     rs = j0; re = min(S - 1, Pk + (wl + 1) * cp1 - 1);      // through the closing beacon
   }
   // first row tile of a dense block from which every streamed row sees every key of the block
@@ -401,7 +401,7 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dkv_kernel(BwdPa
   if (kind == 1 && (blk - NPB) * kBwBM + kBwBM <= nbeac)
     dense_from_rt = ((kBwBM - 1) * cp1 + kBwBN) / kBwBN;
   if (!key_ok) jkey = rs;                      // loads stay in range; contributions are masked
-  const int win_j = (c > 0 && jkey >= Pk) ? (int)__umulhi((uint32_t)(jkey - Pk), magic) : -1;
+  const int win_j = (c > 0 && jkey >= Pk) ? (int)window_of(ws, (uint32_t)(jkey - Pk)) : -1;
 
   // K^T and V^T of the wave's keys as B operands (column n = key, k = head-dim index)
   bf16x8_t kop[4], vop[4];
@@ -486,7 +486,7 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dkv_kernel(BwdPa
       bool ok = key_ok && r <= re && r >= jkey;
       if (kind == 2 && ok) {
         // a response token is seen inside its own window (the closing beacon included)
-        const int wr = (int)__umulhi((uint32_t)(r - Pk), magic);
+        const int wr = (int)window_of(ws, (uint32_t)(r - Pk));
         ok = wr == win_j;
       }
       vis[e] = ok;

@@ -274,3 +274,31 @@ def test_prefill_peaked_keys_forward_and_backward(dev):
     assert np.isfinite(dq).all() and np.isfinite(dk).all() and np.isfinite(dv).all()
     for b in range(pw.B):
         _check_bwd(pw, qkv, dos, off, dq, dk, dv, b)
+
+
+def test_prefill_ratio_whose_window_index_needs_more_than_32_bits(dev):
+    # c = 65535: rows * (c + 1) passes 2^32 inside the third window, where a multiply-high
+    # estimate of offset / (c + 1) is one too large unless it is corrected (offset 131071, the
+    # second beacon, is the first such place).  Forward rows and gradients around both beacons
+    # and in the short third window, against the oracle's per-place sums.
+    P, c = 24, 65535
+    R = 2 * c + 150
+    pw = W.PrefillWorkload("pf_wide_ratio", 66, 1, 2, 1, 128, "bf16", np.array([P], np.int32),
+                           np.array([R], np.int32), np.array([c], np.int32))
+    S = int(pw.S[0])
+    assert S == P + R + 2 and (S - P) * (c + 1) > 2 ** 32
+    b1, b2 = P + c, P + 2 * c + 1                      # the two beacon rows
+    assert OA.is_beacon_row(b1, P, c) and OA.is_beacon_row(b2, P, c)
+    qkv, dos, off, dq, dk, dv = _run_bwd(pw, dev)
+    _, _, out, lse = _run(pw, dev)
+    assert np.isfinite(out).all() and np.isfinite(dq).all() and np.isfinite(dk).all() and np.isfinite(dv).all()
+    rows = [0, P - 1, P, b1 - 1, b1, b1 + 1, b2 - 2, b2 - 1, b2, b2 + 1, b2 + 2, b2 + 77, S - 2, S - 1]
+    _check_rows(pw, qkv, off, out, lse, 0, rows)
+    # keys whose columns are short enough to sum on the CPU: the tail of the second window, its
+    # beacon, the third window
+    keys = [b2 - 3, b2 - 1, b2, b2 + 1, b2 + 40, S - 1]
+    q, k, v = qkv[0]
+    rq, rk, rv = OA.masked_prefill_attention_bwd_at(q, k, v, dos[0], P, c, pw.scale, rows, keys)
+    errs = [float(np.abs(dq[rows] - rq).max()), float(np.abs(dk[keys] - rk).max()),
+            float(np.abs(dv[keys] - rv).max())]
+    assert max(errs) <= TOL, errs

@@ -165,3 +165,33 @@ def test_backward_matches_autograd_and_finite_differences():
     _, dk2, dv2 = A.masked_prefill_attention_bwd(q, k, v, do2, P, c, scale)
     assert np.all(dk2[P:P + c] == 0) and np.all(dv2[P:P + c] == 0)        # window-0 tokens
     assert np.abs(dv2[P + c]).max() > 0                                   # its beacon is visible
+
+
+def test_gradients_at_chosen_places_equal_the_dense_form_and_autograd():
+    # the per-place sums (used where S x S does not fit) against the dense oracle, every row and
+    # key, ragged tail and no compression included; and against torch autograd directly
+    rng = np.random.default_rng(11)
+    for S, Hq, Hkv, d, P, c in ((29, 4, 2, 5, 3, 4), (17, 2, 1, 4, 0, 2), (12, 3, 3, 4, 5, 0), (20, 2, 2, 3, 2, 40)):
+        q, do = rng.standard_normal((S, Hq, d)), rng.standard_normal((S, Hq, d))
+        k, v = rng.standard_normal((S, Hkv, d)), rng.standard_normal((S, Hkv, d))
+        dq, dk, dv = A.masked_prefill_attention_bwd(q, k, v, do, P, c, 0.37)
+        everything = list(range(S))
+        sq, sk, sv = A.masked_prefill_attention_bwd_at(q, k, v, do, P, c, 0.37, everything, everything)
+        assert np.abs(sq - dq).max() < 1e-12 and np.abs(sk - dk).max() < 1e-12 and np.abs(sv - dv).max() < 1e-12
+        # the column rule is the transpose of the row rule
+        m = A.visible_mask(S, P, c)
+        for j in range(S):
+            assert np.array_equal(A.rows_seeing(j, S, P, c), np.nonzero(m[:, j])[0])
+    S, Hq, Hkv, d, P, c = 26, 2, 1, 4, 3, 5
+    q, do = rng.standard_normal((S, Hq, d)), rng.standard_normal((S, Hq, d))
+    k, v = rng.standard_normal((S, Hkv, d)), rng.standard_normal((S, Hkv, d))
+    tq, tk, tv = (torch.tensor(x, requires_grad=True) for x in (q, k, v))
+    mask = torch.from_numpy(A.visible_mask(S, P, c))
+    s = torch.einsum("rhd,jd->hrj", tq, tk[:, 0]) * 0.5
+    a = torch.softmax(s.masked_fill(~mask, -math.inf), dim=-1)
+    (torch.einsum("hrj,jd->rhd", a, tv[:, 0]) * torch.from_numpy(do)).sum().backward()
+    rows, keys = [0, 4, 8, 9, 25], [1, 3, 8, 14, 20, 25]
+    sq, sk, sv = A.masked_prefill_attention_bwd_at(q, k, v, do, P, c, 0.5, rows, keys)
+    assert np.abs(sq - tq.grad.numpy()[rows]).max() < 1e-12
+    assert np.abs(sk - tk.grad.numpy()[keys]).max() < 1e-12
+    assert np.abs(sv - tv.grad.numpy()[keys]).max() < 1e-12
