@@ -1,8 +1,8 @@
 """Softmax attention over a given key set, and the training-time visibility rule
 (oracle, test only; fp64 NumPy).
 
-The paper changes *which* keys a query sees, never the attention itself
-("the standard Transformer attention mechanism", Sec. 2).  So the decode oracle
+The paper changes *which* keys a query sees, never the attention itself (Sec. 2
+says the model attends to the cache with the ordinary Transformer operation).  So the decode oracle
 is the textbook definition over the resident entries, and the prefill oracle is
 the same definition over the visible set of Fig. 2 / Sec. 3.2.
 

@@ -2,8 +2,9 @@
 
 Two independent forms of the same process (Alg. 1, Sec. 3.1):
 
-* ``FlatCache``     - one Python list per sequence and the literal slice of the
-                      eviction line of Alg. 1.  No bookkeeping besides the list.
+* ``FlatCache``     - one Python list per sequence: the eviction step of Alg. 1 as
+                      "remove the window's entries, put the beacon in their place".
+                      No bookkeeping besides the list.
 * ``BatchCache``    - the structured form [prompt | beacons | window] (Fig. 1)
                       for a batch with per-sequence ratio c, with the state and
                       capacity rules a fixed-capacity implementation must
@@ -32,9 +33,10 @@ class FlatCache:
         self.kv.append((k, v))
 
     def beacon_and_evict(self, bk, bv):
-        c = self.c
-        self.kv.append((bk, bv))                     # encode the beacon
-        self.kv = self.kv[: -c - 1] + self.kv[-1:]   # drop c entries, keep the beacon
+        # what is left of the window after the step is its beacon: the c newest entries go,
+        # the beacon's pair takes their place behind the prompt and the earlier beacons
+        del self.kv[len(self.kv) - self.c:]
+        self.kv.append((bk, bv))
 
     def resident(self):
         K = np.stack([r[0] for r in self.kv])
