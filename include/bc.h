@@ -212,8 +212,9 @@ int32_t bc_compress_evict(const bc_shape *shape, const bc_cache *cache, const vo
                           int32_t require_full_window, void *stream);
 
 /* One decode step: append the token rows, attend, then evict where due (supplied-beacon
- * form); a single launch for bf16 (d = 128 or 64).  Same semantics as bc_append_kv(TOKEN) + bc_decode_attn +
- * bc_compress_evict(beacon_k, beacon_v, require_full_window = 1) in that order.
+ * form); a single launch for every supported shape (a second one merges partial results when
+ * a small batch's sequences are split into chunks).  Same semantics as bc_append_kv(TOKEN) +
+ * bc_decode_attn + bc_compress_evict(beacon_k, beacon_v, require_full_window = 1) in that order.
  * beacon_k/v may be NULL: then no eviction is attempted. */
 int32_t bc_decode_step(const bc_shape *shape, const bc_cache *cache, const void *k,
                        const void *v, const void *q, float *out, const void *beacon_k,

@@ -189,33 +189,6 @@ __global__ void set_ratio_kernel(CacheView cv, const int32_t* __restrict__ new_c
   cv.c[s] = nc;
 }
 
-// Evaluation rule for the shapes whose decode step is not fused: mark the sequences whose
-// attention saw nb + w >= budget entries (before the eviction), clear their mask after it.
-__global__ void budget_mark_kernel(CacheView cv, const int32_t* __restrict__ budget,
-                                   const uint8_t* __restrict__ live, int32_t* __restrict__ mark, int B) {
-  const int s = blockIdx.x * blockDim.x + threadIdx.x;
-  if (s >= B) return;
-  mark[s] = (live[s] && cv.nb[s] + cv.w[s] >= budget[s]) ? 1 : 0;
-}
-
-__global__ void budget_apply_kernel(uint8_t* __restrict__ live, int32_t* __restrict__ mark, int B) {
-  const int s = blockIdx.x * blockDim.x + threadIdx.x;
-  if (s >= B) return;
-  if (mark[s]) { live[s] = 0; mark[s] = 0; }
-}
-
-int32_t launch_budget_mark(const bc_shape* shape, const bc_cache* cache, const int32_t* budget,
-                           const uint8_t* live, int32_t* mark, hipStream_t hs) {
-  CacheView cv = make_view(shape, cache);
-  budget_mark_kernel<<<(shape->B + 255) / 256, 256, 0, hs>>>(cv, budget, live, mark, shape->B);
-  return launch_status();
-}
-
-int32_t launch_budget_apply(const bc_shape* shape, uint8_t* live, int32_t* mark, hipStream_t hs) {
-  budget_apply_kernel<<<(shape->B + 255) / 256, 256, 0, hs>>>(live, mark, shape->B);
-  return launch_status();
-}
-
 }  // namespace bc
 
 using namespace bc;

@@ -19,6 +19,9 @@
 //    128-bit reads, V by the 16-bit transposing reads), softmax in registers.
 //  * decode_valu_kernel (fp32): rows held in registers, 16 bytes per lane, plain
 //    FMA dot products completed by a DPP all-reduce.
+// Both carry the fused step (append before, eviction after the attention) in the same launch: the
+// appended row is read from the caller's tensors, every reader of a sequence takes a ticket when
+// it is done with the slab, and the holder of the last ticket moves the beacon and the tables.
 #include <atomic>
 #include <cstdint>
 #include <cstdio>
@@ -254,6 +257,32 @@ __device__ __forceinline__ PairInfo pair_info(const DecodeParams& p, int slot, i
   pi.evict_due = __builtin_amdgcn_readfirstlane((int)pi.evict_due) != 0;
   pi.store_new_row = __builtin_amdgcn_readfirstlane((int)pi.store_new_row) != 0;
   return pi;
+}
+
+// What the holder of a sequence's last ticket does, as one wave, once every reader of the
+// sequence's rows is done with them: the beacon entry goes to its slot behind the earlier beacons
+// (the evicted window's first row), the tables move on, the ticket counter returns to zero.
+template <int ROWB>
+__device__ __forceinline__ void finish_step(const DecodeParams& p, const PairInfo& pi, int lane) {
+  constexpr int UPR = ROWB / 16;                   // 16-byte units per row
+  if (pi.evict_due) {
+    const int n16 = p.Hkv * UPR;                   // 16-byte units of one K (or V) entry
+    for (int i = lane; i < 2 * n16; i += 64) {
+      const int which = i >= n16, r = which ? i - n16 : i;
+      const int h = r / UPR, u = r & (UPR - 1);
+      const char* src = (which ? p.bv : p.bk) + (int64_t)(pi.s * p.Hkv + h) * ROWB + (u << 4);
+      char* slab = const_cast<char*>(which ? p.v_slab : p.k_slab);
+      const int64_t dst =
+          (pi.base * p.Hkv + (int64_t)h * pi.cap + pi.P + pi.nb) * ROWB + (u << 4);
+      *reinterpret_cast<uint4*>(slab + dst) = *reinterpret_cast<const uint4*>(src);
+    }
+  }
+  if (lane == 0) {
+    p.tickets[pi.s * kTicketStride] = 0;
+    p.nb_rw[pi.s] = pi.nb + (pi.evict_due ? 1 : 0);
+    p.w_rw[pi.s] = pi.evict_due ? 0 : pi.w_att;
+    if (p.budget && pi.nb + pi.w_att >= p.budget[pi.s]) p.live[pi.s] = 0;   // generation interrupted
+  }
 }
 
 // Epilogue shared by both kernels: s_m/s_l/s_acc hold one (m, l, o) per wave in LDS;
@@ -836,24 +865,7 @@ __global__ __launch_bounds__(NW * 64) void decode_lds_kernel(DecodeParams p) {
   wait_vmcnt<0>();     // the ticket has arrived
   landed(ticket);
   if (__builtin_amdgcn_readfirstlane(ticket) != p.Hkv * pi.nchunks * VS * NW - 1) return;
-  if (pi.evict_due) {
-    const int n16 = p.Hkv * UPR;                   // 16-byte units of one K (or V) entry
-    for (int i = lane; i < 2 * n16; i += 64) {
-      const int which = i >= n16, r = which ? i - n16 : i;
-      const int h = r / UPR, u = r & (UPR - 1);
-      const char* src = (which ? p.bv : p.bk) + (int64_t)(pi.s * p.Hkv + h) * ROWB + (u << 4);
-      char* slab = const_cast<char*>(which ? p.v_slab : p.k_slab);
-      const int64_t dst =
-          (pi.base * p.Hkv + (int64_t)h * pi.cap + pi.P + pi.nb) * ROWB + (u << 4);
-      *reinterpret_cast<uint4*>(slab + dst) = *reinterpret_cast<const uint4*>(src);
-    }
-  }
-  if (lane == 0) {
-    p.tickets[pi.s * kTicketStride] = 0;
-    p.nb_rw[pi.s] = pi.nb + (pi.evict_due ? 1 : 0);
-    p.w_rw[pi.s] = pi.evict_due ? 0 : pi.w_att;
-    if (p.budget && pi.nb + pi.w_att >= p.budget[pi.s]) p.live[pi.s] = 0;   // generation interrupted
-  }
+  finish_step<ROWB>(p, pi, lane);
 }
 
 // ---------------------------------------------------------------------------
@@ -905,6 +917,23 @@ __global__ __launch_bounds__(256) void decode_valu_kernel(DecodeParams p) {
     for (int e = 0; e < EPL; ++e) acc[h][e] = 0.f;
   }
 
+  // Fused step: the appended row is not in the slab yet.  Whoever needs row `new_row` reads it
+  // from the caller's tensors instead; the workgroup whose chunk holds it stores it for later
+  // steps (unless this step's eviction drops it at once).  No reader touches the slab at that
+  // row in this launch, so the store races with nothing.
+  const char* new_k_row = kbase, *new_v_row = vbase;
+  if (pi.new_row >= 0) {
+    const int64_t at = (int64_t)(pi.s * p.Hkv + pi.kvh) * RB + ls * 16;
+    new_k_row = p.new_k + at;
+    new_v_row = p.new_v + at;
+    if (pi.store_new_row && pi.new_row >= pi.row0 && pi.new_row < row_end && wave == 0 && lr == 0) {
+      *reinterpret_cast<uint4*>(const_cast<char*>(kbase) + (int64_t)pi.new_row * RB) =
+          *reinterpret_cast<const uint4*>(new_k_row);
+      *reinterpret_cast<uint4*>(const_cast<char*>(vbase) + (int64_t)pi.new_row * RB) =
+          *reinterpret_cast<const uint4*>(new_v_row);
+    }
+  }
+
   for (int pr = pi.row0 + wave * (RPI * U); pr < row_end; pr += ROWS_PER_PASS) {
     uint4 kk[U], vv[U];
     bool valid[U];
@@ -913,13 +942,13 @@ __global__ __launch_bounds__(256) void decode_valu_kernel(DecodeParams p) {
       const int r = pr + u * RPI + lr;
       valid[u] = r < row_end;
       const int rc = valid[u] ? r : (L - 1);         // stay inside the resident rows
-      kk[u] = load16_stream(kbase + (int64_t)rc * RB);
+      kk[u] = load16_stream(rc == pi.new_row ? new_k_row : kbase + (int64_t)rc * RB);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int r = pr + u * RPI + lr;
       const int rc = valid[u] ? r : (L - 1);
-      vv[u] = load16_stream(vbase + (int64_t)rc * RB);
+      vv[u] = load16_stream(rc == pi.new_row ? new_v_row : vbase + (int64_t)rc * RB);
     }
     float sc[U][G];
 #pragma unroll
@@ -993,7 +1022,15 @@ __global__ __launch_bounds__(256) void decode_valu_kernel(DecodeParams p) {
     }
   }
   __syncthreads();
+  // Fused step: one ticket per workgroup, taken once all its waves have used the rows they read
+  // (the barrier above); the answer comes back under the merge.  The workgroup that draws the
+  // sequence's last one finishes the step.
+  int ticket = -1;
+  if (pi.update && tid == 0) ticket = atomicAdd(p.tickets + pi.s * kTicketStride, 1);
   merge_waves_and_store<kValuWaves, D>(p, pi, s_m, s_l, s_acc, G, G * D);
+  if (!pi.update || wave != 0) return;
+  if (__builtin_amdgcn_readfirstlane(ticket) != p.Hkv * pi.nchunks - 1) return;
+  finish_step<RB>(p, pi, lane);
 }
 
 // ---------------------------------------------------------------------------
@@ -1299,11 +1336,6 @@ static int32_t check_attention_args(const bc_shape* shape, const bc_cache* cache
   return BC_OK;
 }
 
-// bc_cache_ops.hip
-int32_t launch_budget_mark(const bc_shape* shape, const bc_cache* cache, const int32_t* budget,
-                           const uint8_t* live, int32_t* mark, hipStream_t hs);
-int32_t launch_budget_apply(const bc_shape* shape, uint8_t* live, int32_t* mark, hipStream_t hs);
-
 }  // namespace bc
 
 using namespace bc;
@@ -1383,16 +1415,9 @@ static int32_t decode_step_checked(const bc_shape* shape, const bc_cache* cache,
   if (!k || !v || !aligned16(k) || !aligned16(v)) return BC_ERR_ARG;
   if ((beacon_k == nullptr) != (beacon_v == nullptr)) return BC_ERR_ARG;
   if (beacon_k && (!aligned16(beacon_k) || !aligned16(beacon_v))) return BC_ERR_ARG;
-  if (pl.lds)     // one launch: append, attention and eviction fused
-    return launch_attention(shape, cache, pl, q, out, active, workspace, k, v, beacon_k, beacon_v,
-                            as_stream(stream));
-  int32_t st = bc_append_kv(shape, cache, k, v, active, BC_ROW_TOKEN, stream);
-  if (st != BC_OK) return st;
-  st = launch_attention(shape, cache, pl, q, out, active, workspace, nullptr, nullptr, nullptr,
-                        nullptr, as_stream(stream));
-  if (st != BC_OK) return st;
-  if (beacon_k) st = bc_compress_evict(shape, cache, beacon_k, beacon_v, active, 1, stream);
-  return st;
+  // one launch, whichever kernel serves the shape: append, attention and eviction fused
+  return launch_attention(shape, cache, pl, q, out, active, workspace, k, v, beacon_k, beacon_v,
+                          as_stream(stream));
 }
 
 extern "C" int32_t bc_decode_step(const bc_shape* shape, const bc_cache* cache, const void* k,
@@ -1466,15 +1491,9 @@ extern "C" int32_t bc_beacon_step(const bc_shape* shape, const bc_cache* cache, 
   int32_t st = check_attention_args(shape, cache, q, out, workspace, workspace_bytes, &pl);
   if (st != BC_OK) return st;
   if (!k || !v || !aligned16(k) || !aligned16(v)) return BC_ERR_ARG;
-  if (pl.lds)     // one launch: beacon row at the tail, its attention, compaction
-    return launch_attention(shape, cache, pl, q, out, active, workspace, k, v, k, v,
-                            as_stream(stream), nullptr, nullptr, true);
-  st = bc_append_kv(shape, cache, k, v, active, BC_ROW_BEACON, stream);
-  if (st != BC_OK) return st;
-  st = launch_attention(shape, cache, pl, q, out, active, workspace, nullptr, nullptr, nullptr,
-                        nullptr, as_stream(stream));
-  if (st != BC_OK) return st;
-  return bc_compress_evict(shape, cache, nullptr, nullptr, active, 1, stream);
+  // one launch: beacon row at the tail, its attention, compaction
+  return launch_attention(shape, cache, pl, q, out, active, workspace, k, v, k, v,
+                          as_stream(stream), nullptr, nullptr, true);
 }
 
 extern "C" int32_t bc_decode_step_budget(const bc_shape* shape, const bc_cache* cache, const void* k,
@@ -1488,24 +1507,8 @@ extern "C" int32_t bc_decode_step_budget(const bc_shape* shape, const bc_cache* 
   if (!k || !v || !aligned16(k) || !aligned16(v) || !budget || !live) return BC_ERR_ARG;
   if ((beacon_k == nullptr) != (beacon_v == nullptr)) return BC_ERR_ARG;
   if (beacon_k && (!aligned16(beacon_k) || !aligned16(beacon_v))) return BC_ERR_ARG;
-  if (pl.lds)
-    return launch_attention(shape, cache, pl, q, out, live, workspace, k, v, beacon_k, beacon_v,
-                            as_stream(stream), budget, live);
-  // other shapes: the same steps as separate launches.  The cap is tested on the state the
-  // attention saw (before the eviction); the mask changes only after the eviction has used it.
-  // The per-sequence counters at the head of the workspace (unused on this path) hold the marks.
-  int32_t* mark = static_cast<int32_t*>(workspace);
-  hipStream_t hs = as_stream(stream);
-  st = bc_append_kv(shape, cache, k, v, live, BC_ROW_TOKEN, stream);
-  if (st != BC_OK) return st;
-  st = launch_attention(shape, cache, pl, q, out, live, workspace, nullptr, nullptr, nullptr,
-                        nullptr, hs);
-  if (st != BC_OK) return st;
-  st = launch_budget_mark(shape, cache, budget, live, mark, hs);
-  if (st != BC_OK) return st;
-  if (beacon_k) {
-    st = bc_compress_evict(shape, cache, beacon_k, beacon_v, live, 1, stream);
-    if (st != BC_OK) return st;
-  }
-  return launch_budget_apply(shape, live, mark, hs);
+  // The cap is tested on the state the attention saw (before the eviction); the holder of the
+  // sequence's last ticket clears the mask after the eviction has used it.
+  return launch_attention(shape, cache, pl, q, out, live, workspace, k, v, beacon_k, beacon_v,
+                          as_stream(stream), budget, live);
 }

@@ -223,12 +223,13 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
       }
       float tmax = fmaxf(fmaxf(fmaxf(fmaxf(sv[0], sv[1]), sv[2]), fmaxf(fmaxf(sv[3], sv[4]), sv[5])),
                          fmaxf(sv[6], sv[7]));
-      tmax = rows_allreduce_max(tmax);
       // Lazy reference: the running reference m only moves when the tile's maximum exceeds it by
       // more than kPfLazy (log2 units); until then weights are at most 2^kPfLazy, which fp32 sums
       // and the two-part bf16 weights carry without loss, and the accumulators need no rescale.
-      // The test runs on the unscaled maximum against grow_at = (m + kPfLazy) / qs.
+      // The test runs on the unscaled maximum against grow_at = (m + kPfLazy) / qs - on each
+      // lane's own eight keys: only when some lane passes the mark are the row maxima needed.
       if (__any(tmax > grow_at[h])) {
+        tmax = rows_allreduce_max(tmax);
         const float m_cand = tmax * p.qscale;                   // kNegBig * qs stays hugely negative
         const float m_new = m_cand > m_run[h] + kPfLazy ? m_cand : m_run[h];
         const float alpha = fast_exp2(m_run[h] - m_new);

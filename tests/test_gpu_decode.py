@@ -175,6 +175,30 @@ def test_fused_step_bf16_every_step(dev, c, P, d):
     rollout(wl, rt, oc, 150, steps, steps, use_step_call=True)
 
 
+@pytest.mark.parametrize("dtype,d,B", [("f32", 128, 6), ("f32", 64, 6), ("bf16", 128, 6), ("bf16", 64, 6),
+                                       ("f32", 128, 2), ("bf16", 128, 2)])
+def test_fused_step_on_the_plain_alu_kernel(dev, dtype, d, B):
+    # the same single-launch step on the kernel that serves fp32 rows (and bf16 rows when the
+    # plan asks for it): ragged ratios with c = 1 and no compression among them, sequences that
+    # end early, the budget-free and the beacon-step forms; tables, slabs and outputs each step.
+    # B = 2 with a long prompt spreads a sequence's rows over several workgroups and a merge
+    # launch, each workgroup taking its own ticket.
+    P = np.array([1100, 1050], np.int32) if B == 2 else np.array([40, 0, 17, 64, 5, 33], np.int32)
+    c = np.array([16, 3], np.int32) if B == 2 else np.array([16, 1, 0, 3, 2, 7], np.int32)
+    G = np.array([70, 70], np.int32) if B == 2 else np.array([70, 70, 50, 70, 21, 70], np.int32)
+    for beacon_call in (False, True):
+        wl = W.Workload("fused_alu", 90 + d + B, B, 4, 2, d, dtype, P, G, c)
+        rt, oc = make(wl, dev)
+        if dtype == "bf16":
+            rt.cache.plan = _bc().BC_PLAN_PLAIN_ALU
+        st, text = _bc().bc_decode_plan_describe(rt.shape, rt.cache)
+        assert st == 0 and "decode_valu_kernel" in text, text
+        if B == 2:
+            assert int(text.split("chunks=")[1].split()[0]) > 1, text
+        steps = range(1, 71)
+        rollout(wl, rt, oc, 70, steps, steps, use_step_call=not beacon_call, beacon_call=beacon_call)
+
+
 @pytest.mark.parametrize("promise", ["as built", "none", "prompt too long", "prompt too short"])
 @pytest.mark.parametrize("Hkv,d", [(2, 128), (8, 128), (2, 64)])
 def test_uniform_layout_promise_is_only_a_hint(dev, promise, Hkv, d):
