@@ -202,20 +202,26 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
         ka[t][i] = *reinterpret_cast<const bf16x8_t*>(tk + row * 256 + (((4 * i + kb) ^ lds_swz(row)) << 4));
     }
     bf16x8_t phi[HPW], plo[HPW];
+    // the scores of every head first: 2 * HPW independent accumulation chains keep the matrix
+    // pipe full, and the first head's scores are back when its softmax starts
+    f32x4_t Sx[HPW][2];
+#pragma unroll
+    for (int h = 0; h < HPW; ++h)
+#pragma unroll
+      for (int t = 0; t < 2; ++t) Sx[h][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int h = 0; h < HPW; ++h)
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+          Sx[h][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[t][i], qb[h][i], Sx[h][t], 0, 0, 0);
 #pragma unroll
     for (int h = 0; h < HPW; ++h) {
-      f32x4_t Sx[2];
-#pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        Sx[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-          Sx[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[t][i], qb[h][i], Sx[t], 0, 0, 0);
-      }
       float sv[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        sv[e] = Sx[e >> 2][e & 3];
+        sv[e] = Sx[h][e >> 2][e & 3];
       }
       if (MASKED) {
 #pragma unroll
