@@ -88,7 +88,7 @@ def test_noalloc_step_equals_the_step_with_a_workspace(dev):
 
 def test_noalloc_step_on_the_plain_alu_path(dev):
     import torch
-    # fp32 shapes run append, attention and eviction as separate launches; same contract
+    # fp32 rows: the fused step on the plain-ALU kernel, one ticket per workgroup in the scratch array
     wl = W.tiny()
     ref, sta = _pair(wl, dev)
     for t in range(1, 20):
@@ -96,4 +96,47 @@ def test_noalloc_step_on_the_plain_alu_path(dev):
         q = wl.step_q(t)
         bk, bv = wl.beacon_kv(t)
         assert torch.equal(ref.decode_step(k, v, q, bk, bv), sta.decode_step_noalloc(k, v, q, bk, bv)), t
+    _same_state(ref, sta)
+
+
+def test_noalloc_step_captured_in_a_graph(dev):
+    import torch
+    from paper_2510_13797_amd import bc
+    # the callers the entry point is for: a cycle of steps captured as a HIP graph (no allocation,
+    # the counters cleared by a fill kernel, not a memset node) and replayed, with eager work and
+    # synchronisations between the replays; every replay equals the eager run on a workspace
+    B, cyc, ncyc = 8, 4, 4
+    wl = W.Workload("noalloc_graph", 97, B, 12, 2, 128, "bf16", np.array([3, 40, 0, 17, 64, 5, 33, 1], np.int32),
+                    np.full(B, cyc * ncyc, np.int32), np.array([4, 2, 0, 1, 3, 4, 2, 4], np.int32))
+    ref, sta = _pair(wl, dev)
+    pool = []
+    for j in range(1, cyc + 1):
+        k, v = wl.step_kv(j)
+        bk, bv = wl.beacon_kv(j)
+        pool.append({n: bc.to_device(a, "bf16", dev) for n, a in dict(k=k, v=v, q=wl.step_q(j), bk=bk, bv=bv).items()})
+    outs_ref = [torch.empty_like(ref.out) for _ in range(cyc)]
+    outs_sta = [torch.empty_like(sta.out) for _ in range(cyc)]
+    want = []
+    for _ in range(ncyc):
+        for j, x in enumerate(pool):
+            ref.decode_step(x["k"], x["v"], x["q"], x["bk"], x["bv"], out=outs_ref[j])
+        torch.cuda.synchronize()
+        want.append([o.clone() for o in outs_ref])
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        for j, x in enumerate(pool):                       # first cycle eagerly (also takes the scratch address)
+            sta.decode_step_noalloc(x["k"], x["v"], x["q"], x["bk"], x["bv"], out=outs_sta[j])
+        st.synchronize()
+        assert all(torch.equal(a, b) for a, b in zip(outs_sta, want[0]))
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=st):
+            for j, x in enumerate(pool):
+                sta.decode_step_noalloc(x["k"], x["v"], x["q"], x["bk"], x["bv"], out=outs_sta[j])
+        for r in range(1, ncyc):
+            g.replay()
+            st.synchronize()
+            for j in range(cyc):
+                assert torch.equal(outs_sta[j], want[r][j]), (r, j)
+            sta.decode_attn(pool[0]["q"], out=torch.empty_like(sta.out))      # eager work between replays
+            assert sta.tables()[2] == 0
     _same_state(ref, sta)
