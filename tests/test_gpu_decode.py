@@ -745,6 +745,46 @@ def test_randomised_small_rollouts(dev, case):
             use_step_call=(form == 2), beacon_call=(form == 3))
 
 
+@pytest.mark.parametrize("case", range(24))
+def test_randomised_rollouts_near_the_plan_boundaries(dev, case):
+    # seeded random batches whose pair counts straddle the kernel choices (128 and 256 pairs) and
+    # whose prompt lengths straddle the tile and capacity limits of the straight-line form (384 /
+    # 768 rows) and of the twelve-wave and small-workgroup forms (1100 rows); call form, dispatch
+    # order and uniform / ragged layout rotate with the seed
+    rng = np.random.default_rng([424242, case])
+    dtype, d = [("bf16", 128), ("bf16", 128), ("bf16", 64), ("f32", 64), ("f32", 128), ("bf16", 128)][case % 6]
+    Hq, Hkv = [(12, 2), (4, 4), (8, 1), (6, 2), (7, 1), (16, 2), (3, 1), (32, 8), (24, 8), (2, 2)][int(rng.integers(0, 10))]
+    kind = case % 4
+    if kind == 0:
+        B = max(1, int(rng.integers(120, 136)) // Hkv)
+    elif kind == 1:
+        B = max(1, int(rng.integers(250, 264)) // Hkv)
+    elif kind == 2:
+        B = int(rng.integers(1, 40))
+    else:
+        B = max(1, int(rng.integers(300, 400)) // Hkv)
+    B = min(B, 200)
+    uniform = bool(rng.integers(0, 2))
+    pbase = int(rng.choice([0, 31, 33, 256, 352, 383, 384, 500, 700, 760, 1060, 1090, 1500]))
+    if dtype == "f32":
+        pbase = min(pbase, 400)
+    P = np.full(B, pbase, np.int32) if uniform else np.maximum(0, pbase + rng.integers(-40, 40, size=B)).astype(np.int32)
+    c = (np.full(B, int(rng.choice([0, 1, 2, 3, 7, 16, 32])), np.int32) if uniform
+         else rng.choice([0, 1, 2, 5, 16, 32], size=B).astype(np.int32))
+    steps = int(rng.integers(20, 50))
+    G = np.full(B, steps, np.int32) if uniform else rng.integers(1, steps + 1, size=B).astype(np.int32)
+    G[int(rng.integers(0, B))] = steps
+    form = int(rng.integers(0, 4))
+    wl = W.Workload("bound%d" % case, 5000 + case, B, Hq, Hkv, d, dtype, P, G, c)
+    rt, oc = make(wl, dev)
+    sort = B * Hkv > 256 and bool(rng.integers(0, 2))
+    attn = sorted(set(int(x) for x in rng.integers(1, steps + 1, size=5)) | {1, steps})
+    sample = None if B <= 24 else sorted(set(int(x) for x in rng.integers(0, B, size=16)))
+    rollout(wl, rt, oc, steps, attn, (steps // 2, steps), table_every=7, tail_form=(form == 1),
+            use_step_call=(form == 2), beacon_call=(form == 3), seq_sample=sample,
+            before_step=(lambda t: rt.sort_by_length()) if sort else None)
+
+
 def test_fused_steps_under_graph_replay(dev):
     # The benchmark replays a captured cycle of fused steps.  One runtime runs five 4-step cycles
     # eagerly, a twin runs the first cycle eagerly, captures the cycle as a HIP graph and replays
