@@ -917,38 +917,29 @@ __global__ __launch_bounds__(256) void decode_valu_kernel(DecodeParams p) {
     for (int e = 0; e < EPL; ++e) acc[h][e] = 0.f;
   }
 
-  // Fused step: the appended row is not in the slab yet.  Whoever needs row `new_row` reads it
-  // from the caller's tensors instead; the workgroup whose chunk holds it stores it for later
-  // steps (unless this step's eviction drops it at once).  No reader touches the slab at that
-  // row in this launch, so the store races with nothing.
-  const char* new_k_row = kbase, *new_v_row = vbase;
-  if (pi.new_row >= 0) {
-    const int64_t at = (int64_t)(pi.s * p.Hkv + pi.kvh) * RB + ls * 16;
-    new_k_row = p.new_k + at;
-    new_v_row = p.new_v + at;
-    if (pi.store_new_row && pi.new_row >= pi.row0 && pi.new_row < row_end && wave == 0 && lr == 0) {
-      *reinterpret_cast<uint4*>(const_cast<char*>(kbase) + (int64_t)pi.new_row * RB) =
-          *reinterpret_cast<const uint4*>(new_k_row);
-      *reinterpret_cast<uint4*>(const_cast<char*>(vbase) + (int64_t)pi.new_row * RB) =
-          *reinterpret_cast<const uint4*>(new_v_row);
-    }
-  }
+  // Fused step: the appended row (always the sequence's last) is not in the slab yet.  The loop
+  // below covers the rows that are; the workgroup whose chunk holds the appended row takes it
+  // from the caller's tensors in a pass of its own behind the loop and stores it for later steps
+  // (unless this step's eviction drops it at once).  No reader touches the slab at that row in
+  // this launch, so the store races with nothing.
+  const bool new_row_here = pi.new_row >= pi.row0 && pi.new_row < row_end;      // (uniform)
+  const int slab_end = new_row_here ? pi.new_row : row_end;
 
-  for (int pr = pi.row0 + wave * (RPI * U); pr < row_end; pr += ROWS_PER_PASS) {
+  for (int pr = pi.row0 + wave * (RPI * U); pr < slab_end; pr += ROWS_PER_PASS) {
     uint4 kk[U], vv[U];
     bool valid[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int r = pr + u * RPI + lr;
-      valid[u] = r < row_end;
-      const int rc = valid[u] ? r : (L - 1);         // stay inside the resident rows
-      kk[u] = load16_stream(rc == pi.new_row ? new_k_row : kbase + (int64_t)rc * RB);
+      valid[u] = r < slab_end;
+      const int rc = valid[u] ? r : (slab_end - 1);  // stay inside the resident rows
+      kk[u] = load16_stream(kbase + (int64_t)rc * RB);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int r = pr + u * RPI + lr;
-      const int rc = valid[u] ? r : (L - 1);
-      vv[u] = load16_stream(rc == pi.new_row ? new_v_row : vbase + (int64_t)rc * RB);
+      const int rc = valid[u] ? r : (slab_end - 1);
+      vv[u] = load16_stream(vbase + (int64_t)rc * RB);
     }
     float sc[U][G];
 #pragma unroll
@@ -989,6 +980,36 @@ __global__ __launch_bounds__(256) void decode_valu_kernel(DecodeParams p) {
       for (int h = 0; h < G; ++h)
 #pragma unroll
         for (int e = 0; e < EPL; ++e) acc[h][e] = fmaf(sc[u][h], vf[e], acc[h][e]);
+    }
+  }
+
+  if (new_row_here && wave == 0) {
+    // the appended row: one more row for the first lane group of the first wave
+    const int64_t at = (int64_t)(pi.s * p.Hkv + pi.kvh) * RB + ls * 16;
+    const uint4 kq = *reinterpret_cast<const uint4*>(p.new_k + at);
+    const uint4 vq = *reinterpret_cast<const uint4*>(p.new_v + at);
+    if (pi.store_new_row && lr == 0) {
+      *reinterpret_cast<uint4*>(const_cast<char*>(kbase) + (int64_t)pi.new_row * RB) = kq;
+      *reinterpret_cast<uint4*>(const_cast<char*>(vbase) + (int64_t)pi.new_row * RB) = vq;
+    }
+    float kf[EPL], vf[EPL];
+    unpack16(kq, kf, T{});
+    unpack16(vq, vf, T{});
+    const bool mine = lr == 0;
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+      float a = 0.f;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) a = fmaf(qf[h][e], kf[e], a);
+      a = group_allreduce_sum<LPR>(a);
+      const float sc1 = mine ? a : kNegBig;
+      const float mn = fmaxf(m[h], sc1);
+      const float alpha = fast_exp2(m[h] - mn);
+      const float pw = mine ? fast_exp2(sc1 - mn) : 0.f;
+      m[h] = mn;
+      l[h] = l[h] * alpha + pw;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) acc[h][e] = fmaf(pw, vf[e], acc[h][e] * alpha);
     }
   }
 
