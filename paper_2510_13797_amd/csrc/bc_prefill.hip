@@ -302,6 +302,8 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
     const char* tv = tk + kPfTile;
     stage = stage + 1 == kPfStages ? 0 : stage + 1;
     const TileDesc td = tile_desc(kt);
+    // a band tile that starts behind the last of this wave's 16 rows holds nothing they may see
+    if (td.predicate && td.j0 > r0 + 16 * tg + 15) continue;
     tile_body(tk, tv, td);
   }
   __syncthreads();          // the tile stages are free: the epilogue reuses LDS

@@ -249,6 +249,8 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dq_kernel(BwdPar
     const char* tv = tk + kBwTile;
     stage = stage + 1 == kBwStages ? 0 : stage + 1;
     const TileDesc td = tile_desc(kt);
+    // a band tile that starts behind the last of this wave's 16 rows holds nothing they may see
+    if (td.predicate && td.j0 > r0 + 16 * wave + 15) continue;
 
     // a full tile of the prompt or beacon run under a full query tile needs no per-key tests
     // (uniform over the workgroup: skipped by a scalar branch)
@@ -402,6 +404,13 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dkv_kernel(BwdPa
     dense_from_rt = ((kBwBM - 1) * cp1 + kBwBN) / kBwBN;
   if (!key_ok) jkey = rs;                      // loads stay in range; contributions are masked
   const int win_j = (c > 0 && jkey >= Pk) ? (int)window_of(ws, (uint32_t)(jkey - Pk)) : -1;
+  // the rows this wave's 16 keys can be seen from: [first key, last row of the last key's reach]
+  int wave_first_key = __builtin_amdgcn_readfirstlane(jkey);      // (lane 0 holds the smallest key)
+  int wave_last_row = !key_ok ? -1 : kind == 2 ? min(re, Pk + (win_j + 1) * cp1 - 1) : re;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) wave_last_row = max(wave_last_row, __shfl_xor(wave_last_row, off, 64));
+  wave_last_row = __builtin_amdgcn_readfirstlane(wave_last_row);
+  if (wave_last_row < 0) { wave_first_key = rs; wave_last_row = re; }     // no valid key: nothing is skipped (all masked)
 
   // K^T and V^T of the wave's keys as B operands (column n = key, k = head-dim index)
   bf16x8_t kop[4], vop[4];
@@ -465,6 +474,9 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dkv_kernel(BwdPa
     stage = stage + 1 == kBwStages ? 0 : stage + 1;
     const int rt = cur_rt;
     if (--cur_rt < 0) cur_rt = ntile - 1;
+    // a row tile that ends in front of this wave's first key, or starts behind the last row any
+    // of its keys is seen from (the end of a response token's window), adds nothing here
+    if (rs + rt * kBwBN + kBwBN - 1 < wave_first_key || rs + rt * kBwBN > wave_last_row) continue;
     const int row0 = rs + rt * kBwBN + 8 * kb;          // this lane's 8 rows: row0 + e
 
     // per-row statistics of this lane's rows (head-major, 8 rows = 64 contiguous bytes)
