@@ -280,7 +280,7 @@ int32_t bc_set_ratio(const bc_shape *shape, const bc_cache *cache, const int32_t
  * out: [total_rows, Hq, d] fp32; lse (nullable): [total_rows, Hq] fp32, natural log of
  * the softmax denominator.  row_offsets: device [B+1] int64; P, c: device [B] int32;
  * max_rows: HOST value >= the longest trajectory (sizes the grid), < 2^26.  scale must be > 0 and finite (else BC_ERR_ARG).
- * Supported: kv_dtype BC_BF16 with d = 128; anything else is BC_ERR_SHAPE. */
+ * Supported: kv_dtype BC_BF16 with d = 128 or 64; fp32 inputs are BC_ERR_SHAPE. */
 int32_t bc_prefill_attn(const bc_shape *shape, const void *q, const void *k, const void *v,
                         const int64_t *row_offsets, const int32_t *P, const int32_t *c,
                         int32_t max_rows, float *out, float *lse, void *stream);

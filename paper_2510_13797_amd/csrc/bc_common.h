@@ -33,6 +33,35 @@ __device__ __forceinline__ int lds_swz(int row) {
   return ((row & 3) << 1) | (((row >> 3) & 1) << 3) | ((row >> 4) & 1);
 }
 
+// Swizzle of the 16-byte units of a tile row in LDS: unit u of row `row` lives at position
+// u ^ tile_swz<D>(row).  D = 128 (16 units per row): lds_swz.  D = 64 (8 units per row, two rows
+// per 256 bytes of banks): the 128-bit reads of one unit from the 8 rows {a, a+1, a+2, a+3, a+8,
+// .., a+11} must hit 8 different 16-byte bank groups - the row parity gives two, bits 1 and 3 of
+// the row the other four - and the transposing 64-bit reads of a half wave (rows {a..a+3} and
+// {a+8..a+11}, two adjacent units each) the 32 different 8-byte slots, which the same bits give.
+template <int D> __device__ __forceinline__ int tile_swz(int row);
+template <> __device__ __forceinline__ int tile_swz<128>(int row) { return lds_swz(row); }
+template <> __device__ __forceinline__ int tile_swz<64>(int row) {
+  return (((row >> 1) & 1) << 1) | (((row >> 3) & 1) << 2);
+}
+
+// A wait for the wave's vector-memory counter with a count known at compile time (the
+// instruction takes an immediate).
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N <= 40, "counts used by the kernels");
+  if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  else if constexpr (N == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+  else if constexpr (N == 3) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
+  else if constexpr (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+  else if constexpr (N == 5) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+  else if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+  else if constexpr (N == 12) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+  else if constexpr (N == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+  else if constexpr (N == 20) asm volatile("s_waitcnt vmcnt(20)" ::: "memory");
+  else if constexpr (N == 24) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
+  else static_assert(N < 0, "add the count");
+}
+
 // x minus one half of the bf16 pair hp, exactly, in one instruction: the bf16 dot product with a
 // selector pair that holds -1 in that half and 0 in the other, accumulated onto x.  Used to split
 // an fp32 value into two bf16 parts (hp holds the rounded high parts of two values).  The

@@ -404,18 +404,6 @@ __device__ __forceinline__ uint4 load16_stream(const char* p) {
 
 template <> __device__ __forceinline__ uint4 load16<true>(const char* p) { return load16_stream(p); }
 
-// Swizzle of the 16-byte units of a tile row in LDS: unit u of row `row` lives at position
-// u ^ tile_swz<D>(row).  D = 128 (16 units per row): lds_swz.  D = 64 (8 units per row, two rows
-// per 256 bytes of banks): the 128-bit reads of one unit from the 8 rows {a, a+1, a+2, a+3, a+8,
-// .., a+11} must hit 8 different 16-byte bank groups - the row parity gives two, bits 1 and 3 of
-// the row the other four - and the transposing 64-bit reads of a half wave (rows {a..a+3} and
-// {a+8..a+11}, two adjacent units each) the 32 different 8-byte slots, which the same bits give.
-template <int D> __device__ __forceinline__ int tile_swz(int row);
-template <> __device__ __forceinline__ int tile_swz<128>(int row) { return lds_swz(row); }
-template <> __device__ __forceinline__ int tile_swz<64>(int row) {
-  return (((row >> 1) & 1) << 1) | (((row >> 3) & 1) << 2);
-}
-
 // STREAM: 1 = load K and V with the non-temporal policy (large launches; small ones are
 // latency-bound and about a microsecond faster with the default policy, 0); 2 = V only: with two
 // workgroups per pair and long caches the K lines, which the partner reads a little later, are
@@ -428,20 +416,6 @@ template <> __device__ __forceinline__ int tile_swz<64>(int row) {
 // multiple of 8: the K rows then come from HBM once.
 // NW: waves per workgroup, 8 or (two workgroups per pair, short caches: every wave then has one or
 // two tiles, and twelve waves finish a sequence of up to 384 rows in one pass) 12.
-// A wait for the wave's vector-memory counter with a count known at compile time (the
-// instruction takes an immediate).
-template <int N> __device__ __forceinline__ void wait_vmcnt() {
-  static_assert(N >= 0 && N <= 40, "counts used by the decode kernel");
-  if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  else if constexpr (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-  else if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-  else if constexpr (N == 12) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
-  else if constexpr (N == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-  else if constexpr (N == 20) asm volatile("s_waitcnt vmcnt(20)" ::: "memory");
-  else if constexpr (N == 24) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
-  else static_assert(N < 0, "add the count");
-}
-
 // SHORT: every wave has at most two tiles (the caller's max_cap is at most 2 * NW * 32 rows, one
 // chunk per pair, no dispatch order).  The code is then a straight line: query and appended row
 // are requested first (their addresses do not need the tables), then the K part of the first

@@ -28,9 +28,7 @@ namespace bc {
 constexpr int kPfWaves = 4;
 constexpr int kPfBM = 64;                 // query rows per workgroup
 constexpr int kPfBN = 32;                 // keys per tile
-constexpr int kPfTile = kPfBN * 256;      // bytes of one K (or V) tile
 constexpr int kPfStages = 3;
-constexpr int kPfLds = 49152;               // 3 stages of 16 KB in the loop, 4 x 8 KB in the epilogue
 
 typedef __attribute__((address_space(3))) void pf_lds_void_t;
 typedef __attribute__((address_space(1))) const void pf_global_void_t;
@@ -61,8 +59,21 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {      // RNE, a
 
 constexpr float kPfLazy = 5.0f;
 
-template <int HPW>     // query heads per wave (the group's heads are split over p.hsplit workgroups)
+// HPW: query heads per wave (the group's heads are split over p.hsplit workgroups); D: head
+// dimension, 128 or 64 (rows of 256 or 128 bytes: 16 or 8 units of 16 bytes, four or eight rows
+// per 1 KB LDS-DMA instruction, four or two 32-wide steps of the score product, eight or four
+// 16-column blocks of the output).
+template <int HPW, int D>
 __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams p) {
+  constexpr int ROWB = D * 2;                 // bytes of a K or V row
+  constexpr int UPR = ROWB / 16;              // 16-byte units per row
+  constexpr int KS = D / 32;                  // k-steps of the score product
+  constexpr int NJ = D / 16;                  // 16-column blocks of the output
+  constexpr int kPfTile = kPfBN * ROWB;       // bytes of one K (or V) tile
+  constexpr int RPI = 1024 / ROWB;            // rows per LDS-DMA instruction
+  constexpr int NLD = kPfBN / (RPI * kPfWaves);   // instructions per wave, tile and tensor
+  constexpr int kPfLds = kPfStages * 2 * kPfTile;   // the epilogue's 4 x 16 x D floats fit inside
+  static_assert(kPfLds >= kPfWaves * 16 * D * 4, "the output tiles fit the ring's LDS");
   __shared__ __attribute__((aligned(1024))) char lds[kPfLds];
   // grid: x = (head split, trajectory, KV head), y = query tile; workgroups are dispatched
   // x-fastest, so the longest tiles of every trajectory start first
@@ -95,9 +106,9 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
   const int n = lane & 15, kb = lane >> 4;
   const int tg = wave;
   const HalfSelectors sel = half_selectors();
-  const int64_t kv_row_bytes = (int64_t)p.Hkv * 256;
-  const char* kbase = p.k + (off0 * p.Hkv + kvh) * 256;
-  const char* vbase = p.v + (off0 * p.Hkv + kvh) * 256;
+  const int64_t kv_row_bytes = (int64_t)p.Hkv * ROWB;
+  const char* kbase = p.k + (off0 * p.Hkv + kvh) * ROWB;
+  const char* vbase = p.v + (off0 * p.Hkv + kvh) * ROWB;
 
   // Key tile kt covers 32 consecutive entries of one run.  Entry rr is row j0 + rr*step;
   // entries at and beyond nvalid do not exist (their loads are redirected to row r1).
@@ -115,16 +126,17 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
     t.nvalid = min(t.nvalid, kPfBN);
     return t;
   };
-  // HBM -> LDS gather of tile kt: this wave brings entries 4*wave .. 4*wave+3 of K and of V
-  const int ld_rr = 4 * wave + (lane >> 4);             // and ld_rr + 16 in the second pass
+  // HBM -> LDS gather of tile kt: one instruction moves RPI whole rows; this wave brings entries
+  // RPI*wave .. RPI*wave + RPI-1 of K and of V (and, d = 128, the same 16 entries further on)
+  const int ld_rr = RPI * wave + lane / UPR;
   auto issue_tile = [&](int kt, int stage) {
     const TileDesc t = tile_desc(kt);
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      const int rr = ld_rr + 16 * half;
+    for (int half = 0; half < NLD; ++half) {
+      const int rr = ld_rr + RPI * kPfWaves * half;
       const int j = rr < t.nvalid ? t.j0 + rr * t.step : r1;
-      const int64_t goff = (int64_t)j * kv_row_bytes + (((lane & 15) ^ lds_swz(rr)) << 4);
-      char* dst = lds + stage * (2 * kPfTile) + (wave + 4 * half) * 1024;
+      const int64_t goff = (int64_t)j * kv_row_bytes + (((lane & (UPR - 1)) ^ tile_swz<D>(rr)) << 4);
+      char* dst = lds + stage * (2 * kPfTile) + (wave + kPfWaves * half) * 1024;
       __builtin_amdgcn_global_load_lds((pf_global_void_t*)(kbase + goff), (pf_lds_void_t*)dst, 16, 0, 0);
       __builtin_amdgcn_global_load_lds((pf_global_void_t*)(vbase + goff),
                                        (pf_lds_void_t*)(dst + kPfTile), 16, 0, 0);
@@ -138,29 +150,29 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
   const int r = r0 + 16 * tg + n;
   const bool row_ok = r <= r1;
   const int rq = row_ok ? r : r1;
-  bf16x8_t qb[HPW][4];
+  bf16x8_t qb[HPW][KS];
 #pragma unroll
   for (int h = 0; h < HPW; ++h) {
     const int head = hh * HPW + h;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < KS; ++i) {
       uint4 x = make_uint4(0u, 0u, 0u, 0u);
       if (head < p.g)
         x = *reinterpret_cast<const uint4*>(
-            p.q + (((off0 + rq) * p.Hq + kvh * p.g + head) * 128 + 32 * i + 8 * kb) * 2);
+            p.q + (((off0 + rq) * p.Hq + kvh * p.g + head) * D + 32 * i + 8 * kb) * 2);
       qb[h][i] = __builtin_bit_cast(bf16x8_t, x);
     }
   }
   const int win_r = (c > 0 && r >= P) ? (int)window_of(ws, (uint32_t)(r - P)) : -1;
 
-  f32x4_t O[HPW][8];
+  f32x4_t O[HPW][NJ];
   float m_run[HPW], l_run[HPW], grow_at[HPW];
   const float inv_qscale = 1.0f / p.qscale;
 #pragma unroll
   for (int h = 0; h < HPW; ++h) {
     m_run[h] = kNegBig; l_run[h] = 0.f; grow_at[h] = (kNegBig + kPfLazy) * inv_qscale;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) O[h][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < NJ; ++j) O[h][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
   }
 
   // Body of one key tile.  Scores stay unscaled; the softmax scale enters through one fused
@@ -193,13 +205,13 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
     }
 
     // S^T = K . Q^T ; row m of sub-tile t is tile entry 8*(m/4) + 4*t + m%4
-    bf16x8_t ka[2][4];
+    bf16x8_t ka[2][KS];
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       const int row = ((n >> 2) << 3) + 4 * t + (n & 3);
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-        ka[t][i] = *reinterpret_cast<const bf16x8_t*>(tk + row * 256 + (((4 * i + kb) ^ lds_swz(row)) << 4));
+      for (int i = 0; i < KS; ++i)
+        ka[t][i] = *reinterpret_cast<const bf16x8_t*>(tk + row * ROWB + (((4 * i + kb) ^ tile_swz<D>(row)) << 4));
     }
     bf16x8_t phi[HPW], plo[HPW];
     // the scores of every head first: 2 * HPW independent accumulation chains keep the matrix
@@ -210,7 +222,7 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
 #pragma unroll
       for (int t = 0; t < 2; ++t) Sx[h][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < KS; ++i)
 #pragma unroll
       for (int h = 0; h < HPW; ++h)
 #pragma unroll
@@ -243,7 +255,7 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
         grow_at[h] = (m_new + kPfLazy) * inv_qscale;
         l_run[h] *= alpha;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) O[h][j] *= alpha;
+        for (int j = 0; j < NJ; ++j) O[h][j] *= alpha;
       }
       const float m_new = m_run[h];
       float pe[8];
@@ -273,12 +285,12 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
       const int rowa = 8 * kb + (rl >> 2), rowb = rowa + 4;
       const int sub = (rl & 1) << 3;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
+      for (int j = 0; j < NJ; ++j) {
         const int u = 2 * j + ((rl & 3) >> 1);
         const pf_s16x4_t a0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (pf_lds_s16x4_t*)(tv + rowa * 256 + ((u ^ lds_swz(rowa)) << 4) + sub));
+            (pf_lds_s16x4_t*)(tv + rowa * ROWB + ((u ^ tile_swz<D>(rowa)) << 4) + sub));
         const pf_s16x4_t a1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (pf_lds_s16x4_t*)(tv + rowb * 256 + ((u ^ lds_swz(rowb)) << 4) + sub));
+            (pf_lds_s16x4_t*)(tv + rowb * ROWB + ((u ^ tile_swz<D>(rowb)) << 4) + sub));
         const bf16x8_t av = __builtin_bit_cast(
             bf16x8_t, (pf_s16x8_t)__builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7));
 #pragma unroll
@@ -294,8 +306,8 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
   for (int kt = 0; kt < NT; ++kt) {
     // tile kt has landed (this wave's part); after the barrier everyone's part has, and
     // everyone has finished tile kt-1, whose stage is the one tile kt+2 goes into
-    if (kt + 1 < NT) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (kt + 1 < NT) wait_vmcnt<2 * NLD>();         // (the next tile's loads may stay out)
+    else wait_vmcnt<0>();
     __syncthreads();
     if (kt + 2 < NT) issue_tile(kt + 2, stage >= 1 ? stage - 1 : kPfStages - 1);
     const char* tk = lds + stage * (2 * kPfTile);
@@ -308,8 +320,10 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
   }
   __syncthreads();          // the tile stages are free: the epilogue reuses LDS
 
-  // ---- epilogue: normalise, transpose through LDS, write each 512-byte row as one burst
-  float* my = reinterpret_cast<float*>(lds + wave * 8192);        // [16 rows][128] fp32, swizzled
+  // ---- epilogue: normalise, transpose through LDS, write each row of D floats as one burst
+  constexpr int OLPR = D / 4;                 // lanes that cover one output row, 16 bytes each
+  constexpr int ORPP = 64 / OLPR;             // rows per pass
+  float* my = reinterpret_cast<float*>(lds + wave * (16 * D * 4));        // [16 rows][D] fp32, swizzled
 #pragma unroll
   for (int h = 0; h < HPW; ++h) {
     const int head = hh * HPW + h;
@@ -317,20 +331,20 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
     l = rows_allreduce_sum(l);
     const float inv = 1.0f / l;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int unit = (4 * j + kb) ^ n;                // 16-byte units of a 512-byte row
-      *reinterpret_cast<f32x4_t*>(my + n * 128 + unit * 4) = O[h][j] * inv;
+    for (int j = 0; j < NJ; ++j) {
+      const int unit = (4 * j + kb) ^ n;                // 16-byte units of an output row
+      *reinterpret_cast<f32x4_t*>(my + n * D + unit * 4) = O[h][j] * inv;
     }
     if (head < p.g) {
-      // 32 lanes cover one row (16 bytes each), two rows per pass
+      // OLPR lanes cover one row (16 bytes each), ORPP rows per pass
 #pragma unroll
-      for (int pass = 0; pass < 8; ++pass) {
-        const int t = 2 * pass + (lane >> 5), unit = lane & 31;
-        const f32x4_t val = *reinterpret_cast<const f32x4_t*>(my + t * 128 + ((unit ^ t) << 2));
+      for (int pass = 0; pass < 16 / ORPP; ++pass) {
+        const int t = ORPP * pass + lane / OLPR, unit = lane & (OLPR - 1);
+        const f32x4_t val = *reinterpret_cast<const f32x4_t*>(my + t * D + ((unit ^ t) << 2));
         const int rr = r0 + 16 * tg + t;
         if (rr <= r1)     // written once, not read again by this launch: streaming store
           __builtin_nontemporal_store(val, reinterpret_cast<f32x4_t*>(
-              p.out + ((off0 + rr) * p.Hq + kvh * p.g + head) * 128 + unit * 4));
+              p.out + ((off0 + rr) * p.Hq + kvh * p.g + head) * D + unit * 4));
       }
       if (p.lse && kb == 0 && row_ok)
         p.lse[(off0 + r) * p.Hq + kvh * p.g + head] = (m_run[h] + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
@@ -348,7 +362,7 @@ extern "C" int32_t bc_prefill_attn(const bc_shape* shape, const void* q, const v
                                    void* stream) {
   int32_t st = check_shape(shape);
   if (st != BC_OK) return st;
-  if (shape->kv_dtype != BC_BF16 || shape->d != 128) return BC_ERR_SHAPE;
+  if (shape->kv_dtype != BC_BF16) return BC_ERR_SHAPE;
   if (!q || !k || !v || !row_offsets || !P || !c || !out) return BC_ERR_ARG;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return BC_ERR_ARG;
   if (max_rows < 1 || max_rows >= (1 << 26)) return BC_ERR_ARG;
@@ -369,10 +383,18 @@ extern "C" int32_t bc_prefill_attn(const bc_shape* shape, const void* q, const v
   p.pstride = (p.npairs + 7) & ~7;
   const dim3 grid(p.hsplit * p.pstride, (max_rows + kPfBM - 1) / kPfBM);
   hipStream_t hs = as_stream(stream);
-  switch (hpw) {
-    case 1: prefill_kernel<1><<<grid, kPfWaves * 64, 0, hs>>>(p); break;
-    case 2: prefill_kernel<2><<<grid, kPfWaves * 64, 0, hs>>>(p); break;
-    default: prefill_kernel<3><<<grid, kPfWaves * 64, 0, hs>>>(p); break;
+  if (shape->d == 128) {
+    switch (hpw) {
+      case 1: prefill_kernel<1, 128><<<grid, kPfWaves * 64, 0, hs>>>(p); break;
+      case 2: prefill_kernel<2, 128><<<grid, kPfWaves * 64, 0, hs>>>(p); break;
+      default: prefill_kernel<3, 128><<<grid, kPfWaves * 64, 0, hs>>>(p); break;
+    }
+  } else {
+    switch (hpw) {
+      case 1: prefill_kernel<1, 64><<<grid, kPfWaves * 64, 0, hs>>>(p); break;
+      case 2: prefill_kernel<2, 64><<<grid, kPfWaves * 64, 0, hs>>>(p); break;
+      default: prefill_kernel<3, 64><<<grid, kPfWaves * 64, 0, hs>>>(p); break;
+    }
   }
   return launch_status();
 }

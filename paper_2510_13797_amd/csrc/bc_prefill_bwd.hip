@@ -29,10 +29,20 @@ namespace bc {
 constexpr int kBwWaves = 4;
 constexpr int kBwBM = 64;                 // rows (dq kernel) or keys (dkv kernel) per workgroup
 constexpr int kBwBN = 32;                 // streamed entries per tile
-constexpr int kBwTile = kBwBN * 256;
 constexpr int kBwStages = 3;
-constexpr int kBwLds = kBwStages * 2 * kBwTile;      // 48 KB; the epilogues need 4 x 8 KB
 constexpr int kBwStatLds = kBwStages * 256;          // per-row statistics of the staged tiles (dkv kernel)
+// What follows from the head dimension D (128 or 64): rows of 256 or 128 bytes.
+template <int D> struct BwDims {
+  static constexpr int ROWB = D * 2;                 // bytes of a row of one head
+  static constexpr int UPR = ROWB / 16;              // 16-byte units per row
+  static constexpr int KS = D / 32;                  // k-steps of a product over the head dimension
+  static constexpr int NJ = D / 16;                  // 16-column blocks of a gradient tile
+  static constexpr int TILE = kBwBN * ROWB;          // bytes of one staged tile
+  static constexpr int RPI = 1024 / ROWB;            // rows per LDS-DMA instruction
+  static constexpr int NLD = kBwBN / (RPI * kBwWaves);   // instructions per wave, tile and tensor
+  static constexpr int LDS = kBwStages * 2 * TILE;   // 48 or 24 KB; the epilogues need 4 x 16 x D floats
+  static_assert(LDS >= kBwWaves * 16 * D * 4, "the gradient tiles fit the ring's LDS");
+};
 
 typedef __attribute__((address_space(3))) void bw_lds_void_t;
 typedef __attribute__((address_space(1))) const void bw_global_void_t;
@@ -55,7 +65,8 @@ struct BwdParams {
   float* dk;
   float* dv;
   float* stat;          // [Hq][total_rows][2]: lse*log2(e), Delta
-  float* part;          // [hsplit][2][total_rows][Hkv][128]: dk, dv partials of the dense key blocks
+  float* part;          // [hsplit][2][total_rows][Hkv][D]: dk, dv partials of the dense key blocks
+  int32_t D;            // head dimension (the reduction kernel reads it; the others are templates)
   int32_t hsplit;       // head splits of a dense key block (1: none), heads per split = ceil(g / hsplit)
   int64_t total_rows;
   int32_t Hq, Hkv, g;
@@ -85,38 +96,42 @@ __device__ __forceinline__ void bw_split(const float (&x)[8], bf16x8_t& hi, bf16
 
 // A operand "rows of the tile": lane (m = lane&15, kb = lane>>4) of sub-tile t reads tile entry
 // 8*(m/4) + 4*t + m%4, head-dim bytes 64*i + 16*kb (tile is row-major, 16-byte units swizzled)
+template <int D>
 __device__ __forceinline__ bf16x8_t bw_rows_operand(const char* tile, int t, int i, int n, int kb) {
   const int row = ((n >> 2) << 3) + 4 * t + (n & 3);
-  return *reinterpret_cast<const bf16x8_t*>(tile + row * 256 + (((4 * i + kb) ^ lds_swz(row)) << 4));
+  return *reinterpret_cast<const bf16x8_t*>(tile + row * (2 * D) + (((4 * i + kb) ^ tile_swz<D>(row)) << 4));
 }
 
 // A operand "tile transposed": M = 16 head-dim columns 16*j .., K = the 32 tile entries
+template <int D>
 __device__ __forceinline__ bf16x8_t bw_cols_operand(const char* tile, int j, int lane) {
   const int rl = lane & 15, kb = lane >> 4;
   const int rowa = 8 * kb + (rl >> 2), rowb = rowa + 4;
   const int sub = (rl & 1) << 3;
   const int u = 2 * j + ((rl & 3) >> 1);
   const bw_s16x4_t a0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-      (bw_lds_s16x4_t*)(tile + rowa * 256 + ((u ^ lds_swz(rowa)) << 4) + sub));
+      (bw_lds_s16x4_t*)(tile + rowa * (2 * D) + ((u ^ tile_swz<D>(rowa)) << 4) + sub));
   const bw_s16x4_t a1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-      (bw_lds_s16x4_t*)(tile + rowb * 256 + ((u ^ lds_swz(rowb)) << 4) + sub));
+      (bw_lds_s16x4_t*)(tile + rowb * (2 * D) + ((u ^ tile_swz<D>(rowb)) << 4) + sub));
   return __builtin_bit_cast(bf16x8_t, (bw_s16x8_t)__builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
-// [16 entries][128] fp32 accumulators of one wave (accumulator layout: lane (n, kb) holds
-// columns 16*j + 4*kb .. +3 of entry n) -> LDS -> one 512-byte burst per entry.
+// [16 entries][D] fp32 accumulators of one wave (accumulator layout: lane (n, kb) holds
+// columns 16*j + 4*kb .. +3 of entry n) -> LDS -> one burst of D floats per entry.
 // dst_row(t) returns the destination pointer of entry t or nullptr.
-template <typename F>
-__device__ __forceinline__ void bw_store_tile(float* my, const f32x4_t (&acc)[8], float mul, int lane,
+template <int D, typename F>
+__device__ __forceinline__ void bw_store_tile(float* my, const f32x4_t (&acc)[D / 16], float mul, int lane,
                                               F dst_row) {
+  constexpr int OLPR = D / 4;                 // lanes that cover one row, 16 bytes each
+  constexpr int ORPP = 64 / OLPR;             // rows per pass
   const int n = lane & 15, kb = lane >> 4;
 #pragma unroll
-  for (int j = 0; j < 8; ++j)
-    *reinterpret_cast<f32x4_t*>(my + n * 128 + (((4 * j + kb) ^ n) << 2)) = acc[j] * mul;
+  for (int j = 0; j < D / 16; ++j)
+    *reinterpret_cast<f32x4_t*>(my + n * D + (((4 * j + kb) ^ n) << 2)) = acc[j] * mul;
 #pragma unroll
-  for (int pass = 0; pass < 8; ++pass) {
-    const int t = 2 * pass + (lane >> 5), unit = lane & 31;
-    const f32x4_t val = *reinterpret_cast<const f32x4_t*>(my + t * 128 + ((unit ^ t) << 2));
+  for (int pass = 0; pass < 16 / ORPP; ++pass) {
+    const int t = ORPP * pass + lane / OLPR, unit = lane & (OLPR - 1);
+    const f32x4_t val = *reinterpret_cast<const f32x4_t*>(my + t * D + ((unit ^ t) << 2));
     float* dst = dst_row(t);
     if (dst) __builtin_nontemporal_store(val, reinterpret_cast<f32x4_t*>(dst + unit * 4));   // written once
   }
@@ -127,8 +142,12 @@ __device__ __forceinline__ void bw_store_tile(float* my, const f32x4_t (&acc)[8]
 // ---------------------------------------------------------------------------
 constexpr int kDqHeads = 2;      // query heads per workgroup
 
+template <int D>
 __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dq_kernel(BwdParams p) {
-  __shared__ __attribute__((aligned(1024))) char lds[kBwLds];
+  using Dm = BwDims<D>;
+  constexpr int ROWB = Dm::ROWB, UPR = Dm::UPR, KS = Dm::KS, NJ = Dm::NJ, kBwTile = Dm::TILE, RPI = Dm::RPI,
+                NLD = Dm::NLD;
+  __shared__ __attribute__((aligned(1024))) char lds[Dm::LDS];
   // grid: x = (head pair, trajectory, KV head), y = query tile, longest tiles of every
   // trajectory first (workgroups are dispatched x-fastest)
   // (the head pairs of one (trajectory, KV head) are `pstride` workgroups apart, a multiple of 8:
@@ -158,9 +177,9 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dq_kernel(BwdPar
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const HalfSelectors sel = half_selectors();
   const int n = lane & 15, kb = lane >> 4;
-  const int64_t kv_row_bytes = (int64_t)p.Hkv * 256;
-  const char* kbase = p.k + (off0 * p.Hkv + kvh) * 256;
-  const char* vbase = p.v + (off0 * p.Hkv + kvh) * 256;
+  const int64_t kv_row_bytes = (int64_t)p.Hkv * ROWB;
+  const char* kbase = p.k + (off0 * p.Hkv + kvh) * ROWB;
+  const char* vbase = p.v + (off0 * p.Hkv + kvh) * ROWB;
 
   struct TileDesc { int j0, step, nvalid; bool predicate; };
   auto tile_desc = [&](int kt) -> TileDesc {
@@ -176,15 +195,15 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dq_kernel(BwdPar
     t.nvalid = min(t.nvalid, kBwBN);
     return t;
   };
-  const int ld_rr = 4 * wave + (lane >> 4);
+  const int ld_rr = RPI * wave + lane / UPR;
   auto issue_tile = [&](int kt, int stage) {
     const TileDesc t = tile_desc(kt);
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      const int rr = ld_rr + 16 * half;
+    for (int half = 0; half < NLD; ++half) {
+      const int rr = ld_rr + RPI * kBwWaves * half;
       const int j = rr < t.nvalid ? t.j0 + rr * t.step : r1;
-      const int64_t goff = (int64_t)j * kv_row_bytes + (((lane & 15) ^ lds_swz(rr)) << 4);
-      char* dst = lds + stage * (2 * kBwTile) + (wave + 4 * half) * 1024;
+      const int64_t goff = (int64_t)j * kv_row_bytes + (((lane & (UPR - 1)) ^ tile_swz<D>(rr)) << 4);
+      char* dst = lds + stage * (2 * kBwTile) + (wave + kBwWaves * half) * 1024;
       __builtin_amdgcn_global_load_lds((bw_global_void_t*)(kbase + goff), (bw_lds_void_t*)dst, 16, 0, 0);
       __builtin_amdgcn_global_load_lds((bw_global_void_t*)(vbase + goff),
                                        (bw_lds_void_t*)(dst + kBwTile), 16, 0, 0);
@@ -198,7 +217,7 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dq_kernel(BwdPar
   const bool row_ok = r <= r1;
   const bool full_rows = r0 + kBwBM - 1 <= r1;
   const int rq = row_ok ? r : r1;
-  bf16x8_t qb[kDqHeads][4], dob[kDqHeads][4];
+  bf16x8_t qb[kDqHeads][KS], dob[kDqHeads][KS];
   float lse2[kDqHeads], delta[kDqHeads];
 #pragma unroll
   for (int h = 0; h < kDqHeads; ++h) {
@@ -207,13 +226,13 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dq_kernel(BwdPar
     const int64_t rh = (off0 + rq) * p.Hq + kvh * p.g + (head_ok ? head : 0);
     float part = 0.f;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < KS; ++i) {
       uint4 x = make_uint4(0u, 0u, 0u, 0u), y = make_uint4(0u, 0u, 0u, 0u);
       if (head_ok) {
-        x = *reinterpret_cast<const uint4*>(p.q + (rh * 128 + 32 * i + 8 * kb) * 2);
-        y = *reinterpret_cast<const uint4*>(p.dout + (rh * 128 + 32 * i + 8 * kb) * 2);
-        const float4 o0 = *reinterpret_cast<const float4*>(p.out + rh * 128 + 32 * i + 8 * kb);
-        const float4 o1 = *reinterpret_cast<const float4*>(p.out + rh * 128 + 32 * i + 8 * kb + 4);
+        x = *reinterpret_cast<const uint4*>(p.q + (rh * D + 32 * i + 8 * kb) * 2);
+        y = *reinterpret_cast<const uint4*>(p.dout + (rh * D + 32 * i + 8 * kb) * 2);
+        const float4 o0 = *reinterpret_cast<const float4*>(p.out + rh * D + 32 * i + 8 * kb);
+        const float4 o1 = *reinterpret_cast<const float4*>(p.out + rh * D + 32 * i + 8 * kb + 4);
         float dy[8];
         unpack16(y, dy, bf16_t{});
         part += dy[0] * o0.x + dy[1] * o0.y + dy[2] * o0.z + dy[3] * o0.w +
@@ -233,16 +252,16 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dq_kernel(BwdPar
   }
   const int win_r = (c > 0 && r >= P) ? (int)window_of(ws, (uint32_t)(r - P)) : -1;
 
-  f32x4_t dQ[kDqHeads][8];
+  f32x4_t dQ[kDqHeads][NJ];
 #pragma unroll
   for (int h = 0; h < kDqHeads; ++h)
 #pragma unroll
-    for (int j = 0; j < 8; ++j) dQ[h][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < NJ; ++j) dQ[h][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
   int stage = 0;
   for (int kt = 0; kt < NT; ++kt) {
-    if (kt + 1 < NT) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (kt + 1 < NT) wait_vmcnt<2 * NLD>();
+    else wait_vmcnt<0>();
     __syncthreads();
     if (kt + 2 < NT) issue_tile(kt + 2, stage >= 1 ? stage - 1 : kBwStages - 1);
     const char* tk = lds + stage * (2 * kBwTile);
@@ -286,9 +305,9 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dq_kernel(BwdPar
         Sx[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
         dPx[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          Sx[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bw_rows_operand(tk, t, i, n, kb), qb[h][i], Sx[t], 0, 0, 0);
-          dPx[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bw_rows_operand(tv, t, i, n, kb), dob[h][i], dPx[t], 0, 0, 0);
+        for (int i = 0; i < KS; ++i) {
+          Sx[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bw_rows_operand<D>(tk, t, i, n, kb), qb[h][i], Sx[t], 0, 0, 0);
+          dPx[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bw_rows_operand<D>(tv, t, i, n, kb), dob[h][i], dPx[t], 0, 0, 0);
         }
       }
       float ds[8];
@@ -305,8 +324,8 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dq_kernel(BwdPar
     }
     // dQ^T += K^T . dS^T
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const bf16x8_t kt_op = bw_cols_operand(tk, j, lane);
+    for (int j = 0; j < NJ; ++j) {
+      const bf16x8_t kt_op = bw_cols_operand<D>(tk, j, lane);
 #pragma unroll
       for (int h = 0; h < kDqHeads; ++h) {
         dQ[h][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kt_op, dshi[h], dQ[h][j], 0, 0, 0);
@@ -316,14 +335,14 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dq_kernel(BwdPar
   }
   __syncthreads();
 
-  float* my = reinterpret_cast<float*>(lds + wave * 8192);
+  float* my = reinterpret_cast<float*>(lds + wave * (16 * D * 4));
 #pragma unroll
   for (int h = 0; h < kDqHeads; ++h) {
     const int head = hh * kDqHeads + h;
     if (head >= p.g) continue;
-    bw_store_tile(my, dQ[h], p.scale, lane, [&](int t) -> float* {
+    bw_store_tile<D>(my, dQ[h], p.scale, lane, [&](int t) -> float* {
       const int rr = r0 + 16 * wave + t;
-      return rr <= r1 ? p.dq + ((off0 + rr) * p.Hq + kvh * p.g + head) * 128 : nullptr;
+      return rr <= r1 ? p.dq + ((off0 + rr) * p.Hq + kvh * p.g + head) * D : nullptr;
     });
   }
 }
@@ -331,7 +350,11 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dq_kernel(BwdPar
 // ---------------------------------------------------------------------------
 // dkv kernel
 // ---------------------------------------------------------------------------
+template <int D>
 __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dkv_kernel(BwdParams p) {
+  using Dm = BwDims<D>;
+  constexpr int ROWB = Dm::ROWB, UPR = Dm::UPR, KS = Dm::KS, NJ = Dm::NJ, kBwTile = Dm::TILE, RPI = Dm::RPI,
+                NLD = Dm::NLD, kBwLds = Dm::LDS;
   __shared__ __attribute__((aligned(1024))) char lds[kBwLds + kBwStatLds];
   // grid: x = (trajectory, KV head), y = key block; the long dense blocks of every trajectory
   // are dispatched before any short one
@@ -413,18 +436,17 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dkv_kernel(BwdPa
   if (wave_last_row < 0) { wave_first_key = rs; wave_last_row = re; }     // no valid key: nothing is skipped (all masked)
 
   // K^T and V^T of the wave's keys as B operands (column n = key, k = head-dim index)
-  bf16x8_t kop[4], vop[4];
+  bf16x8_t kop[KS], vop[KS];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int64_t e = ((off0 + jkey) * p.Hkv + kvh) * 128 + 32 * i + 8 * kb;
+  for (int i = 0; i < KS; ++i) {
+    const int64_t e = ((off0 + jkey) * p.Hkv + kvh) * D + 32 * i + 8 * kb;
     kop[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(p.k + e * 2));
     vop[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(p.v + e * 2));
   }
 
   const int ntile = (re - rs) / kBwBN + 1;     // row tiles per head
   const int NT = ntile * (h_end - h_begin);     // streamed tiles: head-major
-  const int64_t q_row_bytes = (int64_t)p.Hq * 256;
-  const int ld_rr = 4 * wave + (lane >> 4);
+  const int ld_rr = RPI * wave + lane / UPR;
   // tiles are issued in order, so the (head, row tile) pair of the next tile to issue is kept
   // in two counters instead of being recovered by a division
   // Row tiles are streamed from the last row of the range backwards: all dense key blocks of a
@@ -436,11 +458,11 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dkv_kernel(BwdPa
     const int h = issue_h, rt = issue_rt;
     if (--issue_rt < 0) { issue_rt = ntile - 1; ++issue_h; }
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      const int tr = ld_rr + 16 * half;                       // entry of the tile
+    for (int half = 0; half < NLD; ++half) {
+      const int tr = ld_rr + RPI * kBwWaves * half;           // entry of the tile
       const int rr = min(rs + rt * kBwBN + tr, S - 1);
-      const int64_t goff = ((off0 + rr) * p.Hq + kvh * p.g + h) * 256 + (((lane & 15) ^ lds_swz(tr)) << 4);
-      char* dst = lds + stage * (2 * kBwTile) + (wave + 4 * half) * 1024;
+      const int64_t goff = ((off0 + rr) * p.Hq + kvh * p.g + h) * ROWB + (((lane & (UPR - 1)) ^ tile_swz<D>(tr)) << 4);
+      char* dst = lds + stage * (2 * kBwTile) + (wave + kBwWaves * half) * 1024;
       __builtin_amdgcn_global_load_lds((bw_global_void_t*)(p.q + goff), (bw_lds_void_t*)dst, 16, 0, 0);
       __builtin_amdgcn_global_load_lds((bw_global_void_t*)(p.dout + goff),
                                        (bw_lds_void_t*)(dst + kBwTile), 16, 0, 0);
@@ -453,19 +475,18 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dkv_kernel(BwdPa
                                        (bw_lds_void_t*)(lds + kBwLds + stage * 256), 4, 0, 0);
     }
   };
-  (void)q_row_bytes;
   issue_tile(0);
   if (NT > 1) issue_tile(1);
 
-  f32x4_t dK[8], dV[8];
+  f32x4_t dK[NJ], dV[NJ];
 #pragma unroll
-  for (int j = 0; j < 8; ++j) { dK[j] = f32x4_t{0.f, 0.f, 0.f, 0.f}; dV[j] = f32x4_t{0.f, 0.f, 0.f, 0.f}; }
+  for (int j = 0; j < NJ; ++j) { dK[j] = f32x4_t{0.f, 0.f, 0.f, 0.f}; dV[j] = f32x4_t{0.f, 0.f, 0.f, 0.f}; }
 
   int stage = 0, cur_rt = ntile - 1;
   for (int it = 0; it < NT; ++it) {
-    if (it + 1 >= NT) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    else if (wave == 0) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");     // one more load per tile
-    else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    if (it + 1 >= NT) wait_vmcnt<0>();
+    else if (wave == 0) wait_vmcnt<2 * NLD + 1>();     // one more load per tile
+    else wait_vmcnt<2 * NLD>();
     __syncthreads();
     if (it + 2 < NT) issue_tile(stage >= 1 ? stage - 1 : kBwStages - 1);
     const char* tq = lds + stage * (2 * kBwTile);
@@ -511,9 +532,9 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dkv_kernel(BwdPa
       Sx[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
       dPx[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        Sx[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bw_rows_operand(tq, t, i, n, kb), kop[i], Sx[t], 0, 0, 0);
-        dPx[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bw_rows_operand(tdo, t, i, n, kb), vop[i], dPx[t], 0, 0, 0);
+      for (int i = 0; i < KS; ++i) {
+        Sx[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bw_rows_operand<D>(tq, t, i, n, kb), kop[i], Sx[t], 0, 0, 0);
+        dPx[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bw_rows_operand<D>(tdo, t, i, n, kb), vop[i], dPx[t], 0, 0, 0);
       }
     }
     float a[8], ds[8];
@@ -527,11 +548,11 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dkv_kernel(BwdPa
     bw_split(a, ahi, alo, sel);
     bw_split(ds, dshi, dslo, sel);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const bf16x8_t dot = bw_cols_operand(tdo, j, lane);      // dO^T
+    for (int j = 0; j < NJ; ++j) {
+      const bf16x8_t dot = bw_cols_operand<D>(tdo, j, lane);      // dO^T
       dV[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dot, ahi, dV[j], 0, 0, 0);
       dV[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dot, alo, dV[j], 0, 0, 0);
-      const bf16x8_t qt_op = bw_cols_operand(tq, j, lane);     // Q^T
+      const bf16x8_t qt_op = bw_cols_operand<D>(tq, j, lane);     // Q^T
       dK[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qt_op, dshi, dK[j], 0, 0, 0);
       dK[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qt_op, dslo, dK[j], 0, 0, 0);
     }
@@ -539,32 +560,33 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dkv_kernel(BwdPa
   __syncthreads();
 
   // every key row is owned by exactly one lane column of one block: plain stores
-  float* my = reinterpret_cast<float*>(lds + wave * 8192);
+  float* my = reinterpret_cast<float*>(lds + wave * (16 * D * 4));
   // key row and validity of entry t of this wave, taken from the lane that owns it
   auto dst_of = [&](float* base, int t) -> float* {
     const int jk = __shfl(jkey, t, 64);
     const int ok = __shfl((int)key_ok, t, 64);
-    return ok ? base + ((off0 + jk) * p.Hkv + kvh) * 128 : nullptr;
+    return ok ? base + ((off0 + jk) * p.Hkv + kvh) * D : nullptr;
   };
   float* dk_base = p.dk;
   float* dv_base = p.dv;
   if (split >= 0) {
-    const int64_t plane = p.total_rows * p.Hkv * 128;
+    const int64_t plane = p.total_rows * p.Hkv * D;
     dk_base = p.part + (int64_t)(2 * split) * plane;
     dv_base = dk_base + plane;
   }
-  bw_store_tile(my, dK, p.scale, lane, [&](int t) { return dst_of(dk_base, t); });
-  bw_store_tile(my, dV, 1.0f, lane, [&](int t) { return dst_of(dv_base, t); });
+  bw_store_tile<D>(my, dK, p.scale, lane, [&](int t) { return dst_of(dk_base, t); });
+  bw_store_tile<D>(my, dV, 1.0f, lane, [&](int t) { return dst_of(dv_base, t); });
 }
 
 // Sum of the head-split partials of the dense keys (prompt rows and beacons), in split order.
 // One thread per 16 bytes of one (row, KV head); rows that are not dense were written directly.
 __global__ __launch_bounds__(256) void prefill_bwd_reduce_kernel(BwdParams p, int B) {
-  const int64_t units = p.total_rows * p.Hkv * 32;
-  const int64_t plane = p.total_rows * p.Hkv * 128;
+  const int upr = p.D / 4;                       // 16-byte units of one (row, KV head)
+  const int64_t units = p.total_rows * p.Hkv * upr;
+  const int64_t plane = p.total_rows * p.Hkv * p.D;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < units;
        i += (int64_t)gridDim.x * blockDim.x) {
-    const int64_t row = i / (p.Hkv * 32);
+    const int64_t row = i / (p.Hkv * upr);
     int lo = 0, hi = B;                        // largest b with row_off[b] <= row
     while (hi - lo > 1) {
       const int mid = (lo + hi) >> 1;
@@ -596,7 +618,7 @@ extern "C" size_t bc_prefill_bwd_workspace_bytes(const bc_shape* shape, int64_t 
   const int g = shape->Hq / shape->Hkv;
   const int hs = bwd_head_splits(g);
   size_t bytes = (size_t)total_rows * shape->Hq * 2 * sizeof(float);
-  if (hs > 1) bytes += (size_t)hs * 2 * total_rows * shape->Hkv * 128 * sizeof(float);
+  if (hs > 1) bytes += (size_t)hs * 2 * total_rows * shape->Hkv * shape->d * sizeof(float);
   return bytes;
 }
 
@@ -608,7 +630,7 @@ extern "C" int32_t bc_prefill_attn_bwd(const bc_shape* shape, const void* q, con
                                        void* workspace, size_t workspace_bytes, void* stream) {
   int32_t st = check_shape(shape);
   if (st != BC_OK) return st;
-  if (shape->kv_dtype != BC_BF16 || shape->d != 128) return BC_ERR_SHAPE;
+  if (shape->kv_dtype != BC_BF16) return BC_ERR_SHAPE;
   if (!q || !k || !v || !out || !lse || !dout || !row_offsets || !P || !c || !dq || !dk || !dv)
     return BC_ERR_ARG;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(dout) ||
@@ -629,6 +651,7 @@ extern "C" int32_t bc_prefill_attn_bwd(const bc_shape* shape, const void* q, con
   p.part = p.stat + (size_t)total_rows * shape->Hq * 2;
   p.hsplit = bwd_head_splits(shape->Hq / shape->Hkv);
   p.total_rows = total_rows;
+  p.D = shape->d;
   p.Hq = shape->Hq; p.Hkv = shape->Hkv; p.g = shape->Hq / shape->Hkv;
   p.scale = shape->scale;
   p.qscale = shape->scale * kLog2e;
@@ -637,12 +660,17 @@ extern "C" int32_t bc_prefill_attn_bwd(const bc_shape* shape, const void* q, con
   const int nhg = (p.g + kDqHeads - 1) / kDqHeads;
   p.npairs = shape->B * shape->Hkv;
   p.pstride = (p.npairs + 7) & ~7;
-  prefill_bwd_dq_kernel<<<dim3(p.pstride * nhg, tiles), kBwWaves * 64, 0, hs>>>(p);
   // key blocks: at most `tiles` dense-causal blocks + the gathered beacons + `tiles` response blocks
-  prefill_bwd_dkv_kernel<<<dim3(p.pstride, (2 * tiles + 2) * p.hsplit + tiles),
-                           kBwWaves * 64, 0, hs>>>(p);
+  const dim3 dq_grid(p.pstride * nhg, tiles), dkv_grid(p.pstride, (2 * tiles + 2) * p.hsplit + tiles);
+  if (shape->d == 128) {
+    prefill_bwd_dq_kernel<128><<<dq_grid, kBwWaves * 64, 0, hs>>>(p);
+    prefill_bwd_dkv_kernel<128><<<dkv_grid, kBwWaves * 64, 0, hs>>>(p);
+  } else {
+    prefill_bwd_dq_kernel<64><<<dq_grid, kBwWaves * 64, 0, hs>>>(p);
+    prefill_bwd_dkv_kernel<64><<<dkv_grid, kBwWaves * 64, 0, hs>>>(p);
+  }
   if (p.hsplit > 1) {
-    const int64_t blocks = (total_rows * shape->Hkv * 32 + 255) / 256;
+    const int64_t blocks = (total_rows * shape->Hkv * (shape->d / 4) + 255) / 256;
     prefill_bwd_reduce_kernel<<<(int)(blocks < 65536 ? blocks : 65536), 256, 0, hs>>>(p, shape->B);
   }
   return launch_status();

@@ -55,6 +55,18 @@ def test_prefill_small_ragged_all_rows(dev, Hq, Hkv):
         _check_rows(pw, qkv, off, out, lse, b, list(range(int(pw.S[b]))))
 
 
+@pytest.mark.parametrize("Hq,Hkv", [(12, 2), (4, 4), (8, 1), (7, 1), (5, 1), (2, 2)])
+def test_prefill_head_dimension_64_all_rows(dev, Hq, Hkv):
+    # rows of 128 bytes: eight rows per LDS-DMA instruction, two k-steps, four output blocks, the
+    # swizzle of the 8-unit rows; ragged trajectories with and without prompt, several ratios
+    pw = W.PrefillWorkload("pf_d64", 64 + Hq, 4, Hq, Hkv, 64, "bf16", np.array([37, 0, 129, 64], np.int32),
+                           np.array([300, 190, 75, 0], np.int32), np.array([4, 16, 0, 3], np.int32))
+    qkv, off, out, lse = _run(pw, dev)
+    assert np.isfinite(out).all()
+    for b in range(pw.B):
+        _check_rows(pw, qkv, off, out, lse, b, list(range(int(pw.S[b]))))
+
+
 def test_prefill_ratios_and_long_beacon_runs(dev):
     # many beacons (several gathered beacon tiles) and every ratio the paper uses
     pw = W.PrefillWorkload("pf_ratios", 61, 5, 12, 2, 128, "bf16", np.array([3, 40, 128, 7, 256], np.int32),
@@ -97,13 +109,14 @@ def test_config5_full_size(dev):
     print("config5 worst", worst)
 
 
-def test_prefill_rows_equal_decode_over_evicted_cache(dev):
+@pytest.mark.parametrize("d", [128, 64])
+def test_prefill_rows_equal_decode_over_evicted_cache(dev, d):
     # Sec. 3.2: masking simulates eviction.  Feed the same q/k/v through the decode path
     # (append, attend, beacon append at the tail, attend with the beacon's query, evict) and
     # compare every row with the prefill output.
     from paper_2510_13797_amd import bc
     P, c, R = 37, 8, 475
-    pw = W.PrefillWorkload("pf_eq", 62, 2, 12, 2, 128, "bf16", np.full(2, P, np.int32),
+    pw = W.PrefillWorkload("pf_eq", 62, 2, 12, 2, d, "bf16", np.full(2, P, np.int32),
                            np.full(2, R, np.int32), np.full(2, c, np.int32))
     qkv, off, out, _ = _run(pw, dev, want_lse=False)
     S = int(pw.S[0])
@@ -182,6 +195,18 @@ def test_prefill_bwd_small_ragged(dev, Hq, Hkv):
                            np.array([16, 2, 4, 0, 1, 16], np.int32))
     qkv, dos, off, dq, dk, dv = _run_bwd(pw, dev)
     assert np.isfinite(dq).all() and np.isfinite(dk).all() and np.isfinite(dv).all()   # every element written
+    for b in range(pw.B):
+        _check_bwd(pw, qkv, dos, off, dq, dk, dv, b)
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(12, 2), (4, 4), (8, 1), (7, 1), (5, 1)])
+def test_prefill_bwd_head_dimension_64(dev, Hq, Hkv):
+    # the gradients at d = 64: every element of dq, dk, dv of ragged trajectories (head splits of
+    # the dense key blocks and the fixed-order reduction included) against the dense oracle
+    pw = W.PrefillWorkload("pfb_d64", 164 + Hq, 4, Hq, Hkv, 64, "bf16", np.array([37, 0, 129, 64], np.int32),
+                           np.array([300, 190, 75, 0], np.int32), np.array([4, 16, 0, 3], np.int32))
+    qkv, dos, off, dq, dk, dv = _run_bwd(pw, dev)
+    assert np.isfinite(dq).all() and np.isfinite(dk).all() and np.isfinite(dv).all()
     for b in range(pw.B):
         _check_bwd(pw, qkv, dos, off, dq, dk, dv, b)
 

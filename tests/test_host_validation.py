@@ -164,7 +164,8 @@ def test_prefill_entry_points():
     fwd = lambda s, q=PTR, out=PTR, max_rows=64: bc.bc_prefill_attn(s, q, PTR, PTR, PTR, PTR, PTR, max_rows,
                                                                     out, None, None)
     assert fwd(shape(B=1, Hq=4, Hkv=2, d=128, dtype=bc.BC_F32)) == bc.BC_ERR_SHAPE
-    assert fwd(shape(B=1, Hq=4, Hkv=2, d=64, dtype=bc.BC_BF16)) == bc.BC_ERR_SHAPE
+    assert fwd(shape(B=1, Hq=4, Hkv=2, d=64, dtype=bc.BC_F32)) == bc.BC_ERR_SHAPE
+    assert fwd(shape(B=1, Hq=4, Hkv=2, d=64, dtype=bc.BC_BF16), q=None) == bc.BC_ERR_ARG      # (a supported shape)
     assert fwd(ok, q=None) == bc.BC_ERR_ARG
     assert fwd(ok, out=ODD) == bc.BC_ERR_ARG
     assert fwd(ok, max_rows=0) == bc.BC_ERR_ARG
@@ -182,6 +183,9 @@ def test_prefill_entry_points():
         return bc.bc_prefill_attn_bwd(s, PTR, PTR, PTR, PTR, lse, PTR, PTR, PTR, PTR, max_rows, total, dq,
                                       PTR, PTR, ws, ws_bytes, None)
     assert bwd(s=shape(B=1, Hq=4, Hkv=2, d=128, dtype=bc.BC_F32)) == bc.BC_ERR_SHAPE
+    ok64 = shape(B=1, Hq=4, Hkv=2, d=64, dtype=bc.BC_BF16, scale=0.125)
+    assert bwd(s=ok64, dq=None) == bc.BC_ERR_ARG                                             # (a supported shape)
+    assert bc.bc_prefill_bwd_workspace_bytes(ok64, 64) < need                                # partials of D floats per row
     assert bwd(dq=None) == bc.BC_ERR_ARG
     assert bwd(dq=ODD) == bc.BC_ERR_ARG
     assert bwd(lse=None) == bc.BC_ERR_ARG
