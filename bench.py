@@ -113,9 +113,20 @@ def bench_prefill(args):
     ptr = lambda t: C.c_void_p(t.data_ptr())
     stream = torch.cuda.current_stream()
 
+    # default: bc_prefill_attn (weights in two bf16 parts, the form whose output also feeds the
+    # backward); --workspace-prefill: bc_prefill_attn_ws (V copied to half precision by a conversion
+    # pass inside the timed call, weights in one half-precision part when V allows it, as N(0,1) does)
+    use_ws = args.workspace_prefill
+    ws_bytes = int(bc.bc_prefill_workspace_bytes(shape, R)) if use_ws else 0
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+
     def step():
-        st = bc.bc_prefill_attn(shape, ptr(q), ptr(k), ptr(v), ptr(offd), ptr(Pd), ptr(cd), S, ptr(out),
-                                ptr(lse), C.c_void_p(stream.cuda_stream))
+        if use_ws:
+            st = bc.bc_prefill_attn_ws(shape, ptr(q), ptr(k), ptr(v), ptr(offd), ptr(Pd), ptr(cd), S, R, ptr(out),
+                                       ptr(lse), ptr(ws), ws_bytes, C.c_void_p(stream.cuda_stream))
+        else:
+            st = bc.bc_prefill_attn(shape, ptr(q), ptr(k), ptr(v), ptr(offd), ptr(Pd), ptr(cd), S, ptr(out),
+                                    ptr(lse), C.c_void_p(stream.cuda_stream))
         assert st == 0, st
 
     W_ = args.warmup if args.warmup >= 0 else 3
@@ -146,7 +157,10 @@ def bench_prefill(args):
                       # q, k, v read once (bf16), out (fp32) and lse written once
                       "algorithmic_MB": round(hbm_bytes / 1e6, 1),
                       "algorithmic_GBps": round(hbm_bytes / (ms * 1e-3) / 1e9, 1)},
-           "roofline": {"bound": "mfma", "kernel": "bc::prefill_kernel<3>", "achieved": round(tflops, 2),
+           "roofline": {"bound": "mfma",
+                        "kernel": "bc::prefill_kernel<3, 128, %s>" % ("true" if use_ws else "false"),
+                        "entry_point": "bc_prefill_attn_ws (conversion pass included)" if use_ws else "bc_prefill_attn",
+                        "achieved": round(tflops, 2),
                         "peak": 2500.0, "unit": "TFLOP/s", "frac": round(tflops / 2500.0, 4),
                         "traffic": stored_value("prefill_fwd_traffic_bytes")}}
     print(json.dumps(rec))
@@ -803,6 +817,8 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", default="decode",
                     choices=["decode", "ragged256", "long", "prefill", "prefill_bwd", "distill", "copy", "readfloor"])
+    ap.add_argument("--workspace-prefill", action="store_true",
+                    help="prefill workload: time bc_prefill_attn_ws (half-precision value product) instead of bc_prefill_attn")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=-1)
     ap.add_argument("--warmup", type=int, default=-1)

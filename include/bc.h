@@ -285,6 +285,25 @@ int32_t bc_prefill_attn(const bc_shape *shape, const void *q, const void *k, con
                         const int64_t *row_offsets, const int32_t *P, const int32_t *c,
                         int32_t max_rows, float *out, float *lse, void *stream);
 
+/* bc_prefill_attn with a workspace (Fig. 2, Sec. 3.2; same operation, same tensors, same
+ * tolerance).  The workspace (device memory, bc_prefill_workspace_bytes() bytes, 16-byte aligned,
+ * no initialisation, contents unspecified afterwards) receives a copy of V in half precision.
+ * When every finite entry of V is below 65520 in magnitude - which a conversion pass checks on the
+ * device - the softmax weights enter the value product as one half-precision part (11 bits)
+ * against that copy instead of two bf16 parts against V: about a sixth less time.  The copy is exact
+ * for entries of magnitude 2^-14 and above (smaller ones keep an absolute error below 2^-25).
+ * Otherwise the call computes exactly what bc_prefill_attn computes.  The half-precision form stays
+ * inside the forward tolerance (2e-3) but lies further from the exact result than the two-part
+ * form (about 4e-4 against 6e-6 on N(0,1) inputs); gradients computed from its `out` inherit that
+ * error scaled by the size of dO and K, so where bc_prefill_attn_bwd must meet the same absolute
+ * bound whatever the data, take `out` and `lse` from bc_prefill_attn.  total_rows: HOST copy of
+ * row_offsets[B].  Workspace missing or too small: BC_ERR_WORKSPACE. */
+size_t bc_prefill_workspace_bytes(const bc_shape *shape, int64_t total_rows);
+int32_t bc_prefill_attn_ws(const bc_shape *shape, const void *q, const void *k, const void *v,
+                           const int64_t *row_offsets, const int32_t *P, const int32_t *c,
+                           int32_t max_rows, int64_t total_rows, float *out, float *lse,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
 /* Gradients of bc_prefill_attn (Sec. 3.2: the student is trained through the masked forward;
  * gradients flow to its parameters only).  Same tensors and tables as the forward, plus
  * out / lse as the forward wrote them and dout: [total_rows, Hq, d] in bf16.  Results, fp32:

@@ -34,7 +34,8 @@ EXPORTS = [
     "bc_decode_workspace_bytes", "bc_workspace_init", "bc_decode_plan_describe", "bc_decode_attn",
     "bc_compress_evict", "bc_decode_step", "bc_decode_step_noalloc", "bc_beacon_step", "bc_decode_step_budget", "bc_set_ratio",
     "bc_sort_by_length",
-    "bc_prefill_attn", "bc_prefill_bwd_workspace_bytes", "bc_prefill_attn_bwd",
+    "bc_prefill_attn", "bc_prefill_workspace_bytes", "bc_prefill_attn_ws",
+    "bc_prefill_bwd_workspace_bytes", "bc_prefill_attn_bwd",
     "bc_topk_kl_loss", "bc_topk_kl_loss_bwd", "bc_tables_to_host",
 ]
 DIAG_EXPORTS = ["bc_diag_stream_read"]
@@ -107,6 +108,10 @@ def load():
     lib.bc_set_ratio.argtypes = [sp, cp, vp, vp, vp]
     lib.bc_prefill_attn.restype = i32
     lib.bc_prefill_attn.argtypes = [sp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp]
+    lib.bc_prefill_workspace_bytes.restype = C.c_size_t
+    lib.bc_prefill_workspace_bytes.argtypes = [sp, C.c_int64]
+    lib.bc_prefill_attn_ws.restype = i32
+    lib.bc_prefill_attn_ws.argtypes = [sp, vp, vp, vp, vp, vp, vp, i32, C.c_int64, vp, vp, vp, C.c_size_t, vp]
     lib.bc_prefill_bwd_workspace_bytes.restype = sz
     lib.bc_prefill_bwd_workspace_bytes.argtypes = [sp, i64]
     lib.bc_prefill_attn_bwd.restype = i32
@@ -222,6 +227,16 @@ def bc_sort_by_length(shape, cache, active, order, stream):
 
 def bc_set_ratio(shape, cache, new_c, active, stream):
     return load().bc_set_ratio(C.byref(shape), C.byref(cache), new_c, active, stream)
+
+
+def bc_prefill_workspace_bytes(shape, total_rows):
+    return load().bc_prefill_workspace_bytes(C.byref(shape), total_rows)
+
+
+def bc_prefill_attn_ws(shape, q, k, v, row_offsets, P, c, max_rows, total_rows, out, lse, workspace,
+                       workspace_bytes, stream):
+    return load().bc_prefill_attn_ws(C.byref(shape), q, k, v, row_offsets, P, c, max_rows, total_rows, out,
+                                     lse, workspace, workspace_bytes, stream)
 
 
 def bc_prefill_attn(shape, q, k, v, row_offsets, P, c, max_rows, out, lse, stream):
@@ -488,8 +503,8 @@ class Runtime:
         return out[0], out[1]
 
 
-def prefill_attn(q, k, v, row_offsets, P, c, Hq, Hkv, d, scale, want_lse=True):
-    """bc_prefill_attn on device tensors.
+def prefill_attn(q, k, v, row_offsets, P, c, Hq, Hkv, d, scale, want_lse=True, workspace=False):
+    """bc_prefill_attn (or, workspace=True, bc_prefill_attn_ws) on device tensors.
 
     q [R, Hq, d], k, v [R, Hkv, d] bf16 device tensors (trajectories concatenated);
     row_offsets [B+1] int64, P, c [B] int32 (host arrays).  Returns (out fp32 [R,Hq,d], lse or None).
@@ -507,9 +522,15 @@ def prefill_attn(q, k, v, row_offsets, P, c, Hq, Hkv, d, scale, want_lse=True):
     out = torch.empty(R, Hq, d, dtype=torch.float32, device=dev)
     lse = torch.empty(R, Hq, dtype=torch.float32, device=dev) if want_lse else None
     max_rows = int(np.diff(row_offsets).max())
-    _check(bc_prefill_attn(shape, _ptr(q), _ptr(k), _ptr(v), _ptr(offd), _ptr(Pd), _ptr(cd), max_rows,
-                           _ptr(out), _ptr(lse), _stream_ptr()))
-    torch.cuda.current_stream().synchronize()      # offd/Pd/cd may be freed after this
+    if workspace:
+        nbytes = int(bc_prefill_workspace_bytes(shape, R))
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        _check(bc_prefill_attn_ws(shape, _ptr(q), _ptr(k), _ptr(v), _ptr(offd), _ptr(Pd), _ptr(cd), max_rows, R,
+                                  _ptr(out), _ptr(lse), _ptr(ws), nbytes, _stream_ptr()))
+    else:
+        _check(bc_prefill_attn(shape, _ptr(q), _ptr(k), _ptr(v), _ptr(offd), _ptr(Pd), _ptr(cd), max_rows,
+                               _ptr(out), _ptr(lse), _stream_ptr()))
+    torch.cuda.current_stream().synchronize()      # offd/Pd/cd (and the workspace) may be freed after this
     return out, lse
 
 

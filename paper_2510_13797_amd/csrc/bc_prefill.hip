@@ -36,11 +36,15 @@ typedef __attribute__((ext_vector_type(4))) short pf_s16x4_t;
 typedef __attribute__((ext_vector_type(8))) short pf_s16x8_t;
 typedef __attribute__((address_space(3))) pf_s16x4_t pf_lds_s16x4_t;
 typedef __attribute__((ext_vector_type(2))) float pf_f32x2_t;
+typedef __attribute__((ext_vector_type(2))) _Float16 pf_f16x2_t;
+typedef __attribute__((ext_vector_type(8))) _Float16 pf_f16x8_t;
 
 struct PrefillParams {
   const char* q;
   const char* k;
   const char* v;
+  const char* v16;         // V rounded to half precision, same layout (workspace form only)
+  const int32_t* flag;     // workspace form: 0 = every V entry fits half precision, 1 = not; else NULL
   const int64_t* row_off;
   const int32_t* P;
   const int32_t* c;
@@ -63,8 +67,14 @@ constexpr float kPfLazy = 5.0f;
 // dimension, 128 or 64 (rows of 256 or 128 bytes: 16 or 8 units of 16 bytes, four or eight rows
 // per 1 KB LDS-DMA instruction, four or two 32-wide steps of the score product, eight or four
 // 16-column blocks of the output).
-template <int HPW, int D>
+// HALF: the weights enter the value product as one half-precision part (11 bits) against V in
+// half precision, instead of two bf16 parts against V in bf16: a third fewer matrix instructions
+// and no split.  V's copy in half precision is exact for entries between 2^-14 and 65504 in
+// magnitude (bf16 has fewer mantissa bits), which a conversion pass checks; both forms of the
+// kernel are launched and each leaves at once when the pass's verdict is for the other.
+template <int HPW, int D, bool HALF>
 __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams p) {
+  if (p.flag != nullptr && (p.flag[0] != 0) == HALF) return;
   constexpr int ROWB = D * 2;                 // bytes of a K or V row
   constexpr int UPR = ROWB / 16;              // 16-byte units per row
   constexpr int KS = D / 32;                  // k-steps of the score product
@@ -108,7 +118,7 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
   const HalfSelectors sel = half_selectors();
   const int64_t kv_row_bytes = (int64_t)p.Hkv * ROWB;
   const char* kbase = p.k + (off0 * p.Hkv + kvh) * ROWB;
-  const char* vbase = p.v + (off0 * p.Hkv + kvh) * ROWB;
+  const char* vbase = (HALF ? p.v16 : p.v) + (off0 * p.Hkv + kvh) * ROWB;
 
   // Key tile kt covers 32 consecutive entries of one run.  Entry rr is row j0 + rr*step;
   // entries at and beyond nvalid do not exist (their loads are redirected to row r1).
@@ -167,10 +177,18 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
 
   f32x4_t O[HPW][NJ];
   float m_run[HPW], l_run[HPW], grow_at[HPW];
+  // HALF: the denominators are summed by the matrix cores from the same rounded weights that
+  // enter the value product (a row of ones as the other operand), so that numerator and
+  // denominator carry the same rounding: what is left of it in o is second order, and a row
+  // with one dominant key is as exact as in the two-part form.
+  f32x4_t Lacc[HPW];
+  const pf_f16x8_t ones = {(_Float16)1.f, (_Float16)1.f, (_Float16)1.f, (_Float16)1.f,
+                           (_Float16)1.f, (_Float16)1.f, (_Float16)1.f, (_Float16)1.f};
   const float inv_qscale = 1.0f / p.qscale;
 #pragma unroll
   for (int h = 0; h < HPW; ++h) {
     m_run[h] = kNegBig; l_run[h] = 0.f; grow_at[h] = (kNegBig + kPfLazy) * inv_qscale;
+    Lacc[h] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int j = 0; j < NJ; ++j) O[h][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
   }
@@ -254,6 +272,7 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
         m_run[h] = m_new;
         grow_at[h] = (m_new + kPfLazy) * inv_qscale;
         l_run[h] *= alpha;
+        if constexpr (HALF) Lacc[h] *= alpha;
 #pragma unroll
         for (int j = 0; j < NJ; ++j) O[h][j] *= alpha;
       }
@@ -271,13 +290,21 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
       uint32_t hi[4], lo[4];
 #pragma unroll
       for (int e = 0; e < 8; e += 2) {
-        const uint32_t hp = pack_bf16(pe[e], pe[e + 1]);
-        hi[e >> 1] = hp;
-        lo[e >> 1] = pack_bf16(minus_half(pe[e], hp, sel.low), minus_half(pe[e + 1], hp, sel.high));
+        if constexpr (HALF) {
+          hi[e >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pf_f32x2_t{pe[e], pe[e + 1]}, pf_f16x2_t));
+          lo[e >> 1] = 0u;
+        } else {
+          const uint32_t hp = pack_bf16(pe[e], pe[e + 1]);
+          hi[e >> 1] = hp;
+          lo[e >> 1] = pack_bf16(minus_half(pe[e], hp, sel.low), minus_half(pe[e + 1], hp, sel.high));
+        }
       }
-      l_run[h] += psum;
       phi[h] = __builtin_bit_cast(bf16x8_t, make_uint4(hi[0], hi[1], hi[2], hi[3]));
       plo[h] = __builtin_bit_cast(bf16x8_t, make_uint4(lo[0], lo[1], lo[2], lo[3]));
+      if constexpr (HALF)
+        Lacc[h] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ones, __builtin_bit_cast(pf_f16x8_t, phi[h]), Lacc[h], 0, 0, 0);
+      else
+        l_run[h] += psum;
     }
     // O^T += V^T . P^T ; V^T through the transposing LDS read
     {
@@ -295,8 +322,13 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
             bf16x8_t, (pf_s16x8_t)__builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7));
 #pragma unroll
         for (int h = 0; h < HPW; ++h) {
-          O[h][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, phi[h], O[h][j], 0, 0, 0);
-          O[h][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, plo[h], O[h][j], 0, 0, 0);
+          if constexpr (HALF) {
+            O[h][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(pf_f16x8_t, av),
+                                                             __builtin_bit_cast(pf_f16x8_t, phi[h]), O[h][j], 0, 0, 0);
+          } else {
+            O[h][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, phi[h], O[h][j], 0, 0, 0);
+            O[h][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, plo[h], O[h][j], 0, 0, 0);
+          }
         }
       }
     }
@@ -327,8 +359,9 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
 #pragma unroll
   for (int h = 0; h < HPW; ++h) {
     const int head = hh * HPW + h;
-    float l = l_run[h];
-    l = rows_allreduce_sum(l);
+    float l;
+    if constexpr (HALF) l = Lacc[h][0];            // (already the sum over all keys of the lane's row)
+    else l = rows_allreduce_sum(l_run[h]);
     const float inv = 1.0f / l;
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
@@ -352,25 +385,56 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_kernel(PrefillParams
   }
 }
 
-}  // namespace bc
+// V in half precision for the workspace form: 8 entries per thread and pass; the verdict word is
+// set when a finite entry does not fit (65520 and beyond rounds to infinity).
+__global__ __launch_bounds__(256) void prefill_v16_kernel(const uint4* __restrict__ v, uint4* __restrict__ v16,
+                                                          int64_t units, int32_t* flag) {
+  bool over = false;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < units; i += (int64_t)gridDim.x * blockDim.x) {
+    float f[8];
+    unpack16(v[i], f, bf16_t{});
+    uint32_t h[4];
+#pragma unroll
+    for (int e = 0; e < 8; e += 2) {
+      over = over || (fabsf(f[e]) >= 65520.f && fabsf(f[e]) < __builtin_inff()) ||
+             (fabsf(f[e + 1]) >= 65520.f && fabsf(f[e + 1]) < __builtin_inff());
+      h[e >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pf_f32x2_t{f[e], f[e + 1]}, pf_f16x2_t));
+    }
+    v16[i] = make_uint4(h[0], h[1], h[2], h[3]);
+  }
+  if (__any(over) && (threadIdx.x & 63) == 0) atomicOr(flag, 1);
+}
+__global__ void prefill_clear_flag_kernel(int32_t* flag) { flag[0] = 0; }
 
-using namespace bc;
+constexpr size_t kPfFlagBytes = 256;
 
-extern "C" int32_t bc_prefill_attn(const bc_shape* shape, const void* q, const void* k,
-                                   const void* v, const int64_t* row_offsets, const int32_t* P,
-                                   const int32_t* c, int32_t max_rows, float* out, float* lse,
-                                   void* stream) {
-  int32_t st = check_shape(shape);
-  if (st != BC_OK) return st;
-  if (shape->kv_dtype != BC_BF16) return BC_ERR_SHAPE;
-  if (!q || !k || !v || !row_offsets || !P || !c || !out) return BC_ERR_ARG;
-  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return BC_ERR_ARG;
-  if (max_rows < 1 || max_rows >= (1 << 26)) return BC_ERR_ARG;
-  if (!positive_finite(shape->scale)) return BC_ERR_ARG;       // the kernel takes maxima of unscaled scores
+template <bool HALF>
+static void launch_prefill(const PrefillParams& p, int d, int hpw, dim3 grid, hipStream_t hs) {
+  if (d == 128) {
+    switch (hpw) {
+      case 1: prefill_kernel<1, 128, HALF><<<grid, kPfWaves * 64, 0, hs>>>(p); break;
+      case 2: prefill_kernel<2, 128, HALF><<<grid, kPfWaves * 64, 0, hs>>>(p); break;
+      default: prefill_kernel<3, 128, HALF><<<grid, kPfWaves * 64, 0, hs>>>(p); break;
+    }
+  } else {
+    switch (hpw) {
+      case 1: prefill_kernel<1, 64, HALF><<<grid, kPfWaves * 64, 0, hs>>>(p); break;
+      case 2: prefill_kernel<2, 64, HALF><<<grid, kPfWaves * 64, 0, hs>>>(p); break;
+      default: prefill_kernel<3, 64, HALF><<<grid, kPfWaves * 64, 0, hs>>>(p); break;
+    }
+  }
+}
+
+// Shared by the two entry points.  workspace == nullptr: the two-part form alone.
+static int32_t prefill_forward(const bc_shape* shape, const void* q, const void* k, const void* v,
+                               const int64_t* row_offsets, const int32_t* P, const int32_t* c,
+                               int32_t max_rows, int64_t total_rows, float* out, float* lse,
+                               void* workspace, void* stream) {
   PrefillParams p;
   p.q = static_cast<const char*>(q);
   p.k = static_cast<const char*>(k);
   p.v = static_cast<const char*>(v);
+  p.v16 = nullptr; p.flag = nullptr;
   p.row_off = row_offsets; p.P = P; p.c = c;
   p.out = out; p.lse = lse;
   p.Hq = shape->Hq; p.Hkv = shape->Hkv; p.g = shape->Hq / shape->Hkv;
@@ -383,18 +447,57 @@ extern "C" int32_t bc_prefill_attn(const bc_shape* shape, const void* q, const v
   p.pstride = (p.npairs + 7) & ~7;
   const dim3 grid(p.hsplit * p.pstride, (max_rows + kPfBM - 1) / kPfBM);
   hipStream_t hs = as_stream(stream);
-  if (shape->d == 128) {
-    switch (hpw) {
-      case 1: prefill_kernel<1, 128><<<grid, kPfWaves * 64, 0, hs>>>(p); break;
-      case 2: prefill_kernel<2, 128><<<grid, kPfWaves * 64, 0, hs>>>(p); break;
-      default: prefill_kernel<3, 128><<<grid, kPfWaves * 64, 0, hs>>>(p); break;
-    }
-  } else {
-    switch (hpw) {
-      case 1: prefill_kernel<1, 64><<<grid, kPfWaves * 64, 0, hs>>>(p); break;
-      case 2: prefill_kernel<2, 64><<<grid, kPfWaves * 64, 0, hs>>>(p); break;
-      default: prefill_kernel<3, 64><<<grid, kPfWaves * 64, 0, hs>>>(p); break;
-    }
+  if (workspace) {
+    int32_t* flag = static_cast<int32_t*>(workspace);
+    char* v16 = static_cast<char*>(workspace) + kPfFlagBytes;
+    const int64_t units = total_rows * shape->Hkv * shape->d / 8;
+    const int64_t blocks = (units + 255) / 256;
+    prefill_clear_flag_kernel<<<1, 1, 0, hs>>>(flag);
+    prefill_v16_kernel<<<(int)(blocks < 4096 ? blocks : 4096), 256, 0, hs>>>(
+        static_cast<const uint4*>(v), reinterpret_cast<uint4*>(v16), units, flag);
+    p.v16 = v16; p.flag = flag;
+    launch_prefill<true>(p, shape->d, hpw, grid, hs);
   }
+  launch_prefill<false>(p, shape->d, hpw, grid, hs);
   return launch_status();
+}
+
+}  // namespace bc
+
+using namespace bc;
+
+extern "C" size_t bc_prefill_workspace_bytes(const bc_shape* shape, int64_t total_rows) {
+  if (check_shape(shape) != BC_OK || total_rows < 1) return 0;
+  return kPfFlagBytes + (size_t)total_rows * shape->Hkv * shape->d * 2;
+}
+
+extern "C" int32_t bc_prefill_attn_ws(const bc_shape* shape, const void* q, const void* k,
+                                      const void* v, const int64_t* row_offsets, const int32_t* P,
+                                      const int32_t* c, int32_t max_rows, int64_t total_rows,
+                                      float* out, float* lse, void* workspace,
+                                      size_t workspace_bytes, void* stream) {
+  int32_t st = check_shape(shape);
+  if (st != BC_OK) return st;
+  if (shape->kv_dtype != BC_BF16) return BC_ERR_SHAPE;
+  if (!q || !k || !v || !row_offsets || !P || !c || !out) return BC_ERR_ARG;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return BC_ERR_ARG;
+  if (max_rows < 1 || max_rows >= (1 << 26) || total_rows < max_rows) return BC_ERR_ARG;
+  if (!positive_finite(shape->scale)) return BC_ERR_ARG;
+  if (!workspace || !aligned16(workspace) || workspace_bytes < bc_prefill_workspace_bytes(shape, total_rows))
+    return BC_ERR_WORKSPACE;
+  return prefill_forward(shape, q, k, v, row_offsets, P, c, max_rows, total_rows, out, lse, workspace, stream);
+}
+
+extern "C" int32_t bc_prefill_attn(const bc_shape* shape, const void* q, const void* k,
+                                   const void* v, const int64_t* row_offsets, const int32_t* P,
+                                   const int32_t* c, int32_t max_rows, float* out, float* lse,
+                                   void* stream) {
+  int32_t st = check_shape(shape);
+  if (st != BC_OK) return st;
+  if (shape->kv_dtype != BC_BF16) return BC_ERR_SHAPE;
+  if (!q || !k || !v || !row_offsets || !P || !c || !out) return BC_ERR_ARG;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return BC_ERR_ARG;
+  if (max_rows < 1 || max_rows >= (1 << 26)) return BC_ERR_ARG;
+  if (!positive_finite(shape->scale)) return BC_ERR_ARG;       // the kernel takes maxima of unscaled scores
+  return prefill_forward(shape, q, k, v, row_offsets, P, c, max_rows, 0, out, lse, nullptr, stream);
 }

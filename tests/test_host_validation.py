@@ -174,6 +174,18 @@ def test_prefill_entry_points():
     for bad in (float("nan"), float("inf"), -1.0):
         assert fwd(shape(B=1, Hq=4, Hkv=2, d=128, dtype=bc.BC_BF16, scale=bad)) == bc.BC_ERR_ARG
 
+    # the workspace form of the forward: the same checks, plus its workspace
+    wsneed = bc.bc_prefill_workspace_bytes(ok, 64)
+    assert wsneed == 256 + 64 * 2 * 128 * 2 and bc.bc_prefill_workspace_bytes(ok, 0) == 0
+    fws = lambda s=ok, q=PTR, max_rows=64, total=64, ws=PTR, nbytes=1 << 40: bc.bc_prefill_attn_ws(
+        s, q, PTR, PTR, PTR, PTR, PTR, max_rows, total, PTR, None, ws, nbytes, None)
+    assert fws(s=shape(B=1, Hq=4, Hkv=2, d=128, dtype=bc.BC_F32)) == bc.BC_ERR_SHAPE
+    assert fws(q=None) == bc.BC_ERR_ARG
+    assert fws(max_rows=65, total=64) == bc.BC_ERR_ARG
+    assert fws(ws=None) == bc.BC_ERR_WORKSPACE
+    assert fws(ws=ODD) == bc.BC_ERR_WORKSPACE
+    assert fws(nbytes=wsneed - 1) == bc.BC_ERR_WORKSPACE
+
     need = bc.bc_prefill_bwd_workspace_bytes(ok, 64)
     assert need > 0
     assert bc.bc_prefill_bwd_workspace_bytes(ok, 0) == 0
