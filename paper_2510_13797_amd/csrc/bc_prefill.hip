@@ -13,12 +13,14 @@
 //
 // One workgroup = 64 query rows x up to three query heads of one KV head, 4 waves of 16 rows
 // each; two workgroups share a CU (matrix and vector instructions of one SIMD overlap only
-// partly on this chip, so the tile body is bound by the sum of the two).  K/V tiles of 32 keys are gathered from HBM into LDS by
-// 16-byte LDS-DMA loads (3-stage ring, one barrier per tile, each row 256 contiguous bytes), shared by the 4
-// waves and fed to 16x16x32 bf16 MFMA: S^T = K.Q^T, O^T += V^T.P^T with P split into two
-// bf16 parts so that the softmax weights keep about 16 bits.  Softmax runs online in
-// registers in the accumulator layout.  The output tile goes through LDS so that every
-// row of 512 bytes is written to HBM as one burst.
+// partly on this chip, so the tile body is bound by the sum of the two).  K/V tiles of 32 keys
+// are gathered from HBM into LDS by 16-byte LDS-DMA loads (3-stage ring, one barrier per tile,
+// each row d * 2 contiguous bytes), shared by the 4 waves and fed to 16x16x32 MFMA: S^T = K.Q^T
+// in bf16, O^T += V^T.P^T with P split into two bf16 parts so that the softmax weights keep
+// about 16 bits (or, in the workspace form, as one half-precision part against a half-precision
+// copy of V).  Softmax runs online in registers in the accumulator layout.  The output tile
+// goes through LDS so that every row of d floats is written to HBM as one burst.  Head
+// dimension 128 or 64 (a template parameter).
 #include <type_traits>
 
 #include "bc_common.h"
