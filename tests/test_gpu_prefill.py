@@ -23,14 +23,11 @@ def dev():
 FORM = {"workspace": False}
 
 
-@pytest.fixture(autouse=True, params=["plain", "workspace"])
-def _entry_point(request):
-    name = request.function.__name__
-    if request.param == "workspace" and ("_bwd_" in name or name.endswith("_bwd_full_size") or "two_part_form" in name
-                                         or "argument_errors" in name or "half_form" in name):
-        pytest.skip("the test does not go through the forward entry points' two forms")
+@pytest.fixture(params=["plain", "workspace"])
+def form(request):
+    """Which forward entry point _run() goes through."""
     FORM["workspace"] = request.param == "workspace"
-    yield
+    yield request.param
     FORM["workspace"] = False
 
 
@@ -61,7 +58,7 @@ def _check_rows(pw, qkv, off, out, lse, b, rows):
 
 
 @pytest.mark.parametrize("Hq,Hkv", [(12, 2), (4, 1), (8, 8), (2, 2), (7, 1), (8, 1), (5, 1), (3, 1), (4, 2)])
-def test_prefill_small_ragged_all_rows(dev, Hq, Hkv):
+def test_prefill_small_ragged_all_rows(dev, Hq, Hkv, form):
     pw = W.PrefillWorkload("pf_small", 50 + Hq, 6, Hq, Hkv, 128, "bf16",
                            np.array([0, 5, 64, 70, 33, 200], np.int32),      # prompt rows
                            np.array([150, 64, 1, 130, 97, 0], np.int32),     # response tokens
@@ -73,7 +70,7 @@ def test_prefill_small_ragged_all_rows(dev, Hq, Hkv):
 
 
 @pytest.mark.parametrize("Hq,Hkv", [(12, 2), (4, 4), (8, 1), (7, 1), (5, 1), (2, 2)])
-def test_prefill_head_dimension_64_all_rows(dev, Hq, Hkv):
+def test_prefill_head_dimension_64_all_rows(dev, Hq, Hkv, form):
     # rows of 128 bytes: eight rows per LDS-DMA instruction, two k-steps, four output blocks, the
     # swizzle of the 8-unit rows; ragged trajectories with and without prompt, several ratios
     pw = W.PrefillWorkload("pf_d64", 64 + Hq, 4, Hq, Hkv, 64, "bf16", np.array([37, 0, 129, 64], np.int32),
@@ -84,7 +81,7 @@ def test_prefill_head_dimension_64_all_rows(dev, Hq, Hkv):
         _check_rows(pw, qkv, off, out, lse, b, list(range(int(pw.S[b]))))
 
 
-def test_prefill_ratios_and_long_beacon_runs(dev):
+def test_prefill_ratios_and_long_beacon_runs(dev, form):
     # many beacons (several gathered beacon tiles) and every ratio the paper uses
     pw = W.PrefillWorkload("pf_ratios", 61, 5, 12, 2, 128, "bf16", np.array([3, 40, 128, 7, 256], np.int32),
                            np.array([700, 900, 1000, 1100, 1200], np.int32),
@@ -98,7 +95,7 @@ def test_prefill_ratios_and_long_beacon_runs(dev):
         _check_rows(pw, qkv, off, out, lse, b, rows)
 
 
-def test_config5_full_size(dev):
+def test_config5_full_size(dev, form):
     pw = W.prefill_train()
     assert int(pw.S[0]) == 8688
     qkv, off, out, lse = _run(pw, dev)
@@ -127,7 +124,7 @@ def test_config5_full_size(dev):
 
 
 @pytest.mark.parametrize("d", [128, 64])
-def test_prefill_rows_equal_decode_over_evicted_cache(dev, d):
+def test_prefill_rows_equal_decode_over_evicted_cache(dev, d, form):
     # Sec. 3.2: masking simulates eviction.  Feed the same q/k/v through the decode path
     # (append, attend, beacon append at the tail, attend with the beacon's query, evict) and
     # compare every row with the prefill output.
@@ -251,7 +248,7 @@ def test_config5_bwd_full_size(dev):
 
 
 @pytest.mark.parametrize("case", range(8))
-def test_prefill_randomised_forward_and_backward(dev, case):
+def test_prefill_randomised_forward_and_backward(dev, case, form):
     # seeded random trajectory counts, prompt and response lengths, ratios and head layouts;
     # every row of the forward and every gradient element against the oracle
     rng = np.random.default_rng([20251013, 78, case])
@@ -272,7 +269,7 @@ def test_prefill_randomised_forward_and_backward(dev, case):
         _check_bwd(pw, qkv, dos, off, dq, dk, dv, b)
 
 
-def test_prefill_long_trajectory(dev):
+def test_prefill_long_trajectory(dev, form):
     # a 32k-token response (the longest generation the paper's setups allow) in one trajectory:
     # 2,048 beacons, 64 gathered beacon tiles per late query tile; sampled rows against the oracle
     pw = W.PrefillWorkload("pf_long", 64, 1, 12, 2, 128, "bf16", np.array([512], np.int32),
@@ -306,7 +303,7 @@ class _PeakedKeys:
         return q, k, v
 
 
-def test_prefill_peaked_keys_forward_and_backward(dev):
+def test_prefill_peaked_keys_forward_and_backward(dev, form):
     pw = _PeakedKeys(W.PrefillWorkload("pf_peak", 65, 3, 12, 2, 128, "bf16", np.array([5, 100, 256], np.int32),
                                        np.array([600, 900, 300], np.int32), np.array([16, 4, 0], np.int32)))
     qkv, off, out, lse = _run(pw, dev)
@@ -319,7 +316,7 @@ def test_prefill_peaked_keys_forward_and_backward(dev):
         _check_bwd(pw, qkv, dos, off, dq, dk, dv, b)
 
 
-def test_prefill_ratio_whose_window_index_needs_more_than_32_bits(dev):
+def test_prefill_ratio_whose_window_index_needs_more_than_32_bits(dev, form):
     # c = 65535: rows * (c + 1) passes 2^32 inside the third window, where a multiply-high
     # estimate of offset / (c + 1) is one too large unless it is corrected (offset 131071, the
     # second beacon, is the first such place).  Forward rows and gradients around both beacons
