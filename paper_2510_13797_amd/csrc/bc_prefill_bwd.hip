@@ -297,24 +297,34 @@ __global__ __launch_bounds__(kBwWaves * 64, 2) void prefill_bwd_dq_kernel(BwdPar
     }
 
     bf16x8_t dshi[kDqHeads], dslo[kDqHeads];
+    // scores and dA of both heads first: the K and V operands are read once, and the eight
+    // accumulation chains are independent
+    f32x4_t Sx[kDqHeads][2], dPx[kDqHeads][2];
 #pragma unroll
-    for (int h = 0; h < kDqHeads; ++h) {
-      f32x4_t Sx[2], dPx[2];
+    for (int h = 0; h < kDqHeads; ++h)
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
-        Sx[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-        dPx[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        Sx[h][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        dPx[h][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+      }
 #pragma unroll
-        for (int i = 0; i < KS; ++i) {
-          Sx[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bw_rows_operand<D>(tk, t, i, n, kb), qb[h][i], Sx[t], 0, 0, 0);
-          dPx[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bw_rows_operand<D>(tv, t, i, n, kb), dob[h][i], dPx[t], 0, 0, 0);
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int i = 0; i < KS; ++i) {
+        const bf16x8_t ka = bw_rows_operand<D>(tk, t, i, n, kb), va = bw_rows_operand<D>(tv, t, i, n, kb);
+#pragma unroll
+        for (int h = 0; h < kDqHeads; ++h) {
+          Sx[h][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qb[h][i], Sx[h][t], 0, 0, 0);
+          dPx[h][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, dob[h][i], dPx[h][t], 0, 0, 0);
         }
       }
+#pragma unroll
+    for (int h = 0; h < kDqHeads; ++h) {
       float ds[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        const float a = fast_exp2(fmaf(Sx[e >> 2][e & 3], p.qscale, -lse2[h]));
-        ds[e] = a * (dPx[e >> 2][e & 3] - delta[h]);
+        const float a = fast_exp2(fmaf(Sx[h][e >> 2][e & 3], p.qscale, -lse2[h]));
+        ds[e] = a * (dPx[h][e >> 2][e & 3] - delta[h]);
       }
       if (MASKED) {
 #pragma unroll
